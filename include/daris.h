@@ -1,0 +1,234 @@
+/*
+ * daris.h -- C ABI of the MI355X DARIS hot path.
+ *
+ * DARIS (Sec. III-IV of the paper) runs several periodic, two-priority DNN inference tasks concurrently on
+ * partitions ("contexts") of one GPU.  A task's DNN is cut into sequential stages; a synchronisation point
+ * at every stage boundary is the only preemption / migration point (Sec. III-B1).  Here a partition is a set
+ * of compute units: a CU mask plus N_s CU-masked HIP streams; the sum of partition sizes may exceed the 256
+ * CUs of the device (oversubscription, Sec. III-C2).
+ *
+ * General rules
+ *   - Every function returns a status (0 = DARIS_OK, negative = error) or a non-negative handle; nothing
+ *     throws or aborts.  daris_last_error() gives the text of the calling thread's last failure.
+ *   - All calls come from one API thread.  The library runs one internal scheduler thread in real-time mode.
+ *   - "host" pointers are ordinary CPU memory, read during the call only (the library copies what it keeps).
+ *     "device" pointers are HIP device memory owned by the caller, which must stay valid until the job that
+ *     uses them has completed (daris_run_until_idle() or the blocking run calls return).
+ *   - Times are int64 nanoseconds.  In virtual-time mode they are positions on the library's virtual clock;
+ *     in real-time mode they count from the library's epoch (set by daris_commit()).
+ *   - Utilisations (eq. 3-7) are evaluated in Q32 fixed point: u = floor(mret * 2^32 / T).
+ */
+#ifndef DARIS_H
+#define DARIS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t daris_status;
+typedef int32_t daris_part; /* partition handle: 0,1,2,... in creation order; <0 is an error code */
+typedef int32_t daris_task; /* task handle:      0,1,2,... in registration order; <0 is an error code */
+
+enum {
+  DARIS_OK = 0,
+  DARIS_EINVAL = -1, /* bad argument / unsupported layer shape */
+  DARIS_ENOMEM = -2, /* host or device allocation failed */
+  DARIS_EHIP = -3,   /* a HIP runtime call failed (text in daris_last_error) */
+  DARIS_ESTATE = -4, /* call not allowed in the current state (e.g. not initialised, already committed) */
+  DARIS_ERANGE = -5  /* handle or index out of range */
+};
+
+/* daris_init flags */
+enum {
+  DARIS_VIRTUAL_TIME = 1,     /* decisions run on a virtual clock fed by daris_set_virtual_time tables        */
+  DARIS_NO_DEVICE = 2,        /* host logic only: no HIP call is made, no kernel runs (needs VIRTUAL_TIME)     */
+  DARIS_NO_LAST = 4,          /* ablation (Sec. VI, "No Last"): last stages get no extra level                 */
+  DARIS_NO_PRIOR = 8,         /* ablation ("No Prior"): a missed predecessor gives no extra level              */
+  DARIS_NO_FIXED = 16,        /* ablation ("No Fixed"): all stages share one level, EDF only                   */
+  DARIS_HP_ADMISSION = 32,    /* Overload+HPA (Sec. VI-I): HP jobs must pass the test in their own context     */
+  DARIS_KEEP_ACTIVATIONS = 64 /* debugging: one buffer per layer output so daris_read_layer works              */
+};
+
+enum { DARIS_LP = 0, DARIS_HP = 1 };
+enum { DARIS_FP32 = 0, DARIS_BF16 = 1 };
+enum { DARIS_OP_CONV = 0, DARIS_OP_MAXPOOL = 1, DARIS_OP_GAVGPOOL = 2, DARIS_OP_FC = 3 };
+enum { DARIS_ACT_NONE = 0, DARIS_ACT_RELU = 1, DARIS_ACT_RELU6 = 2 };
+
+/* Outcome of daris_release_job (Sec. IV-B1). */
+enum {
+  DARIS_ACCEPTED = 1,         /* admitted in the task's current partition                                      */
+  DARIS_MIGRATED = 2,         /* admitted after migration to another partition (LP only)                       */
+  DARIS_REJECT_ADMISSION = 3, /* failed eq. (11) in every partition                                            */
+  DARIS_REJECT_OVERRUN = 4,   /* LP: the task's previous job is still active                                   */
+  DARIS_QUEUED = 5            /* HP: waits behind the task's previous job, starts when it ends                 */
+};
+
+/*
+ * One layer of a DNN.  Layer l reads the output of layer in_from (-1 = the network input) and, if
+ * res_from >= 0, adds the output of layer res_from (same shape as its own output) before the activation.
+ *   CONV     : cross-correlation, zero padding, groups == 1 (dense) or groups == c_in == c_out (depthwise);
+ *              w = host float[c_out][c_in/groups][k][k], b = host float[c_out] or NULL.  BN must already be
+ *              folded into (w, b).  c_in and c_out must be multiples of 4 (8 for bf16 tasks) except that the
+ *              network input may have 1..4 channels.
+ *   MAXPOOL  : k x k window, padding acts as -inf.  w, b unused.
+ *   GAVGPOOL : mean over all pixels.  w, b unused.
+ *   FC       : w = host float[c_out][c_in], c_in = C*H*W of the producing tensor flattened in (c, y, x)
+ *              order; b as for CONV.
+ */
+typedef struct daris_layer {
+  int32_t op;
+  int32_t c_in, c_out;
+  int32_t k, stride, pad;
+  int32_t groups;
+  int32_t act;
+  int32_t in_from;
+  int32_t res_from;
+  const float* w;
+  const float* b;
+} daris_layer;
+
+/* A DNN: input tensor (c, h, w), fp32 NCHW in caller memory; arithmetic type of the task. */
+typedef struct daris_dnn {
+  int32_t n_layers;
+  int32_t in_c, in_h, in_w;
+  int32_t dtype; /* DARIS_FP32: fp32 storage, fp32 MFMA.  DARIS_BF16: bf16 weights/activations, fp32 accumulate */
+  const daris_layer* layers;
+} daris_dnn;
+
+typedef struct daris_task_stats {
+  int64_t released, accepted, completed, missed; /* DMR = missed / accepted (Sec. V)                         */
+  int64_t rejected_admission, rejected_overrun;
+  int64_t resp_min_ns, resp_max_ns, resp_sum_ns; /* response time = completion - release                     */
+  int64_t first_release_ns, last_finish_ns;
+  int32_t partition;                            /* ctx_i: current partition                                  */
+  int32_t n_stages;
+} daris_task_stats;
+
+/* 32-byte little-endian trace record; `type` values follow. */
+typedef struct daris_trace_rec {
+  uint64_t seq;
+  int64_t t_ns;
+  uint8_t type, level, stage, partition;
+  uint16_t task, stream;
+  uint32_t job;
+  uint32_t aux; /* DISPATCH: virtual deadline - release; STAGE_DONE/JOB_DONE: 1 = (virtual) deadline missed;
+                   REJECT: 1 admission, 2 overrun; MIGRATE: source partition, +256 if forced; ACCEPT: 1 if the job
+                   had been queued */
+} daris_trace_rec;
+enum {
+  DARIS_T_RELEASE = 1, DARIS_T_ACCEPT = 2, DARIS_T_REJECT = 3, DARIS_T_MIGRATE = 4, DARIS_T_DISPATCH = 5,
+  DARIS_T_STAGE_DONE = 6, DARIS_T_JOB_DONE = 7, DARIS_T_QUEUED = 8, DARIS_T_CMD_MIGRATE = 9
+};
+
+/* ---- life cycle ------------------------------------------------------------------------------------------ */
+
+/* Select HIP device `device` and reset all library state.  `seed` is stored for reproducibility reports only
+ * (the scheduler draws no random numbers).  Returns DARIS_ESTATE if already initialised. */
+daris_status daris_init(int device, uint64_t seed, int flags);
+/* Wait for running work, stop the scheduler thread, free every stream, event and device buffer. */
+daris_status daris_shutdown(void);
+const char* daris_last_error(void);
+
+/* ---- partitions (Sec. III-C) ------------------------------------------------------------------------------- */
+
+/* N_SM = ceil_even(OS * N_max / N_c) with OS = os_num/os_den (Sec. III-C2); pure integer helper, needs no init. */
+int32_t daris_cu_per_partition(int32_t os_num, int32_t os_den, int32_t n_cu_max, int32_t n_c);
+/* New partition of n_cu compute units (1..256) with one stream.  Partition p covers the logical CUs
+ * [start_p, start_p + n_cu) mod 256 with start_p = sum of earlier sizes mod 256, so partitions overlap only when
+ * their sizes sum past 256 (oversubscription).  Must precede daris_commit(). */
+daris_part daris_create_partition(int n_cu);
+/* Number of streams N_s of a partition (1..8); each stream runs one stage at a time (Sec. III-C1). */
+daris_status daris_partition_set_streams(daris_part p, int n_s);
+/* Copy the partition's CU mask (8 x 32 bits, bit i of word i/32 = logical CU i). */
+daris_status daris_partition_get_mask(daris_part p, uint32_t mask_out[8]);
+
+/* ---- tasks (Sec. III-A) ------------------------------------------------------------------------------------ */
+
+/* Register a periodic task: copies and re-packs the weights into device memory, allocates activation buffers.
+ * period_ns = T_i > 0, deadline_ns = D_i > 0 (the paper uses D_i = T_i), priority DARIS_HP or DARIS_LP.
+ * The task starts with one stage; its partition is chosen by daris_commit() (Algorithm 1). */
+daris_task daris_register_task(const daris_dnn* dnn, int64_t period_ns, int64_t deadline_ns, int priority);
+/* Cut the DNN into k sequential stages (Sec. III-B1).  A cut is legal after layer l when no later layer reads
+ * anything produced before l except l's own output.  The k-1 cuts minimise the largest per-stage MAC count; ties
+ * go to the lexicographically smallest cut list.  DARIS_ERANGE if k > legal cuts + 1. */
+daris_status daris_split_stages(daris_task t, int k);
+/* Writes the index of the first layer of each stage into first_layer[0..cap) and returns the stage count. */
+int32_t daris_get_stage_cuts(daris_task t, int32_t* first_layer, int32_t cap);
+/* Per-stage AFET (Sec. IV-A1), ns > 0: the execution-time estimate used until the stage has run once. */
+daris_status daris_set_afet(daris_task t, int stage, int64_t ns);
+/* MRET window size ws (eq. 1), default 5. */
+daris_status daris_set_window(int ws);
+/* Virtual-time mode: execution time of jobs job_lo..job_hi-1 of (task, stage) when run in partition p;
+ * et_ns = host int64[job_hi - job_lo], each >= 1. */
+daris_status daris_set_virtual_time(daris_task t, int stage, daris_part p, int64_t job_lo, int64_t job_hi,
+                                    const int64_t* et_ns);
+/* Offline phase (Algorithm 1): HP tasks, then LP tasks, each in registration order, go to the partition of least
+ * total utilisation afet_i/T_i (ties: lowest index).  Creates the CU-masked streams, starts the real-time
+ * clock and the scheduler thread.  Called implicitly by the first release. */
+daris_status daris_commit(void);
+/* Current partition ctx_i of a task (after commit). */
+daris_part daris_get_partition(daris_task t);
+
+/* ---- online phase (Sec. IV-B) ------------------------------------------------------------------------------ */
+
+/* Release one job of task t.  d_input = device float[c][h][w]; d_logits = device float[n_out] receiving the last
+ * layer's output in (c, y, x) order.  release_ns: virtual-time mode -- the release instant, non-decreasing over
+ * calls (events before it are simulated first; stage completions at exactly release_ns are processed before the
+ * release, dispatching at release_ns happens after all releases of that instant); real-time mode -- the nominal
+ * release used for deadlines and response times, or -1 for "now".  *decision (may be NULL) receives a
+ * DARIS_ACCEPTED.. code.  LP jobs take the admission test eq. (10)-(11); HP jobs are always scheduled. */
+daris_status daris_release_job(daris_task t, const void* d_input, void* d_logits, int64_t release_ns,
+                               int32_t* decision);
+/* Forced migration of task t to partition p: applied at once unless a stage of t is running, else at that
+ * stage's boundary; later jobs of t stay in p. */
+daris_status daris_migrate(daris_task t, daris_part p);
+/* Virtual time: simulate until no event is left.  Real time: block until no job is active or queued. */
+daris_status daris_run_until_idle(void);
+
+/* Per-task I/O pool for the library-driven runs below: job m reads input (m mod n_inputs) of d_inputs =
+ * device float[n_inputs][c*h*w] and writes logits row (m mod n_slots) of d_logits = device float[n_slots][n_out]. */
+daris_status daris_task_set_io(daris_task t, const void* d_inputs, int32_t n_inputs, void* d_logits, int32_t n_slots);
+/* Release job m of task i at phase_ns[i] + m * T_i for m < n_jobs[i] (arrays indexed by task handle, host), in
+ * (time, task) order, and return when every job has finished or was rejected. */
+daris_status daris_run_periodic(const int64_t* phase_ns, const int32_t* n_jobs);
+/* Saturated variant: every task with n_jobs[i] > 0 releases its next job the instant the previous one finishes
+ * (or is rejected) until n_jobs[i] were released.  Real-time mode only. */
+daris_status daris_run_closed_loop(const int32_t* n_jobs);
+
+/* ---- observation ------------------------------------------------------------------------------------------- */
+
+daris_status daris_get_stats(daris_task t, daris_task_stats* out);
+/* Copies up to cap_bytes / 32 not-yet-read trace records into buf (host); returns the byte count copied. */
+int64_t daris_trace_read(void* buf, int64_t cap_bytes);
+/* Current MRET of a stage (eq. 1), ns. */
+int64_t daris_get_mret(daris_task t, int stage);
+
+/* ---- direct execution (parity tests, calibration, profiling) --------------------------------------------------- */
+
+/* Run the whole DNN of task t once, stage after stage, on stream 0 of partition p, and wait for it.  No scheduler
+ * state is touched.  The logits do not depend on p or on the stage split. */
+daris_status daris_forward(daris_task t, const void* d_input, void* d_logits, daris_part p);
+/* After daris_forward with DARIS_KEEP_ACTIVATIONS: copy layer l's output to host float[c][h][w]. */
+daris_status daris_read_layer(daris_task t, int layer, float* host_out, int64_t cap_elems);
+/* Time each layer of task t on stream 0 of partition p with HIP events, `reps` runs averaged.
+ * ms_per_layer = host float[n_layers]; kernel_id = host int32[n_layers] (which kernel variant ran, see
+ * daris_kernel_name); flops = host double[n_layers] algorithmic FLOPs (2*MACs) of the layer. */
+daris_status daris_profile_layers(daris_task t, daris_part p, int reps, float* ms_per_layer, int32_t* kernel_id,
+                                  double* flops);
+const char* daris_kernel_name(int32_t kernel_id);
+/* Measure per-stage execution times of task t alone on partition p (`reps` runs, the maximum is kept) and store
+ * them as the task's AFET values. */
+daris_status daris_calibrate_afet(daris_task t, daris_part p, int reps);
+
+/* Mask probing: launch n_groups (<= 65536) short workgroups on stream 0 of partition p; out = host
+ * uint32[2 * n_groups] receives, per workgroup, the XCC (die) id and the hardware id register of the compute unit
+ * it ran on.  `spin` (0..100000) bounds a sleep loop that keeps workgroups resident so that they spread over
+ * every CU the mask allows. */
+daris_status daris_probe_cus(daris_part p, int n_groups, int spin, uint32_t* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DARIS_H */

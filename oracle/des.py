@@ -182,21 +182,24 @@ class SchedulerModel:
         """Eq. (10)-(11): U^{l,a}_k + u < N_s - U^{h,t}_k, strict, in Q32 integers."""
         return self.ula[k] + u + self.u_high_total(k) < self.n_streams[k] * Q
 
-    def release(self, t: int, i: int) -> int:
+    def release(self, t: int, i: int, r: Optional[int] = None) -> int:
+        """Release processed at time t; deadlines and response time count from the nominal release r <= t
+        (r = t in virtual time; a real-time run may process a release slightly late)."""
         self.commit()
+        r = t if r is None else min(r, t)
         ts = self.tasks[i]
         m = ts.n_released
         ts.n_released += 1
-        self._rec(t, RELEASE, part=ts.ctx, task=i, job=m)
+        self._rec(t, RELEASE, part=ts.ctx, task=i, job=m, aux=t - r)
         if ts.active is not None:
             if ts.p.prio == HP and not (self.flags & F_HP_ADMISSION):
-                ts.fifo.append((m, t))               # HP jobs are always scheduled: wait behind the running job
+                ts.fifo.append((m, r))               # HP jobs are always scheduled: wait behind the running job
                 self._rec(t, QUEUED, part=ts.ctx, task=i, job=m)
                 return QUEUED
             ts.rej_over += 1                         # previous job of the task still active
             self._rec(t, REJECT, part=ts.ctx, task=i, job=m, aux=REJECT_OVERRUN)
             return REJECT
-        return self._start_job(t, i, m, t, queued=False)
+        return self._start_job(t, i, m, r, queued=False)
 
     def _start_job(self, t: int, i: int, m: int, r: int, queued: bool) -> int:
         ts = self.tasks[i]
@@ -383,7 +386,7 @@ def run_replay(model: SchedulerModel, recorded):
     for rec in recorded:
         _, t, typ, _lvl, _stage, part, task, _stream, _job, _aux = rec
         if typ == RELEASE:
-            model.release(t, task)
+            model.release(t, task, t - _aux)
         elif typ == CMD_MIGRATE:
             model.migrate_command(t, task, part)
         elif typ == STAGE_DONE:

@@ -1,0 +1,950 @@
+// C ABI of the library: global state, partitions as CU-masked HIP streams, task registration, and the two
+// drivers around the decision core -- a virtual-time event loop and the real-time loop (API thread + one polling
+// scheduler thread) in which a stage boundary is a completion event observed by the host (Sec. III-B1).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <atomic>
+#include <chrono>
+#include <condition_variable>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <memory>
+#include <mutex>
+#include <queue>
+#include <string>
+#include <thread>
+#include <unordered_map>
+#include <vector>
+
+#include "../../include/daris.h"
+#include "kernels.h"
+#include "net_plan.h"
+#include "sched_core.h"
+
+using namespace daris;
+
+namespace {
+
+thread_local std::string tl_error;
+
+daris_status fail(daris_status code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  tl_error = buf;
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                                       \
+  do {                                                                                                      \
+    hipError_t e_ = (expr);                                                                                 \
+    if (e_ != hipSuccess) return fail(DARIS_EHIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+  } while (0)
+
+struct JobIo {
+  const void* in = nullptr;
+  void* out = nullptr;
+};
+
+struct TaskRt {
+  NetPlan net;
+  std::vector<void*> slots;
+  float* ws = nullptr;
+  std::vector<void*> owned;  // every device allocation of the task
+  // I/O
+  const void* pool_in = nullptr;
+  void* pool_out = nullptr;
+  int32_t n_inputs = 0, n_slots = 0;
+  std::unordered_map<uint32_t, JobIo> io;  // per released job
+  hipEvent_t chain = nullptr;              // virtual-time mode: orders a task's stages across streams
+  // virtual execution times: (stage, partition) -> (job_lo, values)
+  std::map<std::pair<int, int>, std::pair<int64_t, std::vector<int64_t>>> vt;
+  // library-driven runs
+  int32_t closed_left = 0;
+};
+
+struct StreamRt {
+  hipStream_t s = nullptr;
+  hipEvent_t done = nullptr;
+  bool busy = false;
+  int task = -1;
+};
+
+struct PartRt {
+  int n_cu = 0, start = 0, n_streams = 1;
+  uint32_t mask[8] = {0};
+  std::vector<StreamRt> streams;
+};
+
+struct VtEvent {
+  int64_t t;
+  int task;
+  uint32_t job;
+  bool operator>(const VtEvent& o) const {
+    if (t != o.t) return t > o.t;
+    if (task != o.task) return task > o.task;
+    return job > o.job;
+  }
+};
+
+struct Global {
+  bool inited = false;
+  int device = 0, flags = 0;
+  uint64_t seed = 0;
+  bool vt = false, nodev = false;
+  SchedCore core;
+  std::vector<PartRt> parts;
+  std::vector<std::unique_ptr<TaskRt>> tasks;
+  int cu_cursor = 0;
+  size_t trace_cursor = 0;
+  bool committed = false;  // Algorithm 1 has run, the online phase has begun
+  bool frozen = false;     // streams exist, the partition set can no longer change
+  // virtual time
+  int64_t vt_now = -1;
+  bool vt_dirty = false;
+  std::priority_queue<VtEvent, std::vector<VtEvent>, std::greater<VtEvent>> heap;
+  // real time
+  std::mutex mu;
+  std::condition_variable cv_work, cv_idle;
+  std::thread thr;
+  bool stop = false;
+  std::chrono::steady_clock::time_point epoch;
+  std::string async_error;
+};
+
+Global* G = nullptr;
+
+int64_t now_ns() {
+  return std::chrono::duration_cast<std::chrono::nanoseconds>(std::chrono::steady_clock::now() - G->epoch).count();
+}
+
+// ---- stage execution ----------------------------------------------------------------------------------------------
+
+hipError_t launch_layer(TaskRt& T, int l, void* d_logits, hipStream_t s) {
+  NetPlan& net = T.net;
+  LayerPlan& L = net.layers[l];
+  const TensorInfo& in = net.tensor(L.in_t);
+  const void* x = T.slots[in.slot];
+  const bool last = l == (int)net.layers.size() - 1;
+  void* y = (last && net.final_direct) ? d_logits : T.slots[L.out.slot];
+  switch (L.d.op) {
+    case DARIS_OP_CONV:
+      if (L.depthwise) {
+        DwArgs a;
+        a.x = x; a.w = L.w_dev; a.bias = L.b_dev; a.y = y;
+        a.H = in.H; a.W = in.W; a.C = in.Cs; a.Ho = L.out.H; a.Wo = L.out.W;
+        a.k = L.d.k; a.stride = L.d.stride; a.pad = L.d.pad; a.act = L.d.act;
+        return launch_dwconv(a, net.bf16, s);
+      } else {
+        ConvArgs a;
+        a.x = x; a.w = L.w_dev; a.bias = L.b_dev; a.y = y; a.ws = T.ws;
+        a.res = L.res_t >= 0 ? T.slots[net.tensor(L.res_t).slot] : nullptr;
+        a.H = in.H; a.W = in.W; a.Cin = in.Cs; a.Ho = L.out.H; a.Wo = L.out.W; a.Cout = L.out.Cs;
+        a.kh = a.kw = L.d.k; a.stride = L.d.stride; a.pad = L.d.pad;
+        a.K = L.K; a.Kpad = L.Kpad; a.M = L.out.H * L.out.W; a.act = L.d.act;
+        a.splitk = L.cp.splitk; a.kchunk = L.cp.kchunk;
+        return launch_conv(L.cp, a, net.bf16, s);
+      }
+    case DARIS_OP_MAXPOOL:
+    case DARIS_OP_GAVGPOOL: {
+      PoolArgs a;
+      a.x = x; a.y = y; a.H = in.H; a.W = in.W; a.C = in.Cs; a.Ho = L.out.H; a.Wo = L.out.W;
+      a.k = L.d.k; a.stride = L.d.stride; a.pad = L.d.pad;
+      return L.d.op == DARIS_OP_MAXPOOL ? launch_maxpool(a, net.bf16, s) : launch_gavgpool(a, net.bf16, s);
+    }
+    case DARIS_OP_FC: {
+      FcArgs a;
+      a.x = x; a.w = L.w_dev; a.bias = L.b_dev; a.y = y;
+      a.K = L.K; a.N = L.d.c_out; a.Ns = (last && net.final_direct) ? L.d.c_out : L.out.Cs;
+      a.act = L.d.act; a.out_f32 = (last && net.final_direct) ? 1 : 0;
+      return launch_fc(a, net.bf16, s);
+    }
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_stage(TaskRt& T, int stage, const JobIo& io, hipStream_t s) {
+  NetPlan& net = T.net;
+  const int n = (int)net.layers.size();
+  const int first = net.stage_first[stage];
+  const int end = stage + 1 < (int)net.stage_first.size() ? net.stage_first[stage + 1] : n;
+  hipError_t e;
+  if (stage == 0) {
+    e = launch_ingest((const float*)io.in, T.slots[net.ingest.slot], net.ingest.C, net.ingest.Cs, net.ingest.H, net.ingest.W,
+                      net.bf16, s);
+    if (e != hipSuccess) return e;
+  }
+  for (int l = first; l < end; ++l) {
+    e = launch_layer(T, l, io.out, s);
+    if (e != hipSuccess) return e;
+  }
+  if (end == n && !net.final_direct) {
+    const TensorInfo& o = net.layers[n - 1].out;
+    e = launch_egress(T.slots[o.slot], (float*)io.out, o.C, o.Cs, o.H, o.W, net.bf16, s);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+// Acts on the launches a dispatch pass produced.  Virtual time: schedule the completion from the table and (with a
+// device) enqueue the kernels behind the task's previous stage.  Real time: enqueue and record the boundary event.
+daris_status issue(const std::vector<Launch>& ls, int64_t t) {
+  for (const Launch& l : ls) {
+    TaskRt& T = *G->tasks[l.task];
+    if (G->vt) {
+      auto it = T.vt.find(std::make_pair(l.stage, l.part));
+      if (it == T.vt.end()) return fail(DARIS_ESTATE, "no virtual execution time for task %d stage %d partition %d", l.task, l.stage, l.part);
+      const int64_t idx = (int64_t)l.job - it->second.first;
+      if (idx < 0 || idx >= (int64_t)it->second.second.size())
+        return fail(DARIS_ESTATE, "virtual execution time table of task %d stage %d partition %d has no job %u", l.task, l.stage, l.part, l.job);
+      G->heap.push(VtEvent{t + it->second.second[idx], l.task, l.job});
+    }
+    if (!G->nodev) {
+      StreamRt& S = G->parts[l.part].streams[l.stream];
+      auto io = T.io.find(l.job);
+      if (io == T.io.end()) return fail(DARIS_ESTATE, "job %u of task %d has no I/O buffers", l.job, l.task);
+      if (G->vt) HIP_TRY(hipStreamWaitEvent(S.s, T.chain, 0));
+      HIP_TRY(launch_stage(T, l.stage, io->second, S.s));
+      if (G->vt) {
+        HIP_TRY(hipEventRecord(T.chain, S.s));
+      } else {
+        HIP_TRY(hipEventRecord(S.done, S.s));
+        S.busy = true;
+        S.task = l.task;
+      }
+    }
+  }
+  return DARIS_OK;
+}
+
+daris_status dispatch_and_issue(int64_t t) {
+  std::vector<Launch> ls;
+  G->core.dispatch(t, &ls);
+  return issue(ls, t);
+}
+
+// ---- virtual-time driver -------------------------------------------------------------------------------------------
+
+// Process every completion due at exactly G->vt_now (ordered by task, job).
+void vt_completions_now() {
+  while (!G->heap.empty() && G->heap.top().t == G->vt_now) {
+    VtEvent ev = G->heap.top();
+    G->heap.pop();
+    if (G->core.stage_done(ev.t, ev.task)) G->tasks[ev.task]->io.erase(ev.job);
+    G->vt_dirty = true;
+  }
+}
+
+// Advance the virtual clock up to `limit` (exclusive): dispatch what is pending, then event by event.
+daris_status vt_advance(int64_t limit, bool unbounded) {
+  for (;;) {
+    if (G->vt_dirty) {
+      G->vt_dirty = false;
+      daris_status st = dispatch_and_issue(G->vt_now);
+      if (st != DARIS_OK) return st;
+    }
+    if (G->heap.empty()) return DARIS_OK;
+    const int64_t t = G->heap.top().t;
+    if (!unbounded && t >= limit) return DARIS_OK;
+    G->vt_now = t;
+    vt_completions_now();
+  }
+}
+
+// ---- real-time driver ----------------------------------------------------------------------------------------------
+
+daris_status rt_release_locked(int task, const JobIo& io, int64_t now, int64_t r, int32_t* decision) {
+  uint32_t job = 0;
+  Decision d = G->core.release(now, task, r, &job);
+  if (decision) *decision = (int32_t)d;
+  if (d == D_ACCEPTED || d == D_MIGRATED || d == D_QUEUED) G->tasks[task]->io[job] = io;
+  return dispatch_and_issue(now);
+}
+
+JobIo pool_io(TaskRt& T, uint32_t job) {
+  JobIo io;
+  const NetPlan& n = T.net;
+  const size_t in_elems = (size_t)n.in_c * n.in_h * n.in_w;
+  io.in = (const float*)T.pool_in + (size_t)(job % (uint32_t)T.n_inputs) * in_elems;
+  io.out = (float*)T.pool_out + (size_t)(job % (uint32_t)T.n_slots) * n.n_out;
+  return io;
+}
+
+void sched_loop() {
+  (void)hipSetDevice(G->device);
+  std::unique_lock<std::mutex> lk(G->mu);
+  while (!G->stop) {
+    bool any_busy = false;
+    for (size_t k = 0; k < G->parts.size(); ++k) {
+      for (StreamRt& S : G->parts[k].streams) {
+        if (!S.busy) continue;
+        any_busy = true;
+        hipError_t q = hipEventQuery(S.done);
+        if (q == hipErrorNotReady) continue;
+        if (q != hipSuccess && G->async_error.empty())
+          G->async_error = std::string("stage completion event: ") + hipGetErrorString(q);
+        const int64_t now = now_ns();
+        const int task = S.task;
+        TaskRt& T = *G->tasks[task];
+        S.busy = false;
+        S.task = -1;
+        const uint32_t job = G->core.active_job(task);
+        if (G->core.stage_done(now, task)) {
+          T.io.erase(job);
+          // closed loop: the next job of the task is released the instant this one ends
+          while (T.closed_left > 0 && !G->core.has_active(task)) {
+            T.closed_left--;
+            const uint32_t next = (uint32_t)G->core.stats(task).released;
+            int32_t dec = 0;
+            if (rt_release_locked(task, pool_io(T, next), now, now, &dec) != DARIS_OK && G->async_error.empty())
+              G->async_error = tl_error;
+          }
+        }
+        if (dispatch_and_issue(now) != DARIS_OK && G->async_error.empty()) G->async_error = tl_error;
+        if (G->core.idle()) G->cv_idle.notify_all();
+      }
+    }
+    if (!any_busy) {
+      G->cv_work.wait_for(lk, std::chrono::microseconds(500));
+    } else {
+      lk.unlock();
+      std::this_thread::yield();
+      lk.lock();
+    }
+  }
+}
+
+daris_status check_task(daris_task t) {
+  if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
+  if (t < 0 || t >= (int)G->tasks.size()) return fail(DARIS_ERANGE, "task handle %d out of range", t);
+  return DARIS_OK;
+}
+daris_status check_part(daris_part p) {
+  if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
+  if (p < 0 || p >= (int)G->parts.size()) return fail(DARIS_ERANGE, "partition handle %d out of range", p);
+  return DARIS_OK;
+}
+
+daris_status wait_idle() {
+  std::unique_lock<std::mutex> lk(G->mu);
+  while (!G->core.idle()) {
+    if (!G->async_error.empty()) break;
+    G->cv_idle.wait_for(lk, std::chrono::milliseconds(1));
+  }
+  if (!G->async_error.empty()) {
+    daris_status st = fail(DARIS_EHIP, "%s", G->async_error.c_str());
+    G->async_error.clear();
+    return st;
+  }
+  return DARIS_OK;
+}
+
+void free_task(TaskRt& T) {
+  for (void* p : T.owned) (void)hipFree(p);
+  T.owned.clear();
+  if (T.chain) (void)hipEventDestroy(T.chain);
+  T.chain = nullptr;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* daris_last_error(void) { return tl_error.c_str(); }
+
+int32_t daris_cu_per_partition(int32_t os_num, int32_t os_den, int32_t n_cu_max, int32_t n_c) {
+  if (os_num < 1 || os_den < 1 || n_cu_max < 1 || n_c < 1) return fail(DARIS_EINVAL, "arguments must be positive");
+  return (int32_t)ceil_even((int64_t)os_num * n_cu_max, (int64_t)os_den * n_c);
+}
+
+daris_status daris_init(int device, uint64_t seed, int flags) {
+  if (G && G->inited) return fail(DARIS_ESTATE, "already initialised");
+  if ((flags & DARIS_NO_DEVICE) && !(flags & DARIS_VIRTUAL_TIME)) return fail(DARIS_EINVAL, "DARIS_NO_DEVICE needs DARIS_VIRTUAL_TIME");
+  delete G;
+  G = new Global();
+  G->device = device;
+  G->seed = seed;
+  G->flags = flags;
+  G->vt = flags & DARIS_VIRTUAL_TIME;
+  G->nodev = flags & DARIS_NO_DEVICE;
+  int cf = 0;
+  if (flags & DARIS_NO_LAST) cf |= CF_NO_LAST;
+  if (flags & DARIS_NO_PRIOR) cf |= CF_NO_PRIOR;
+  if (flags & DARIS_NO_FIXED) cf |= CF_NO_FIXED;
+  if (flags & DARIS_HP_ADMISSION) cf |= CF_HP_ADMISSION;
+  G->core.set_flags(cf);
+  if (!G->nodev) {
+    int n = 0;
+    hipError_t e = hipGetDeviceCount(&n);
+    if (e != hipSuccess || device < 0 || device >= n) {
+      delete G;
+      G = nullptr;
+      return fail(DARIS_EHIP, "no usable HIP device %d (%s)", device, e == hipSuccess ? "index out of range" : hipGetErrorString(e));
+    }
+    e = hipSetDevice(device);
+    if (e != hipSuccess) {
+      delete G;
+      G = nullptr;
+      return fail(DARIS_EHIP, "hipSetDevice failed: %s", hipGetErrorString(e));
+    }
+  }
+  G->inited = true;
+  return DARIS_OK;
+}
+
+daris_status daris_shutdown(void) {
+  if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
+  if (G->thr.joinable()) {
+    {
+      std::lock_guard<std::mutex> lk(G->mu);
+      G->stop = true;
+    }
+    G->cv_work.notify_all();
+    G->thr.join();
+  }
+  if (!G->nodev) {
+    (void)hipDeviceSynchronize();
+    for (auto& T : G->tasks) free_task(*T);
+    for (PartRt& P : G->parts)
+      for (StreamRt& S : P.streams) {
+        if (S.done) (void)hipEventDestroy(S.done);
+        if (S.s) (void)hipStreamDestroy(S.s);
+      }
+  }
+  delete G;
+  G = nullptr;
+  return DARIS_OK;
+}
+
+daris_part daris_create_partition(int n_cu) {
+  if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
+  if (G->frozen) return fail(DARIS_ESTATE, "partitions must be created before the first execution or daris_commit");
+  if (n_cu < 1 || n_cu > 256) return fail(DARIS_EINVAL, "n_cu must be in 1..256, got %d", n_cu);
+  if (G->parts.size() >= 255) return fail(DARIS_ERANGE, "too many partitions");
+  PartRt P;
+  P.n_cu = n_cu;
+  P.start = G->cu_cursor;
+  for (int i = 0; i < n_cu; ++i) {
+    const int cu = (P.start + i) % 256;
+    P.mask[cu / 32] |= 1u << (cu % 32);
+  }
+  G->cu_cursor = (G->cu_cursor + n_cu) % 256;
+  G->parts.push_back(P);
+  return G->core.add_partition(1);
+}
+
+daris_status daris_partition_set_streams(daris_part p, int n_s) {
+  daris_status st = check_part(p);
+  if (st != DARIS_OK) return st;
+  if (G->frozen) return fail(DARIS_ESTATE, "stream count must be set before the first execution or daris_commit");
+  if (n_s < 1 || n_s > 8) return fail(DARIS_EINVAL, "n_s must be in 1..8");
+  G->parts[p].n_streams = n_s;
+  G->core.set_streams(p, n_s);
+  return DARIS_OK;
+}
+
+daris_status daris_partition_get_mask(daris_part p, uint32_t mask_out[8]) {
+  daris_status st = check_part(p);
+  if (st != DARIS_OK) return st;
+  if (!mask_out) return fail(DARIS_EINVAL, "mask_out is NULL");
+  std::memcpy(mask_out, G->parts[p].mask, sizeof(uint32_t) * 8);
+  return DARIS_OK;
+}
+
+daris_task daris_register_task(const daris_dnn* dnn, int64_t period_ns, int64_t deadline_ns, int priority) {
+  if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
+  if (G->committed) return fail(DARIS_ESTATE, "tasks must be registered before daris_commit");
+  if (!dnn) return fail(DARIS_EINVAL, "dnn is NULL");
+  if (period_ns <= 0 || deadline_ns <= 0) return fail(DARIS_EINVAL, "period and deadline must be positive");
+  if (priority != DARIS_HP && priority != DARIS_LP) return fail(DARIS_EINVAL, "priority must be DARIS_HP or DARIS_LP");
+  if (G->tasks.size() >= 65535) return fail(DARIS_ERANGE, "too many tasks");
+  std::unique_ptr<TaskRt> T(new TaskRt());
+  std::string err = build_plan(*dnn, G->flags & DARIS_KEEP_ACTIVATIONS, &T->net);
+  if (!err.empty()) return fail(DARIS_EINVAL, "%s", err.c_str());
+  if (!G->nodev) {
+    NetPlan& net = T->net;
+    auto dev_alloc = [&](size_t bytes, void** out) -> hipError_t {
+      hipError_t e = hipMalloc(out, bytes ? bytes : 16);
+      if (e == hipSuccess) T->owned.push_back(*out);
+      return e;
+    };
+    for (size_t i = 0; i < net.layers.size(); ++i) {
+      LayerPlan& L = net.layers[i];
+      const daris_layer& src = dnn->layers[i];
+      if (L.d.op != DARIS_OP_CONV && L.d.op != DARIS_OP_FC) continue;
+      if (!src.w) {
+        free_task(*T);
+        return fail(DARIS_EINVAL, "layer %zu has no weights", i);
+      }
+      std::vector<unsigned char> wp;
+      std::vector<float> bp;
+      if (L.d.op == DARIS_OP_CONV) pack_conv(net, L, src.w, src.b, &wp, &bp);
+      else pack_fc(net, L, src.w, src.b, &wp, &bp);
+      hipError_t e = dev_alloc(wp.size(), &L.w_dev);
+      if (e == hipSuccess) e = dev_alloc(bp.size() * sizeof(float), (void**)&L.b_dev);
+      if (e == hipSuccess) e = hipMemcpy(L.w_dev, wp.data(), wp.size(), hipMemcpyHostToDevice);
+      if (e == hipSuccess) e = hipMemcpy(L.b_dev, bp.data(), bp.size() * sizeof(float), hipMemcpyHostToDevice);
+      if (e != hipSuccess) {
+        free_task(*T);
+        return fail(e == hipErrorOutOfMemory ? DARIS_ENOMEM : DARIS_EHIP, "weight upload of layer %zu: %s", i, hipGetErrorString(e));
+      }
+    }
+    T->slots.resize(net.slot_bytes.size());
+    for (size_t i = 0; i < net.slot_bytes.size(); ++i) {
+      hipError_t e = dev_alloc(net.slot_bytes[i], &T->slots[i]);
+      if (e == hipSuccess) e = hipMemset(T->slots[i], 0, net.slot_bytes[i]);
+      if (e != hipSuccess) {
+        free_task(*T);
+        return fail(DARIS_ENOMEM, "activation buffer: %s", hipGetErrorString(e));
+      }
+    }
+    if (net.ws_bytes) {
+      hipError_t e = dev_alloc(net.ws_bytes, (void**)&T->ws);
+      if (e != hipSuccess) {
+        free_task(*T);
+        return fail(DARIS_ENOMEM, "split-K workspace: %s", hipGetErrorString(e));
+      }
+    }
+    hipError_t e = hipEventCreateWithFlags(&T->chain, hipEventDisableTiming);
+    if (e != hipSuccess) {
+      free_task(*T);
+      return fail(DARIS_EHIP, "hipEventCreate: %s", hipGetErrorString(e));
+    }
+  }
+  G->tasks.push_back(std::move(T));
+  return G->core.add_task(period_ns, deadline_ns, priority, 1);
+}
+
+daris_status daris_split_stages(daris_task t, int k) {
+  daris_status st = check_task(t);
+  if (st != DARIS_OK) return st;
+  if (G->committed) return fail(DARIS_ESTATE, "stages must be chosen before daris_commit");
+  NetPlan& net = G->tasks[t]->net;
+  if (k < 1) return fail(DARIS_EINVAL, "k must be >= 1");
+  if (k > 255) return fail(DARIS_ERANGE, "k must be <= 255");
+  if (!split_stages(&net, k)) return fail(DARIS_ERANGE, "k = %d exceeds the %zu legal cut points + 1", k, net.legal_cuts.size());
+  G->core.set_stage_count(t, k);
+  G->tasks[t]->vt.clear();
+  return DARIS_OK;
+}
+
+int32_t daris_get_stage_cuts(daris_task t, int32_t* first_layer, int32_t cap) {
+  daris_status st = check_task(t);
+  if (st != DARIS_OK) return st;
+  const std::vector<int>& f = G->tasks[t]->net.stage_first;
+  for (int i = 0; i < (int)f.size() && i < cap && first_layer; ++i) first_layer[i] = f[i];
+  return (int32_t)f.size();
+}
+
+daris_status daris_set_afet(daris_task t, int stage, int64_t ns) {
+  daris_status st = check_task(t);
+  if (st != DARIS_OK) return st;
+  if (stage < 0 || stage >= G->core.n_stages(t)) return fail(DARIS_ERANGE, "stage %d out of range", stage);
+  if (ns <= 0) return fail(DARIS_EINVAL, "AFET must be positive");
+  if (G->committed) return fail(DARIS_ESTATE, "AFET must be set before daris_commit");
+  G->core.set_afet(t, stage, ns);
+  return DARIS_OK;
+}
+
+daris_status daris_set_window(int ws) {
+  if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
+  if (ws < 1) return fail(DARIS_EINVAL, "ws must be >= 1");
+  G->core.set_window(ws);
+  return DARIS_OK;
+}
+
+daris_status daris_set_virtual_time(daris_task t, int stage, daris_part p, int64_t job_lo, int64_t job_hi, const int64_t* et_ns) {
+  daris_status st = check_task(t);
+  if (st != DARIS_OK) return st;
+  st = check_part(p);
+  if (st != DARIS_OK) return st;
+  if (stage < 0 || stage >= G->core.n_stages(t)) return fail(DARIS_ERANGE, "stage %d out of range", stage);
+  if (job_lo < 0 || job_hi < job_lo || !et_ns) return fail(DARIS_EINVAL, "bad job range or NULL table");
+  std::vector<int64_t> v(et_ns, et_ns + (job_hi - job_lo));
+  for (int64_t x : v)
+    if (x < 1) return fail(DARIS_EINVAL, "execution times must be >= 1 ns");
+  G->tasks[t]->vt[std::make_pair(stage, (int)p)] = std::make_pair(job_lo, std::move(v));
+  return DARIS_OK;
+}
+
+// Creates the CU-masked streams of every partition; after this the partition set is frozen.
+static daris_status make_streams(void) {
+  if (G->frozen) return DARIS_OK;
+  if (G->parts.empty()) return fail(DARIS_ESTATE, "no partition");
+  if (!G->nodev) {
+    for (PartRt& P : G->parts) {
+      P.streams.resize(P.n_streams);
+      for (StreamRt& S : P.streams) {
+        HIP_TRY(hipExtStreamCreateWithCUMask(&S.s, 8, P.mask));
+        HIP_TRY(hipEventCreateWithFlags(&S.done, hipEventDisableTiming));
+      }
+    }
+  }
+  G->frozen = true;
+  return DARIS_OK;
+}
+
+daris_status daris_commit(void) {
+  if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
+  if (G->committed) return DARIS_OK;
+  if (G->tasks.empty()) return fail(DARIS_ESTATE, "no task");
+  daris_status st0 = make_streams();
+  if (st0 != DARIS_OK) return st0;
+  G->core.commit();
+  G->committed = true;
+  G->epoch = std::chrono::steady_clock::now();
+  if (!G->vt) G->thr = std::thread(sched_loop);
+  return DARIS_OK;
+}
+
+daris_part daris_get_partition(daris_task t) {
+  daris_status st = check_task(t);
+  if (st != DARIS_OK) return st;
+  if (!G->committed) return fail(DARIS_ESTATE, "not committed");
+  std::lock_guard<std::mutex> lk(G->mu);
+  return G->core.context(t);
+}
+
+daris_status daris_release_job(daris_task t, const void* d_input, void* d_logits, int64_t release_ns, int32_t* decision) {
+  daris_status st = check_task(t);
+  if (st != DARIS_OK) return st;
+  if (!G->nodev && (!d_input || !d_logits)) return fail(DARIS_EINVAL, "NULL device buffer");
+  st = daris_commit();
+  if (st != DARIS_OK) return st;
+  JobIo io;
+  io.in = d_input;
+  io.out = d_logits;
+  if (G->vt) {
+    if (release_ns < 0 || release_ns < G->vt_now) return fail(DARIS_ESTATE, "virtual release times must not decrease");
+    if (release_ns > G->vt_now) {
+      st = vt_advance(release_ns, false);
+      if (st != DARIS_OK) return st;
+      G->vt_now = release_ns;
+      vt_completions_now();
+    }
+    uint32_t job = 0;
+    Decision d = G->core.release(release_ns, t, release_ns, &job);
+    if (decision) *decision = (int32_t)d;
+    if (d == D_ACCEPTED || d == D_MIGRATED || d == D_QUEUED) G->tasks[t]->io[job] = io;
+    G->vt_dirty = true;
+    return DARIS_OK;
+  }
+  {
+    std::lock_guard<std::mutex> lk(G->mu);
+    const int64_t now = now_ns();
+    st = rt_release_locked(t, io, now, release_ns < 0 ? now : release_ns, decision);
+  }
+  G->cv_work.notify_all();
+  return st;
+}
+
+daris_status daris_migrate(daris_task t, daris_part p) {
+  daris_status st = check_task(t);
+  if (st != DARIS_OK) return st;
+  st = check_part(p);
+  if (st != DARIS_OK) return st;
+  st = daris_commit();
+  if (st != DARIS_OK) return st;
+  if (G->vt) {
+    G->core.migrate_command(G->vt_now < 0 ? 0 : G->vt_now, t, p);
+    G->vt_dirty = true;
+    return DARIS_OK;
+  }
+  std::lock_guard<std::mutex> lk(G->mu);
+  const int64_t now = now_ns();
+  G->core.migrate_command(now, t, p);
+  return dispatch_and_issue(now);
+}
+
+daris_status daris_run_until_idle(void) {
+  if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
+  if (!G->committed) return DARIS_OK;
+  if (G->vt) {
+    daris_status st = vt_advance(0, true);
+    if (st != DARIS_OK) return st;
+    if (!G->nodev) HIP_TRY(hipDeviceSynchronize());
+    return DARIS_OK;
+  }
+  return wait_idle();
+}
+
+daris_status daris_task_set_io(daris_task t, const void* d_inputs, int32_t n_inputs, void* d_logits, int32_t n_slots) {
+  daris_status st = check_task(t);
+  if (st != DARIS_OK) return st;
+  if (!G->nodev && (!d_inputs || !d_logits)) return fail(DARIS_EINVAL, "NULL device buffer");
+  if (n_inputs < 1 || n_slots < 1) return fail(DARIS_EINVAL, "pool sizes must be >= 1");
+  TaskRt& T = *G->tasks[t];
+  T.pool_in = d_inputs;
+  T.pool_out = d_logits;
+  T.n_inputs = n_inputs;
+  T.n_slots = n_slots;
+  return DARIS_OK;
+}
+
+daris_status daris_run_periodic(const int64_t* phase_ns, const int32_t* n_jobs) {
+  if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
+  if (!n_jobs) return fail(DARIS_EINVAL, "n_jobs is NULL");
+  daris_status st = daris_commit();
+  if (st != DARIS_OK) return st;
+  struct Rel {
+    int64_t t;
+    int task;
+    uint32_t m;
+  };
+  std::vector<Rel> rels;
+  for (int i = 0; i < (int)G->tasks.size(); ++i) {
+    if (n_jobs[i] > 0 && G->tasks[i]->n_inputs < 1) return fail(DARIS_ESTATE, "task %d has no I/O pool (daris_task_set_io)", i);
+    const int64_t ph = phase_ns ? phase_ns[i] : 0;
+    if (ph < 0) return fail(DARIS_EINVAL, "phases must be >= 0");
+    const int64_t period = G->core.period(i);
+    for (int32_t m = 0; m < n_jobs[i]; ++m) rels.push_back(Rel{ph + (int64_t)m * period, i, (uint32_t)m});
+  }
+  std::sort(rels.begin(), rels.end(), [](const Rel& a, const Rel& b) {
+    if (a.t != b.t) return a.t < b.t;
+    if (a.task != b.task) return a.task < b.task;
+    return a.m < b.m;
+  });
+  const int64_t base = G->vt ? (G->vt_now < 0 ? 0 : G->vt_now + 1) : now_ns() + 200000;  // real time: start 0.2 ms from now
+  for (const Rel& r : rels) {
+    TaskRt& T = *G->tasks[r.task];
+    const int64_t t = base + r.t;
+    if (G->vt) {
+      const uint32_t job = (uint32_t)G->core.stats(r.task).released;
+      st = daris_release_job(r.task, G->nodev ? nullptr : pool_io(T, job).in, G->nodev ? nullptr : pool_io(T, job).out, t, nullptr);
+      if (st != DARIS_OK) return st;
+      continue;
+    }
+    // sleep most of the wait, spin the last stretch
+    for (;;) {
+      const int64_t left = t - now_ns();
+      if (left <= 0) break;
+      if (left > 150000) std::this_thread::sleep_for(std::chrono::nanoseconds(left - 100000));
+    }
+    {
+      std::lock_guard<std::mutex> lk(G->mu);
+      const uint32_t job = (uint32_t)G->core.stats(r.task).released;
+      st = rt_release_locked(r.task, pool_io(T, job), now_ns(), t, nullptr);
+    }
+    G->cv_work.notify_all();
+    if (st != DARIS_OK) return st;
+  }
+  return daris_run_until_idle();
+}
+
+daris_status daris_run_closed_loop(const int32_t* n_jobs) {
+  if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
+  if (G->vt) return fail(DARIS_ESTATE, "closed-loop runs need real-time mode");
+  if (!n_jobs) return fail(DARIS_EINVAL, "n_jobs is NULL");
+  daris_status st = daris_commit();
+  if (st != DARIS_OK) return st;
+  for (int i = 0; i < (int)G->tasks.size(); ++i)
+    if (n_jobs[i] > 0 && G->tasks[i]->n_inputs < 1) return fail(DARIS_ESTATE, "task %d has no I/O pool (daris_task_set_io)", i);
+  {
+    std::lock_guard<std::mutex> lk(G->mu);
+    const int64_t now = now_ns();
+    for (int i = 0; i < (int)G->tasks.size(); ++i) {
+      TaskRt& T = *G->tasks[i];
+      T.closed_left = n_jobs[i];
+      // a rejected release ends no job, so keep releasing until one is admitted or the budget is spent
+      while (T.closed_left > 0 && !G->core.has_active(i)) {
+        T.closed_left--;
+        const uint32_t job = (uint32_t)G->core.stats(i).released;
+        st = rt_release_locked(i, pool_io(T, job), now, now, nullptr);
+        if (st != DARIS_OK) return st;
+      }
+    }
+  }
+  G->cv_work.notify_all();
+  return wait_idle();
+}
+
+daris_status daris_get_stats(daris_task t, daris_task_stats* out) {
+  daris_status st = check_task(t);
+  if (st != DARIS_OK) return st;
+  if (!out) return fail(DARIS_EINVAL, "out is NULL");
+  std::lock_guard<std::mutex> lk(G->mu);
+  const TaskStats& s = G->core.stats(t);
+  out->released = s.released;
+  out->accepted = s.accepted;
+  out->completed = s.completed;
+  out->missed = s.missed;
+  out->rejected_admission = s.rej_adm;
+  out->rejected_overrun = s.rej_over;
+  out->resp_min_ns = s.resp_min;
+  out->resp_max_ns = s.resp_max;
+  out->resp_sum_ns = s.resp_sum;
+  out->first_release_ns = s.first_release;
+  out->last_finish_ns = s.last_finish;
+  out->partition = G->core.context(t);
+  out->n_stages = G->core.n_stages(t);
+  return DARIS_OK;
+}
+
+int64_t daris_trace_read(void* buf, int64_t cap_bytes) {
+  if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
+  if (!buf || cap_bytes < 0) return fail(DARIS_EINVAL, "bad buffer");
+  std::lock_guard<std::mutex> lk(G->mu);
+  std::vector<TraceRec>& tr = G->core.trace();
+  size_t n = std::min<size_t>((size_t)cap_bytes / sizeof(TraceRec), tr.size() - G->trace_cursor);
+  std::memcpy(buf, tr.data() + G->trace_cursor, n * sizeof(TraceRec));
+  G->trace_cursor += n;
+  return (int64_t)(n * sizeof(TraceRec));
+}
+
+int64_t daris_get_mret(daris_task t, int stage) {
+  daris_status st = check_task(t);
+  if (st != DARIS_OK) return st;
+  if (stage < 0 || stage >= G->core.n_stages(t)) return fail(DARIS_ERANGE, "stage %d out of range", stage);
+  std::lock_guard<std::mutex> lk(G->mu);
+  return G->core.mret_stage(t, stage);
+}
+
+// ---- direct execution ---------------------------------------------------------------------------------------------------
+
+static daris_status direct_checks(daris_task t, daris_part p) {
+  daris_status st = check_task(t);
+  if (st != DARIS_OK) return st;
+  st = check_part(p);
+  if (st != DARIS_OK) return st;
+  if (G->nodev) return fail(DARIS_ESTATE, "no device in DARIS_NO_DEVICE mode");
+  return make_streams();
+}
+
+daris_status daris_forward(daris_task t, const void* d_input, void* d_logits, daris_part p) {
+  daris_status st = direct_checks(t, p);
+  if (st != DARIS_OK) return st;
+  if (!d_input || !d_logits) return fail(DARIS_EINVAL, "NULL device buffer");
+  std::lock_guard<std::mutex> lk(G->mu);
+  if (G->core.has_active(t)) return fail(DARIS_ESTATE, "task %d has an active job", t);
+  TaskRt& T = *G->tasks[t];
+  hipStream_t s = G->parts[p].streams[0].s;
+  JobIo io;
+  io.in = d_input;
+  io.out = d_logits;
+  for (int j = 0; j < (int)T.net.stage_first.size(); ++j) HIP_TRY(launch_stage(T, j, io, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  return DARIS_OK;
+}
+
+daris_status daris_read_layer(daris_task t, int layer, float* host_out, int64_t cap_elems) {
+  daris_status st = check_task(t);
+  if (st != DARIS_OK) return st;
+  if (G->nodev) return fail(DARIS_ESTATE, "no device in DARIS_NO_DEVICE mode");
+  if (!(G->flags & DARIS_KEEP_ACTIVATIONS)) return fail(DARIS_ESTATE, "needs DARIS_KEEP_ACTIVATIONS");
+  TaskRt& T = *G->tasks[t];
+  if (layer < -1 || layer >= (int)T.net.layers.size()) return fail(DARIS_ERANGE, "layer %d out of range", layer);
+  const TensorInfo& o = T.net.tensor(layer + 1);
+  if (o.slot < 0) return fail(DARIS_ESTATE, "layer %d writes straight to the caller's logits", layer);
+  const int64_t n = (int64_t)o.C * o.H * o.W;
+  if (!host_out || cap_elems < n) return fail(DARIS_EINVAL, "host buffer too small (%lld needed)", (long long)n);
+  float* tmp = nullptr;
+  HIP_TRY(hipMalloc((void**)&tmp, (size_t)n * sizeof(float)));
+  hipError_t e = launch_egress(T.slots[o.slot], tmp, o.C, o.Cs, o.H, o.W, T.net.bf16, nullptr);
+  if (e == hipSuccess) e = hipMemcpy(host_out, tmp, (size_t)n * sizeof(float), hipMemcpyDeviceToHost);
+  (void)hipFree(tmp);
+  if (e != hipSuccess) return fail(DARIS_EHIP, "read_layer: %s", hipGetErrorString(e));
+  return DARIS_OK;
+}
+
+daris_status daris_profile_layers(daris_task t, daris_part p, int reps, float* ms_per_layer, int32_t* kernel_id, double* flops) {
+  daris_status st = direct_checks(t, p);
+  if (st != DARIS_OK) return st;
+  if (reps < 1 || !ms_per_layer) return fail(DARIS_EINVAL, "bad arguments");
+  std::lock_guard<std::mutex> lk(G->mu);
+  if (G->core.has_active(t)) return fail(DARIS_ESTATE, "task %d has an active job", t);
+  TaskRt& T = *G->tasks[t];
+  hipStream_t s = G->parts[p].streams[0].s;
+  const int n = (int)T.net.layers.size();
+  float* scratch_out = nullptr;
+  HIP_TRY(hipMalloc((void**)&scratch_out, (size_t)std::max(T.net.n_out, 4) * sizeof(float)));
+  hipEvent_t e0, e1;
+  HIP_TRY(hipEventCreate(&e0));
+  HIP_TRY(hipEventCreate(&e1));
+  daris_status result = DARIS_OK;
+  for (int l = 0; l < n && result == DARIS_OK; ++l) {
+    hipError_t e = launch_layer(T, l, scratch_out, s);  // warm-up
+    if (e == hipSuccess) e = hipEventRecord(e0, s);
+    for (int r = 0; r < reps && e == hipSuccess; ++r) e = launch_layer(T, l, scratch_out, s);
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (e != hipSuccess) result = fail(DARIS_EHIP, "profiling layer %d: %s", l, hipGetErrorString(e));
+    ms_per_layer[l] = ms / reps;
+    if (kernel_id) kernel_id[l] = T.net.layers[l].kernel_id;
+    if (flops) flops[l] = 2.0 * (double)T.net.layers[l].macs;
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  (void)hipFree(scratch_out);
+  return result;
+}
+
+const char* daris_kernel_name(int32_t kernel_id) { return kernel_name(kernel_id); }
+
+daris_status daris_probe_cus(daris_part p, int n_groups, int spin, uint32_t* out) {
+  daris_status st = check_part(p);
+  if (st != DARIS_OK) return st;
+  if (G->nodev) return fail(DARIS_ESTATE, "no device in DARIS_NO_DEVICE mode");
+  if (n_groups < 1 || n_groups > 65536 || spin < 0 || spin > 100000 || !out) return fail(DARIS_EINVAL, "bad arguments");
+  st = make_streams();
+  if (st != DARIS_OK) return st;
+  uint32_t* d = nullptr;
+  const size_t bytes = (size_t)n_groups * 2 * sizeof(uint32_t);
+  HIP_TRY(hipMalloc((void**)&d, bytes));
+  hipStream_t s = G->parts[p].streams[0].s;
+  hipError_t e = launch_cu_probe(d, n_groups, spin, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (e == hipSuccess) e = hipMemcpy(out, d, bytes, hipMemcpyDeviceToHost);
+  (void)hipFree(d);
+  if (e != hipSuccess) return fail(DARIS_EHIP, "probe: %s", hipGetErrorString(e));
+  return DARIS_OK;
+}
+
+daris_status daris_calibrate_afet(daris_task t, daris_part p, int reps) {
+  daris_status st = direct_checks(t, p);
+  if (st != DARIS_OK) return st;
+  if (reps < 1) return fail(DARIS_EINVAL, "reps must be >= 1");
+  std::lock_guard<std::mutex> lk(G->mu);
+  if (G->core.has_active(t) || G->core.stats(t).released > 0) return fail(DARIS_ESTATE, "calibrate before the first release of task %d", t);
+  TaskRt& T = *G->tasks[t];
+  hipStream_t s = G->parts[p].streams[0].s;
+  const int k = (int)T.net.stage_first.size();
+  float* in = nullptr;
+  float* out = nullptr;
+  const size_t in_elems = (size_t)T.net.in_c * T.net.in_h * T.net.in_w;
+  HIP_TRY(hipMalloc((void**)&in, in_elems * sizeof(float)));
+  HIP_TRY(hipMemset(in, 0, in_elems * sizeof(float)));
+  HIP_TRY(hipMalloc((void**)&out, (size_t)std::max(T.net.n_out, 4) * sizeof(float)));
+  JobIo io;
+  io.in = in;
+  io.out = out;
+  std::vector<int64_t> best(k, 0);
+  daris_status result = DARIS_OK;
+  for (int r = 0; r <= reps && result == DARIS_OK; ++r) {  // run 0 is a warm-up
+    for (int j = 0; j < k; ++j) {
+      auto t0 = std::chrono::steady_clock::now();
+      hipError_t e = launch_stage(T, j, io, s);
+      if (e == hipSuccess) e = hipStreamSynchronize(s);
+      auto t1 = std::chrono::steady_clock::now();
+      if (e != hipSuccess) {
+        result = fail(DARIS_EHIP, "calibration: %s", hipGetErrorString(e));
+        break;
+      }
+      const int64_t ns = std::chrono::duration_cast<std::chrono::nanoseconds>(t1 - t0).count();
+      if (r > 0) best[j] = std::max(best[j], ns);
+    }
+  }
+  (void)hipFree(in);
+  (void)hipFree(out);
+  if (result != DARIS_OK) return result;
+  for (int j = 0; j < k; ++j) G->core.set_afet(t, j, std::max<int64_t>(best[j], 1));
+  return DARIS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,80 @@
+// Launch interface between the host runtime and the HIP kernels (gfx950 only).
+//
+// Device tensor format: NHWC, element type float (fp32 tasks) or bfloat16 stored as uint16 (bf16 tasks),
+// channel stride Cs = channel count rounded up to one 16-byte vector (4 floats / 8 bf16); pad channels hold 0.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace daris {
+
+enum KernelId : int32_t {
+  K_NONE = 0,
+  K_CONV_F32_128x64, K_CONV_F32_64x64, K_CONV_F32_64x32, K_CONV_F32_32x64, K_CONV_F32_32x32,
+  K_CONV_BF16_128x64, K_CONV_BF16_64x64, K_CONV_BF16_64x32, K_CONV_BF16_32x64, K_CONV_BF16_32x32,
+  K_SPLITK_REDUCE, K_DWCONV, K_MAXPOOL, K_GAVGPOOL, K_FC, K_INGEST, K_EGRESS,
+  K_COUNT
+};
+const char* kernel_name(int32_t id);
+
+struct ConvArgs {
+  const void* x;      // [H][W][Cin]
+  const void* w;      // packed [Cout][Kpad], k = (ky*kw + kx)*Cin + ci, zero padded to Kpad
+  const float* bias;  // [Cout]
+  const void* res;    // [Ho*Wo][Cout] or nullptr
+  void* y;            // [Ho*Wo][Cout]
+  float* ws;          // split-K partial sums [splitk][M][Cout] (splitk > 1)
+  int H, W, Cin, Ho, Wo, Cout;
+  int kh, kw, stride, pad;
+  int K, Kpad, M;
+  int act;
+  int splitk;  // grid.z
+  int kchunk;  // k range per split, multiple of the kernel's BK
+};
+
+struct DwArgs {
+  const void* x;      // [H][W][C]
+  const void* w;      // [k*k][C]
+  const float* bias;  // [C]
+  void* y;            // [Ho][Wo][C]
+  int H, W, C, Ho, Wo, k, stride, pad, act;
+};
+
+struct PoolArgs {
+  const void* x;
+  void* y;
+  int H, W, C, Ho, Wo, k, stride, pad;
+};
+
+struct FcArgs {
+  const void* x;      // [K]
+  const void* w;      // [N][K]
+  const float* bias;  // [N]
+  void* y;            // [Ns], element type of the task, or float when out_f32; outputs N..Ns-1 are written as 0
+  int K, N, Ns, act, out_f32;
+};
+
+// Tile configuration chosen on the host for one dense convolution.
+struct ConvPlan {
+  int32_t kernel;  // KernelId
+  int bm, bn, bk, splitk, kchunk;
+  dim3 grid;
+  int threads;
+};
+// bf16 = 0/1.  Chooses tile shape and split-K from (M, N, K) only, so results do not depend on the partition.
+ConvPlan plan_conv(int M, int N, int Kpad, int bf16);
+
+hipError_t launch_conv(const ConvPlan& pl, const ConvArgs& a, int bf16, hipStream_t s);
+hipError_t launch_dwconv(const DwArgs& a, int bf16, hipStream_t s);
+hipError_t launch_maxpool(const PoolArgs& a, int bf16, hipStream_t s);
+hipError_t launch_gavgpool(const PoolArgs& a, int bf16, hipStream_t s);
+hipError_t launch_fc(const FcArgs& a, int bf16, hipStream_t s);
+// x: float [C][H][W] -> y: [H][W][Cs]
+hipError_t launch_ingest(const float* x, void* y, int C, int Cs, int H, int W, int bf16, hipStream_t s);
+// x: [H][W][Cs] -> y: float [C][H][W]
+hipError_t launch_egress(const void* x, float* y, int C, int Cs, int H, int W, int bf16, hipStream_t s);
+// Records, per workgroup, the XCC id and the hardware id register of the CU it ran on (mask probing).
+hipError_t launch_cu_probe(uint32_t* out, int n_groups, int spin, hipStream_t s);
+
+}  // namespace daris

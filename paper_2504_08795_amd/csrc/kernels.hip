@@ -1,0 +1,509 @@
+// HIP kernels of the DNN stages for gfx950 (CDNA4): implicit-GEMM convolution on MFMA with LDS-staged tiles
+// and a fused bias / residual / activation epilogue, split-K reduction, depthwise convolution, pooling, FC
+// (batch-1 GEMV), and the NCHW<->NHWC boundary conversions.  A DNN is, for the scheduler of the paper
+// (Sec. I, Sec. III-B1), a sequence of such kernels cut into stages.
+#include "kernels.h"
+
+namespace daris {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+// ---- element helpers ------------------------------------------------------------------------------------------
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+// float -> bfloat16 bits, round to nearest, ties to even; NaN stays a quiet NaN.
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+__device__ __forceinline__ float apply_act(float v, int act) {
+  if (act == 1) v = fmaxf(v, 0.f);
+  else if (act == 2) v = fminf(fmaxf(v, 0.f), 6.f);
+  return v;
+}
+
+template <bool BF16>
+__device__ __forceinline__ float load_elem(const void* p, size_t i) {
+  if (BF16) return bf16_bits_to_f32(((const uint16_t*)p)[i]);
+  return ((const float*)p)[i];
+}
+
+template <bool BF16>
+__device__ __forceinline__ void store_elem(void* p, size_t i, float v) {
+  if (BF16) ((uint16_t*)p)[i] = (uint16_t)f32_to_bf16_bits(v);
+  else ((float*)p)[i] = v;
+}
+
+// Unpack one 16-byte vector into VEC floats (4 for fp32, 8 for bf16).
+template <bool BF16>
+__device__ __forceinline__ void unpack(const uint4& v, float* o) {
+  if (BF16) {
+    o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xffff0000u);
+    o[2] = __uint_as_float(v.y << 16); o[3] = __uint_as_float(v.y & 0xffff0000u);
+    o[4] = __uint_as_float(v.z << 16); o[5] = __uint_as_float(v.z & 0xffff0000u);
+    o[6] = __uint_as_float(v.w << 16); o[7] = __uint_as_float(v.w & 0xffff0000u);
+  } else {
+    o[0] = __uint_as_float(v.x); o[1] = __uint_as_float(v.y); o[2] = __uint_as_float(v.z); o[3] = __uint_as_float(v.w);
+  }
+}
+
+template <bool BF16>
+__device__ __forceinline__ uint4 pack(const float* o) {
+  uint4 v;
+  if (BF16) {
+    v.x = f32_to_bf16_bits(o[0]) | (f32_to_bf16_bits(o[1]) << 16);
+    v.y = f32_to_bf16_bits(o[2]) | (f32_to_bf16_bits(o[3]) << 16);
+    v.z = f32_to_bf16_bits(o[4]) | (f32_to_bf16_bits(o[5]) << 16);
+    v.w = f32_to_bf16_bits(o[6]) | (f32_to_bf16_bits(o[7]) << 16);
+  } else {
+    v.x = __float_as_uint(o[0]); v.y = __float_as_uint(o[1]); v.z = __float_as_uint(o[2]); v.w = __float_as_uint(o[3]);
+  }
+  return v;
+}
+
+// ---- implicit-GEMM convolution ----------------------------------------------------------------------------------
+//
+// GEMM view (batch 1): Y[M = Ho*Wo][N = Cout] = A[M][K] * W^T, K = kh*kw*Cin with k = (ky*kw + kx)*Cin + ci.
+// A is never materialised: each 16-byte vector of a tile row is gathered from the NHWC input (Cin is a multiple
+// of the vector width, so a vector never straddles two filter taps).  Both tiles are staged in LDS with the K
+// dimension contiguous ("row = pixel or output channel, KV vectors of 16 bytes per row", row stride (KV+1)*16
+// bytes so that eight lanes reading 16 bytes each hit 32 distinct banks), double buffered, one barrier per
+// K step.  A wave owns a WM x WN block built from 32x32 MFMA tiles: rows of the MFMA A operand are pixels,
+// columns of the B operand are output channels, so that one accumulator register of all 32 lanes of a
+// half-wave is a contiguous 128-byte run of one output pixel.
+//   fp32 : v_mfma_f32_32x32x2_f32, four per 16-byte vector pair (lane half h, element s  <->  k = 4*(2q+h)+s);
+//   bf16 : v_mfma_f32_32x32x16_bf16, one per vector pair (lane half h, element e  <->  k = 8*(2q+h)+e).
+// The same k <-> (lane, element) map is used for both operands, which is all a dot product needs.
+template <bool BF16, int BM, int BN, int WM, int WN, int KV>
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void conv_igemm_kernel(const ConvArgs p) {
+  constexpr int ES = BF16 ? 2 : 4;
+  constexpr int VEC = 16 / ES;
+  constexpr int BK = KV * VEC;
+  constexpr int WAVES_N = BN / WN;
+  constexpr int NT = (BM / WM) * WAVES_N * 64;
+  constexpr int ROWB = (KV + 1) * 16;
+  constexpr int A_LD = BM * KV / NT, B_LD = BN * KV / NT;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  static_assert(BM * KV % NT == 0 && BN * KV % NT == 0 && NT % KV == 0 && KV % 2 == 0, "tile / thread mismatch");
+
+  __shared__ __attribute__((aligned(16))) unsigned char lds[2][(BM + BN) * ROWB];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+  const int kbeg = blockIdx.z * p.kchunk;
+  const int kend = min(kbeg + p.kchunk, p.Kpad);
+  const int nit = (kend - kbeg) / BK;
+
+  const unsigned char* xb = (const unsigned char*)p.x;
+  const unsigned char* wb = (const unsigned char*)p.w;
+
+  // --- per-thread gather state: all vectors of a thread share the k slot kv, rows differ -------------------------
+  const int kv = tid % KV;
+  int a_iy0[A_LD], a_ix0[A_LD];
+  bool a_ok[A_LD];
+#pragma unroll
+  for (int r = 0; r < A_LD; ++r) {
+    const int row = (tid + r * NT) / KV;
+    const int m = m0 + row;
+    a_ok[r] = m < p.M;
+    const int oy = m / p.Wo, ox = m - oy * p.Wo;
+    a_iy0[r] = oy * p.stride - p.pad;
+    a_ix0[r] = ox * p.stride - p.pad;
+  }
+  size_t b_off[B_LD];
+  bool b_ok[B_LD];
+#pragma unroll
+  for (int r = 0; r < B_LD; ++r) {
+    const int n = n0 + (tid + r * NT) / KV;
+    b_ok[r] = n < p.Cout;
+    b_off[r] = ((size_t)n * p.Kpad + kbeg + kv * VEC) * ES;
+  }
+  int kcur = kbeg + kv * VEC;
+  int tap = kcur / p.Cin;
+  int ci = kcur - tap * p.Cin;
+  int ky = tap / p.kw, kx = tap - ky * p.kw;
+
+  uint4 areg[A_LD], breg[B_LD];
+  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+
+  auto gload = [&]() {
+#pragma unroll
+    for (int r = 0; r < A_LD; ++r) {
+      const int iy = a_iy0[r] + ky, ix = a_ix0[r] + kx;
+      const bool ok = a_ok[r] && ky < p.kh && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
+      areg[r] = ok ? *(const uint4*)(xb + ((size_t)(iy * p.W + ix) * p.Cin + ci) * ES) : zero4;
+    }
+#pragma unroll
+    for (int r = 0; r < B_LD; ++r) {
+      breg[r] = b_ok[r] ? *(const uint4*)(wb + b_off[r]) : zero4;
+      b_off[r] += (size_t)BK * ES;
+    }
+    ci += BK;
+    while (ci >= p.Cin) {
+      ci -= p.Cin;
+      if (++kx == p.kw) { kx = 0; ++ky; }
+    }
+  };
+  auto lstore = [&](int buf) {
+#pragma unroll
+    for (int r = 0; r < A_LD; ++r) {
+      const int row = (tid + r * NT) / KV;
+      *(uint4*)(&lds[buf][row * ROWB + kv * 16]) = areg[r];
+    }
+#pragma unroll
+    for (int r = 0; r < B_LD; ++r) {
+      const int row = (tid + r * NT) / KV;
+      *(uint4*)(&lds[buf][(BM + row) * ROWB + kv * 16]) = breg[r];
+    }
+  };
+
+  const int wm = wave / WAVES_N, wn = wave - wm * WAVES_N;
+  const int li = lane & 31, lh = lane >> 5;
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  if (nit > 0) {
+    gload();
+    lstore(0);
+  }
+  __syncthreads();
+
+  for (int it = 0; it < nit; ++it) {
+    const int buf = it & 1;
+    if (it + 1 < nit) gload();
+    const unsigned char* As = &lds[buf][(wm * WM + li) * ROWB + lh * 16];
+    const unsigned char* Bs = &lds[buf][(BM + wn * WN + li) * ROWB + lh * 16];
+#pragma unroll
+    for (int q = 0; q < KV / 2; ++q) {
+      uint4 av[TM], bv[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) av[i] = *(const uint4*)(As + i * 32 * ROWB + q * 32);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) bv[j] = *(const uint4*)(Bs + j * 32 * ROWB + q * 32);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          if (BF16) {
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av[i]),
+                                                                __builtin_bit_cast(bf16x8, bv[j]), acc[i][j], 0, 0, 0);
+          } else {
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av[i].x), __uint_as_float(bv[j].x), acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av[i].y), __uint_as_float(bv[j].y), acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av[i].z), __uint_as_float(bv[j].z), acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av[i].w), __uint_as_float(bv[j].w), acc[i][j], 0, 0, 0);
+          }
+        }
+    }
+    if (it + 1 < nit) lstore(buf ^ 1);
+    __syncthreads();
+  }
+
+  // --- epilogue: accumulator register v of lane (li, lh) is row 8*(v/4) + 4*lh + (v%4), column li of a 32x32 tile -
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int n = n0 + wn * WN + j * 32 + li;
+    if (n >= p.Cout) continue;
+    const float bias = (p.splitk == 1) ? p.bias[n] : 0.f;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int m = m0 + wm * WM + i * 32 + (v >> 2) * 8 + lh * 4 + (v & 3);
+        if (m >= p.M) continue;
+        const size_t o = (size_t)m * p.Cout + n;
+        if (p.splitk == 1) {
+          float val = acc[i][j][v] + bias;
+          if (p.res) val += load_elem<BF16>(p.res, o);
+          store_elem<BF16>(p.y, o, apply_act(val, p.act));
+        } else {
+          p.ws[(size_t)blockIdx.z * p.M * p.Cout + o] = acc[i][j][v];
+        }
+      }
+    }
+  }
+}
+
+// Sums the split-K partials in split order and applies the fused epilogue.  One thread per 4 output channels.
+template <bool BF16>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ ws, const float* __restrict__ bias,
+                                                            const void* res, void* y, int M, int N, int splitk, int act) {
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t total4 = (size_t)M * N / 4;
+  if (idx >= total4) return;
+  const size_t o = idx * 4;
+  const int n = (int)(o % N);
+  float4 s = *(const float4*)(ws + o);
+  for (int z = 1; z < splitk; ++z) {
+    const float4 t = *(const float4*)(ws + (size_t)z * M * N + o);
+    s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+  }
+  const float4 b = *(const float4*)(bias + n);
+  float v[4] = {s.x + b.x, s.y + b.y, s.z + b.z, s.w + b.w};
+  if (res) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] += load_elem<BF16>(res, o + i);
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) v[i] = apply_act(v[i], act);
+  if (BF16) {
+    uint2 out;
+    out.x = f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16);
+    out.y = f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16);
+    *(uint2*)((uint16_t*)y + o) = out;
+  } else {
+    *(float4*)((float*)y + o) = make_float4(v[0], v[1], v[2], v[3]);
+  }
+}
+
+// ---- depthwise convolution: memory bound, one thread per (output pixel, 16-byte channel vector) -----------------------
+template <bool BF16>
+__global__ __launch_bounds__(256) void dwconv_kernel(const DwArgs a) {
+  constexpr int VEC = BF16 ? 8 : 4;
+  constexpr int ES = BF16 ? 2 : 4;
+  const int cvn = a.C / VEC;
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (size_t)a.Ho * a.Wo * cvn) return;
+  const int cv = (int)(idx % cvn);
+  const int m = (int)(idx / cvn);
+  const int oy = m / a.Wo, ox = m - oy * a.Wo;
+  const int c0 = cv * VEC;
+  float acc[VEC];
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) acc[i] = a.bias[c0 + i];
+  const unsigned char* xb = (const unsigned char*)a.x;
+  const unsigned char* wb = (const unsigned char*)a.w;
+  for (int ky = 0; ky < a.k; ++ky) {
+    const int iy = oy * a.stride + ky - a.pad;
+    if ((unsigned)iy >= (unsigned)a.H) continue;
+    for (int kx = 0; kx < a.k; ++kx) {
+      const int ix = ox * a.stride + kx - a.pad;
+      if ((unsigned)ix >= (unsigned)a.W) continue;
+      float xv[VEC], wv[VEC];
+      unpack<BF16>(*(const uint4*)(xb + ((size_t)(iy * a.W + ix) * a.C + c0) * ES), xv);
+      unpack<BF16>(*(const uint4*)(wb + ((size_t)(ky * a.k + kx) * a.C + c0) * ES), wv);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) acc[i] = fmaf(xv[i], wv[i], acc[i]);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) acc[i] = apply_act(acc[i], a.act);
+  *(uint4*)((unsigned char*)a.y + ((size_t)m * a.C + c0) * ES) = pack<BF16>(acc);
+}
+
+// ---- max pooling: padding acts as -inf --------------------------------------------------------------------------------
+template <bool BF16>
+__global__ __launch_bounds__(256) void maxpool_kernel(const PoolArgs a) {
+  constexpr int VEC = BF16 ? 8 : 4;
+  constexpr int ES = BF16 ? 2 : 4;
+  const int cvn = a.C / VEC;
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (size_t)a.Ho * a.Wo * cvn) return;
+  const int cv = (int)(idx % cvn);
+  const int m = (int)(idx / cvn);
+  const int oy = m / a.Wo, ox = m - oy * a.Wo;
+  const int c0 = cv * VEC;
+  float best[VEC];
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) best[i] = -INFINITY;
+  const unsigned char* xb = (const unsigned char*)a.x;
+  for (int ky = 0; ky < a.k; ++ky) {
+    const int iy = oy * a.stride + ky - a.pad;
+    if ((unsigned)iy >= (unsigned)a.H) continue;
+    for (int kx = 0; kx < a.k; ++kx) {
+      const int ix = ox * a.stride + kx - a.pad;
+      if ((unsigned)ix >= (unsigned)a.W) continue;
+      float xv[VEC];
+      unpack<BF16>(*(const uint4*)(xb + ((size_t)(iy * a.W + ix) * a.C + c0) * ES), xv);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) best[i] = fmaxf(best[i], xv[i]);
+    }
+  }
+  *(uint4*)((unsigned char*)a.y + ((size_t)m * a.C + c0) * ES) = pack<BF16>(best);
+}
+
+// ---- global average pooling: one thread per channel, coalesced across channels ---------------------------------------
+template <bool BF16>
+__global__ __launch_bounds__(256) void gavgpool_kernel(const PoolArgs a) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= a.C) return;
+  const int hw = a.H * a.W;
+  float s = 0.f;
+  for (int i = 0; i < hw; ++i) s += load_elem<BF16>(a.x, (size_t)i * a.C + c);
+  store_elem<BF16>(a.y, c, s / (float)hw);
+}
+
+// ---- FC, batch 1: one wave per output, 16-byte loads along K, butterfly reduction ------------------------------------
+template <bool BF16>
+__global__ __launch_bounds__(256) void fc_kernel(const FcArgs a) {
+  constexpr int VEC = BF16 ? 8 : 4;
+  constexpr int ES = BF16 ? 2 : 4;
+  const int lane = threadIdx.x & 63;
+  const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (n >= a.Ns) return;
+  if (n >= a.N) {  // pad element of the output vector
+    if (lane == 0) store_elem<BF16>(a.y, n, 0.f);
+    return;
+  }
+  const unsigned char* wrow = (const unsigned char*)a.w + (size_t)n * a.K * ES;
+  const unsigned char* xb = (const unsigned char*)a.x;
+  float acc = 0.f;
+  const int nvec = a.K / VEC;
+  for (int v = lane; v < nvec; v += 64) {
+    float wv[VEC], xv[VEC];
+    unpack<BF16>(*(const uint4*)(wrow + (size_t)v * 16), wv);
+    unpack<BF16>(*(const uint4*)(xb + (size_t)v * 16), xv);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc = fmaf(wv[i], xv[i], acc);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+  if (lane == 0) {
+    const float v = apply_act(acc + a.bias[n], a.act);
+    if (a.out_f32) ((float*)a.y)[n] = v;
+    else store_elem<BF16>(a.y, n, v);
+  }
+}
+
+// ---- boundary conversions ------------------------------------------------------------------------------------------------
+template <bool BF16>
+__global__ __launch_bounds__(256) void ingest_kernel(const float* __restrict__ x, void* y, int C, int Cs, int HW) {
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (size_t)HW * Cs) return;
+  const int c = (int)(idx % Cs);
+  const size_t px = idx / Cs;
+  store_elem<BF16>(y, idx, c < C ? x[(size_t)c * HW + px] : 0.f);
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void egress_kernel(const void* x, float* __restrict__ y, int C, int Cs, int HW) {
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (size_t)HW * C) return;
+  const int c = (int)(idx / HW);
+  const size_t px = idx % HW;
+  y[idx] = load_elem<BF16>(x, px * Cs + c);
+}
+
+// ---- CU mask probe: which XCC / CU did each workgroup run on ----------------------------------------------------------------
+__global__ __launch_bounds__(64) void cu_probe_kernel(uint32_t* out, int spin) {
+  uint32_t xcc, hwid;
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid));
+  // bounded busy wait so that the workgroups of one launch spread over every CU the mask allows
+  for (int i = 0; i < spin; ++i) __builtin_amdgcn_s_sleep(8);
+  if (threadIdx.x == 0) {
+    out[2 * blockIdx.x] = xcc;
+    out[2 * blockIdx.x + 1] = hwid;
+  }
+}
+
+// ---- host side -----------------------------------------------------------------------------------------------------------------
+
+static const char* const kNames[K_COUNT] = {
+    "none",
+    "conv_igemm_f32_128x64", "conv_igemm_f32_64x64", "conv_igemm_f32_64x32", "conv_igemm_f32_32x64", "conv_igemm_f32_32x32",
+    "conv_igemm_bf16_128x64", "conv_igemm_bf16_64x64", "conv_igemm_bf16_64x32", "conv_igemm_bf16_32x64", "conv_igemm_bf16_32x32",
+    "splitk_reduce", "dwconv", "maxpool", "gavgpool", "fc", "ingest", "egress"};
+
+const char* kernel_name(int32_t id) { return (id >= 0 && id < K_COUNT) ? kNames[id] : "?"; }
+
+static inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+ConvPlan plan_conv(int M, int N, int Kpad, int bf16) {
+  ConvPlan pl;
+  const int bk = bf16 ? 32 : 16;  // KV = 4 vectors of 16 bytes per tile row
+  pl.bk = bk;
+  const int blocks32 = cdiv(M, 32) * cdiv(N, 32);  // 32x32 MFMA tiles in the output
+  const int wave_slots = 512;                      // 128 CUs x 4 SIMDs: the nominal partition
+  int variant;                                     // 0: 128x64, 1: 64x64, 2: 64x32, 3: 32x64, 4: 32x32
+  if (blocks32 >= 4 * wave_slots && N >= 64) variant = 0;
+  else if (N <= 32) variant = (M > 32) ? 2 : 4;
+  else if (M <= 32) variant = 3;
+  else variant = 1;
+  static const int bm_[5] = {128, 64, 64, 32, 32}, bn_[5] = {64, 64, 32, 64, 32}, thr_[5] = {256, 256, 128, 128, 64};
+  pl.bm = bm_[variant];
+  pl.bn = bn_[variant];
+  pl.threads = thr_[variant];
+  pl.kernel = (bf16 ? K_CONV_BF16_128x64 : K_CONV_F32_128x64) + variant;
+  // split-K until the launch has about one wave per SIMD of the nominal partition
+  int splitk = 1;
+  if (variant != 0 && blocks32 < wave_slots) {
+    splitk = cdiv(wave_slots, blocks32);
+    const int max_by_k = Kpad / (4 * bk) > 0 ? Kpad / (4 * bk) : 1;  // at least four K steps per split
+    if (splitk > max_by_k) splitk = max_by_k;
+    if (splitk > 16) splitk = 16;
+  }
+  int kchunk = cdiv(cdiv(Kpad, splitk), bk) * bk;
+  splitk = cdiv(Kpad, kchunk);
+  pl.splitk = splitk;
+  pl.kchunk = kchunk;
+  pl.grid = dim3(cdiv(M, pl.bm), cdiv(N, pl.bn), splitk);
+  return pl;
+}
+
+template <bool BF16>
+static hipError_t launch_conv_t(const ConvPlan& pl, const ConvArgs& a, hipStream_t s) {
+  const int variant = pl.kernel - (BF16 ? K_CONV_BF16_128x64 : K_CONV_F32_128x64);
+  switch (variant) {
+    case 0: hipLaunchKernelGGL((conv_igemm_kernel<BF16, 128, 64, 64, 32, 4>), pl.grid, dim3(256), 0, s, a); break;
+    case 1: hipLaunchKernelGGL((conv_igemm_kernel<BF16, 64, 64, 32, 32, 4>), pl.grid, dim3(256), 0, s, a); break;
+    case 2: hipLaunchKernelGGL((conv_igemm_kernel<BF16, 64, 32, 32, 32, 4>), pl.grid, dim3(128), 0, s, a); break;
+    case 3: hipLaunchKernelGGL((conv_igemm_kernel<BF16, 32, 64, 32, 32, 4>), pl.grid, dim3(128), 0, s, a); break;
+    case 4: hipLaunchKernelGGL((conv_igemm_kernel<BF16, 32, 32, 32, 32, 4>), pl.grid, dim3(64), 0, s, a); break;
+    default: return hipErrorInvalidValue;
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (pl.splitk > 1) {
+    const size_t total4 = (size_t)a.M * a.Cout / 4;
+    hipLaunchKernelGGL((splitk_reduce_kernel<BF16>), dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, s, a.ws, a.bias,
+                       a.res, a.y, a.M, a.Cout, pl.splitk, a.act);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+hipError_t launch_conv(const ConvPlan& pl, const ConvArgs& a, int bf16, hipStream_t s) {
+  return bf16 ? launch_conv_t<true>(pl, a, s) : launch_conv_t<false>(pl, a, s);
+}
+
+#define DARIS_LAUNCH_1D(kern, total, ...)                                                                   \
+  do {                                                                                                      \
+    const size_t total_ = (total);                                                                          \
+    if (total_ == 0) return hipSuccess;                                                                     \
+    if (bf16) hipLaunchKernelGGL((kern<true>), dim3((unsigned)((total_ + 255) / 256)), dim3(256), 0, s, __VA_ARGS__); \
+    else hipLaunchKernelGGL((kern<false>), dim3((unsigned)((total_ + 255) / 256)), dim3(256), 0, s, __VA_ARGS__);     \
+    return hipGetLastError();                                                                               \
+  } while (0)
+
+hipError_t launch_dwconv(const DwArgs& a, int bf16, hipStream_t s) {
+  DARIS_LAUNCH_1D(dwconv_kernel, (size_t)a.Ho * a.Wo * (a.C / (bf16 ? 8 : 4)), a);
+}
+hipError_t launch_maxpool(const PoolArgs& a, int bf16, hipStream_t s) {
+  DARIS_LAUNCH_1D(maxpool_kernel, (size_t)a.Ho * a.Wo * (a.C / (bf16 ? 8 : 4)), a);
+}
+hipError_t launch_gavgpool(const PoolArgs& a, int bf16, hipStream_t s) { DARIS_LAUNCH_1D(gavgpool_kernel, (size_t)a.C, a); }
+hipError_t launch_fc(const FcArgs& a, int bf16, hipStream_t s) { DARIS_LAUNCH_1D(fc_kernel, (size_t)cdiv(a.Ns, 4) * 256, a); }
+hipError_t launch_ingest(const float* x, void* y, int C, int Cs, int H, int W, int bf16, hipStream_t s) {
+  DARIS_LAUNCH_1D(ingest_kernel, (size_t)H * W * Cs, x, y, C, Cs, H * W);
+}
+hipError_t launch_egress(const void* x, float* y, int C, int Cs, int H, int W, int bf16, hipStream_t s) {
+  DARIS_LAUNCH_1D(egress_kernel, (size_t)H * W * C, x, y, C, Cs, H * W);
+}
+hipError_t launch_cu_probe(uint32_t* out, int n_groups, int spin, hipStream_t s) {
+  hipLaunchKernelGGL(cu_probe_kernel, dim3(n_groups), dim3(64), 0, s, out, spin);
+  return hipGetLastError();
+}
+
+}  // namespace daris

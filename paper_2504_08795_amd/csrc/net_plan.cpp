@@ -1,0 +1,244 @@
+#include "net_plan.h"
+
+#include <algorithm>
+#include <cstring>
+#include <limits>
+
+namespace daris {
+
+static inline int round_up(int a, int b) { return (a + b - 1) / b * b; }
+
+uint16_t host_f32_to_bf16(float f) {
+  uint32_t u;
+  std::memcpy(&u, &f, 4);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // NaN
+  u += 0x7fffu + ((u >> 16) & 1u);                                           // nearest, ties to even
+  return (uint16_t)(u >> 16);
+}
+
+std::string build_plan(const daris_dnn& dnn, bool keep_activations, NetPlan* out) {
+  NetPlan& net = *out;
+  net = NetPlan();
+  if (dnn.n_layers < 1 || !dnn.layers) return "DNN has no layers";
+  if (dnn.in_c < 1 || dnn.in_h < 1 || dnn.in_w < 1) return "bad input shape";
+  if (dnn.dtype != DARIS_FP32 && dnn.dtype != DARIS_BF16) return "bad dtype";
+  net.bf16 = dnn.dtype == DARIS_BF16;
+  const int vec = net.bf16 ? 8 : 4, es = net.bf16 ? 2 : 4;
+  net.in_c = dnn.in_c;
+  net.in_h = dnn.in_h;
+  net.in_w = dnn.in_w;
+  net.ingest.C = dnn.in_c;
+  net.ingest.Cs = round_up(dnn.in_c, vec);
+  net.ingest.H = dnn.in_h;
+  net.ingest.W = dnn.in_w;
+  net.ingest.bytes = (size_t)net.ingest.H * net.ingest.W * net.ingest.Cs * es;
+  const int n = dnn.n_layers;
+  net.layers.resize(n);
+
+  for (int l = 0; l < n; ++l) {
+    LayerPlan& L = net.layers[l];
+    L.d = dnn.layers[l];
+    L.d.w = nullptr;
+    L.d.b = nullptr;
+    const daris_layer& d = L.d;
+    if (d.in_from < -1 || d.in_from >= l) return "layer " + std::to_string(l) + ": in_from must name an earlier layer or -1";
+    if (d.res_from < -1 || d.res_from >= l) return "layer " + std::to_string(l) + ": res_from must name an earlier layer or -1";
+    L.in_t = d.in_from + 1;
+    L.res_t = d.res_from < 0 ? -1 : d.res_from + 1;
+    const TensorInfo& in = net.tensor(L.in_t);
+    TensorInfo& o = L.out;
+    switch (d.op) {
+      case DARIS_OP_CONV: {
+        if (d.c_in != in.C) return "layer " + std::to_string(l) + ": c_in does not match its input";
+        if (d.k < 1 || d.stride < 1 || d.pad < 0 || d.c_out < 1) return "layer " + std::to_string(l) + ": bad conv geometry";
+        L.depthwise = d.groups != 1;
+        if (L.depthwise && !(d.groups == d.c_in && d.c_in == d.c_out))
+          return "layer " + std::to_string(l) + ": only dense (groups=1) and depthwise (groups=c_in=c_out) convolutions";
+        o.C = d.c_out;
+        o.Cs = round_up(d.c_out, vec);
+        o.H = (in.H + 2 * d.pad - d.k) / d.stride + 1;
+        o.W = (in.W + 2 * d.pad - d.k) / d.stride + 1;
+        if (o.H < 1 || o.W < 1) return "layer " + std::to_string(l) + ": empty output";
+        L.macs = (int64_t)o.H * o.W * d.c_out * (d.c_in / d.groups) * d.k * d.k;
+        if (!L.depthwise) {
+          L.K = d.k * d.k * in.Cs;
+          L.Kpad = round_up(L.K, 32);
+          L.cp = plan_conv(o.H * o.W, o.Cs, L.Kpad, net.bf16);
+          L.kernel_id = L.cp.kernel;
+          if (L.cp.splitk > 1)
+            net.ws_bytes = std::max(net.ws_bytes, (size_t)L.cp.splitk * o.H * o.W * o.Cs * sizeof(float));
+        } else {
+          L.kernel_id = K_DWCONV;
+        }
+        break;
+      }
+      case DARIS_OP_MAXPOOL:
+        if (d.k < 1 || d.stride < 1 || d.pad < 0 || 2 * d.pad > d.k) return "layer " + std::to_string(l) + ": bad pool geometry";
+        o.C = in.C;
+        o.Cs = in.Cs;
+        o.H = (in.H + 2 * d.pad - d.k) / d.stride + 1;
+        o.W = (in.W + 2 * d.pad - d.k) / d.stride + 1;
+        if (o.H < 1 || o.W < 1) return "layer " + std::to_string(l) + ": empty output";
+        L.kernel_id = K_MAXPOOL;
+        break;
+      case DARIS_OP_GAVGPOOL:
+        o.C = in.C;
+        o.Cs = in.Cs;
+        o.H = o.W = 1;
+        L.kernel_id = K_GAVGPOOL;
+        break;
+      case DARIS_OP_FC:
+        if (d.c_in != in.C * in.H * in.W) return "layer " + std::to_string(l) + ": FC c_in must equal C*H*W of its input";
+        if (d.c_out < 1) return "layer " + std::to_string(l) + ": bad FC size";
+        o.C = d.c_out;
+        o.Cs = round_up(d.c_out, vec);
+        o.H = o.W = 1;
+        L.macs = (int64_t)d.c_in * d.c_out;
+        L.K = in.H * in.W * in.Cs;
+        L.Kpad = L.K;
+        L.kernel_id = K_FC;
+        break;
+      default:
+        return "layer " + std::to_string(l) + ": unknown op";
+    }
+    if (d.act < DARIS_ACT_NONE || d.act > DARIS_ACT_RELU6) return "layer " + std::to_string(l) + ": unknown activation";
+    if (L.res_t >= 0) {
+      const TensorInfo& r = net.tensor(L.res_t);
+      if (d.op != DARIS_OP_CONV || L.depthwise) return "layer " + std::to_string(l) + ": residual only on dense convolutions";
+      if (r.C != o.C || r.H != o.H || r.W != o.W) return "layer " + std::to_string(l) + ": residual shape mismatch";
+    }
+    o.bytes = (size_t)o.H * o.W * o.Cs * es;
+  }
+  const TensorInfo& fin = net.layers[n - 1].out;
+  net.n_out = fin.C * fin.H * fin.W;
+  net.final_direct = net.layers[n - 1].d.op == DARIS_OP_FC;
+
+  // legal cuts: after layer l, when every later layer reads only tensors produced at or after l
+  for (int l = 0; l + 1 < n; ++l) {
+    bool ok = true;
+    for (int q = l + 1; q < n && ok; ++q) {
+      const daris_layer& d = net.layers[q].d;
+      if (d.in_from < l) ok = false;
+      if (d.res_from >= 0 && d.res_from < l) ok = false;
+    }
+    if (ok) net.legal_cuts.push_back(l);
+  }
+  net.stage_first.assign(1, 0);
+
+  // activation slots: a tensor's slot is free again once its last reader has been issued (same stream, in order)
+  std::vector<int> last_use(n + 1, -1);
+  for (int l = 0; l < n; ++l) {
+    last_use[net.layers[l].in_t] = std::max(last_use[net.layers[l].in_t], l);
+    if (net.layers[l].res_t >= 0) last_use[net.layers[l].res_t] = std::max(last_use[net.layers[l].res_t], l);
+  }
+  std::vector<int> slot_owner;  // tensor currently held by each slot, -1 = free
+  auto take_slot = [&](int tensor, size_t bytes) {
+    int s = -1;
+    if (!keep_activations)
+      for (size_t i = 0; i < slot_owner.size(); ++i)
+        if (slot_owner[i] < 0) { s = (int)i; break; }
+    if (s < 0) {
+      slot_owner.push_back(-1);
+      net.slot_bytes.push_back(0);
+      s = (int)slot_owner.size() - 1;
+    }
+    slot_owner[s] = tensor;
+    net.slot_bytes[s] = std::max(net.slot_bytes[s], bytes);
+    return s;
+  };
+  net.ingest.slot = take_slot(0, net.ingest.bytes);
+  for (int l = 0; l < n; ++l) {
+    for (size_t i = 0; i < slot_owner.size(); ++i)
+      if (slot_owner[i] >= 0 && last_use[slot_owner[i]] < l) slot_owner[i] = -1;
+    if (l == n - 1 && net.final_direct) break;  // logits go straight to the caller's buffer
+    net.layers[l].out.slot = take_slot(l + 1, net.layers[l].out.bytes);
+  }
+  return "";
+}
+
+bool split_stages(NetPlan* net, int k) {
+  const int n = (int)net->layers.size();
+  if (k < 1 || k - 1 > (int)net->legal_cuts.size()) return false;
+  std::vector<int64_t> pre(n + 1, 0);
+  for (int l = 0; l < n; ++l) pre[l + 1] = pre[l] + net->layers[l].macs;
+  auto sum = [&](int a, int b) { return pre[b + 1] - pre[a]; };  // layers a..b inclusive
+  const int64_t INF = std::numeric_limits<int64_t>::max();
+  std::vector<char> legal(n, 0);
+  for (int c : net->legal_cuts) legal[c] = 1;
+  // f[r][s]: least possible largest-stage MACs when layers s..n-1 form r stages
+  std::vector<std::vector<int64_t>> f(k + 1, std::vector<int64_t>(n + 1, INF));
+  for (int s = 0; s < n; ++s) f[1][s] = sum(s, n - 1);
+  for (int r = 2; r <= k; ++r)
+    for (int s = 0; s < n; ++s)
+      for (int c = s; c + 1 < n; ++c) {
+        if (!legal[c] || f[r - 1][c + 1] == INF) continue;
+        f[r][s] = std::min(f[r][s], std::max(sum(s, c), f[r - 1][c + 1]));
+      }
+  const int64_t best = f[k][0];
+  if (best == INF) return false;
+  std::vector<int> first(1, 0);
+  int pos = 0;
+  for (int r = k; r >= 2; --r) {
+    int chosen = -1;
+    for (int c = pos; c + 1 < n; ++c) {
+      if (!legal[c] || f[r - 1][c + 1] == INF) continue;
+      if (std::max(sum(pos, c), f[r - 1][c + 1]) <= best) { chosen = c; break; }
+    }
+    if (chosen < 0) return false;
+    pos = chosen + 1;
+    first.push_back(pos);
+  }
+  net->stage_first = first;
+  return true;
+}
+
+template <typename T>
+static void put(std::vector<unsigned char>* buf, size_t idx, float v, bool bf16) {
+  if (bf16) reinterpret_cast<uint16_t*>(buf->data())[idx] = host_f32_to_bf16(v);
+  else reinterpret_cast<float*>(buf->data())[idx] = v;
+}
+
+void pack_conv(const NetPlan& net, const LayerPlan& L, const float* w, const float* b, std::vector<unsigned char>* wp,
+               std::vector<float>* bp) {
+  const daris_layer& d = L.d;
+  const TensorInfo& in = net.tensor(L.in_t);
+  const bool bf = net.bf16;
+  const size_t es = bf ? 2 : 4;
+  const int kk = d.k * d.k;
+  bp->assign(L.out.Cs, 0.f);
+  if (b)
+    for (int o = 0; o < d.c_out; ++o) (*bp)[o] = b[o];
+  if (L.depthwise) {
+    // [tap][C]
+    wp->assign((size_t)kk * in.Cs * es, 0);
+    for (int c = 0; c < d.c_out; ++c)
+      for (int t = 0; t < kk; ++t) put<float>(wp, (size_t)t * in.Cs + c, w[(size_t)c * kk + t], bf);
+    return;
+  }
+  // [Cs_out][Kpad], k = tap * Cs_in + ci
+  wp->assign((size_t)L.out.Cs * L.Kpad * es, 0);
+  for (int o = 0; o < d.c_out; ++o)
+    for (int ci = 0; ci < d.c_in; ++ci)
+      for (int t = 0; t < kk; ++t)
+        put<float>(wp, (size_t)o * L.Kpad + (size_t)t * in.Cs + ci, w[((size_t)o * d.c_in + ci) * kk + t], bf);
+}
+
+void pack_fc(const NetPlan& net, const LayerPlan& L, const float* w, const float* b, std::vector<unsigned char>* wp,
+             std::vector<float>* bp) {
+  const daris_layer& d = L.d;
+  const TensorInfo& in = net.tensor(L.in_t);
+  const bool bf = net.bf16;
+  const size_t es = bf ? 2 : 4;
+  const int hw = in.H * in.W;
+  bp->assign(d.c_out, 0.f);
+  if (b)
+    for (int o = 0; o < d.c_out; ++o) (*bp)[o] = b[o];
+  // [N][H*W*Cs]: caller order is (c, y, x); device tensors are (y, x, c) with channel stride Cs
+  wp->assign((size_t)d.c_out * L.K * es, 0);
+  for (int o = 0; o < d.c_out; ++o)
+    for (int c = 0; c < in.C; ++c)
+      for (int px = 0; px < hw; ++px)
+        put<float>(wp, (size_t)o * L.K + (size_t)px * in.Cs + c, w[(size_t)o * d.c_in + (size_t)c * hw + px], bf);
+}
+
+}  // namespace daris

@@ -1,0 +1,240 @@
+"""CPU-only tests of the library's host logic through the C ABI (DARIS_NO_DEVICE | DARIS_VIRTUAL_TIME):
+exports, error behaviour, stage split and the scheduler trace against the oracle."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2504_08795_amd as D
+import workloads as wl
+from lib_helpers import Session, load_et, register_plain_tasks, run_commands
+from oracle import des, staging
+from sched_helpers import check_trace_invariants, load_golden, model_from_golden
+
+HOST = D.VIRTUAL_TIME | D.NO_DEVICE
+
+
+def test_library_exports_every_declared_symbol(repo_root):
+    hdr = open(os.path.join(repo_root, "include", "daris.h")).read()
+    declared = set(re.findall(r"\b(daris_[a-z_0-9]+)\s*\(", hdr))
+    assert declared, "no declarations found"
+    lib = ctypes.CDLL(D.binding.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"{name} declared in daris.h but not exported"
+    assert declared == set(D.binding.EXPORTS), declared ^ set(D.binding.EXPORTS)
+
+
+def test_trace_record_is_32_bytes():
+    assert D.binding.TRACE_DTYPE.itemsize == 32
+
+
+def test_cu_per_partition_formula():
+    assert D.daris_cu_per_partition(3, 2, 256, 3) == 128 and D.daris_cu_per_partition(2, 1, 256, 4) == 128
+    assert [D.daris_cu_per_partition(n, 2, 256, 4) for n in (2, 3, 4, 5)] == [64, 96, 128, 160]
+    for num, den, nmax, nc in [(1, 1, 68, 3), (3, 2, 68, 4), (7, 3, 255, 5), (6, 1, 68, 6), (1, 1, 1, 1)]:
+        assert D.daris_cu_per_partition(num, den, nmax, nc) == des.partition_cus(num, den, nmax, nc)
+    with pytest.raises(D.DarisError):
+        D.daris_cu_per_partition(0, 1, 256, 4)
+
+
+def test_error_paths():
+    with pytest.raises(D.DarisError) as e:
+        D.daris_create_partition(8)                      # not initialised
+    assert e.value.code == D.ESTATE
+    with pytest.raises(D.DarisError):
+        D.daris_init(0, 0, D.NO_DEVICE)                  # NO_DEVICE needs VIRTUAL_TIME
+    with Session(HOST):
+        with pytest.raises(D.DarisError) as e:
+            D.daris_init(0, 0, HOST)
+        assert e.value.code == D.ESTATE
+        for bad in (0, 257, -3):
+            with pytest.raises(D.DarisError) as e:
+                D.daris_create_partition(bad)
+            assert e.value.code == D.EINVAL
+        p = D.daris_create_partition(256)
+        with pytest.raises(D.DarisError):
+            D.daris_partition_set_streams(p, 0)
+        with pytest.raises(D.DarisError) as e:
+            D.daris_partition_set_streams(p + 1, 1)
+        assert e.value.code == D.ERANGE
+        layers, shp = wl.build_net("tiny")
+        dnn, keep = D.make_dnn(layers, None, shp, "fp32")
+        with pytest.raises(D.DarisError):
+            D.daris_register_task(dnn, 0, 10, D.HP)      # period must be positive
+        with pytest.raises(D.DarisError):
+            D.daris_register_task(dnn, 10, 10, 7)        # priority
+        t = D.daris_register_task(dnn, 10_000_000, 10_000_000, D.HP)
+        with pytest.raises(D.DarisError) as e:
+            D.daris_split_stages(t, 99)
+        assert e.value.code == D.ERANGE
+        with pytest.raises(D.DarisError) as e:
+            D.daris_split_stages(t + 5, 2)
+        assert e.value.code == D.ERANGE
+        with pytest.raises(D.DarisError):
+            D.daris_set_afet(t, 3, 100)
+        with pytest.raises(D.DarisError):
+            D.daris_set_afet(t, 0, 0)
+        # malformed networks
+        N = wl.nets
+        bad = [N.Layer(op=N.OP_CONV, c_in=5, c_out=8, k=3, pad=1, in_from=-1)]
+        dnn2, keep2 = D.make_dnn(bad, None, (3, 8, 8), "fp32")
+        with pytest.raises(D.DarisError) as e:
+            D.daris_register_task(dnn2, 10, 10, D.LP)    # c_in mismatch
+        assert e.value.code == D.EINVAL
+        bad = [N.Layer(op=N.OP_CONV, c_in=3, c_out=8, k=3, pad=1, in_from=0)]
+        dnn3, keep3 = D.make_dnn(bad, None, (3, 8, 8), "fp32")
+        with pytest.raises(D.DarisError):
+            D.daris_register_task(dnn3, 10, 10, D.LP)    # reads itself
+        # virtual time: a release without a table is an error, and time cannot go back
+        D.daris_split_stages(t, 2)
+        D.daris_release_job(t, None, None, 100)
+        with pytest.raises(D.DarisError):
+            D.daris_release_job(t, None, None, 50)
+        with pytest.raises(D.DarisError):
+            D.daris_run_until_idle()                     # no execution-time table
+    with pytest.raises(D.DarisError):
+        D.daris_shutdown()
+
+
+def test_partition_masks_follow_cyclic_rule():
+    with Session(HOST):
+        ps = [D.daris_create_partition(n) for n in (96, 96, 128, 192)]
+        masks = [D.daris_partition_get_mask(p) for p in ps]
+        cover = np.zeros(256, int)
+        start = 0
+        for n, m in zip((96, 96, 128, 192), masks):
+            bits = np.array([(m[i // 32] >> (i % 32)) & 1 for i in range(256)])
+            assert bits.sum() == n
+            want = np.zeros(256, int)
+            want[[(start + i) % 256 for i in range(n)]] = 1
+            assert (bits == want).all()
+            cover += bits
+            start = (start + n) % 256
+        assert (cover == 2).all()        # 512 CUs over 256: every CU shared by exactly two partitions
+    with Session(HOST):
+        masks = [D.daris_partition_get_mask(D.daris_create_partition(128)) for _ in range(3)]
+        cover = sum(np.array([(m[i // 32] >> (i % 32)) & 1 for i in range(256)]) for m in masks)
+        assert sorted(set(cover)) == [1, 2]
+
+
+@pytest.mark.parametrize("net,ks", [("tiny", (1, 2, 3, 4)), ("resnet18", (1, 2, 3, 4, 6)), ("resnet50", (1, 4, 5)),
+                                    ("vgg16", (1, 3, 4)), ("mobilenet_v2", (1, 3, 4))])
+def test_stage_split_matches_oracle(net, ks):
+    layers, shp = wl.build_net(net)
+    macs = wl.net_macs(layers, shp)
+    legal = staging.legal_cuts(layers)
+    with Session(HOST):
+        D.daris_create_partition(64)
+        dnn, keep = D.make_dnn(layers, None, shp, "fp32")
+        t = D.daris_register_task(dnn, 10**7, 10**7, D.LP)
+        assert D.daris_get_stage_cuts(t) == [0]
+        for k in ks:
+            D.daris_split_stages(t, k)
+            assert D.daris_get_stage_cuts(t) == staging.split(macs, legal, k), (net, k)
+        with pytest.raises(D.DarisError):
+            D.daris_split_stages(t, len(legal) + 2)
+
+
+def test_stage_split_known_results():
+    """Per-stage MAC totals at the benchmark configurations (integers from the layer tables)."""
+    def stage_macs(net, k):
+        layers, shp = wl.build_net(net)
+        macs = wl.net_macs(layers, shp)
+        first = staging.split(macs, staging.legal_cuts(layers), k) + [len(layers)]
+        return [sum(macs[a:b]) for a, b in zip(first, first[1:])], first
+    m, first = stage_macs("tiny", 2)
+    assert m == [5_160_960, 7_118_848]
+    m, first = stage_macs("resnet18", 3)
+    assert sum(m) == 1_814_073_344 and max(m) < 650_000_000
+    # a residual block is never cut in the middle: every stage starts at a block boundary (or the stem pool)
+    layers, _ = wl.build_net("resnet18")
+    for f in first[1:-1]:
+        assert layers[f].name.endswith((".ds", ".c1")) or layers[f].name in ("stem.pool", "gap", "fc")
+
+
+@pytest.mark.parametrize("name", ["sched_single_task.json", "sched_hp_preempts_lp.json", "sched_admission_migration.json"])
+def test_library_reproduces_golden_traces(name):
+    g, cmds, et, want = load_golden(name)
+    with Session(HOST):
+        register_plain_tasks(g["partitions"], g["tasks"])
+        load_et(et, len(g["partitions"]))
+        run_commands(cmds)
+        got = D.trace_read_all()
+    for a, b in zip(got, want):
+        assert a == b, f"first difference at seq {a[0]}: got {a}, want {b}"
+    assert len(got) == len(want)
+
+
+def _oracle_and_library(ts, et, afet, flags=0, n_streams=None, migrations=()):
+    n_streams = n_streams or [1] * len(ts.partitions)
+    tasks = [des.TaskParam(t.period_ns, t.deadline_ns, t.priority, list(afet[i])) for i, t in enumerate(ts.tasks)]
+    cmds = [("release", t, i) for t, i, _ in ts.releases()] + list(migrations)
+    cmds.sort(key=lambda c: c[1])
+    oflags = 0
+    for lf, of in ((D.NO_LAST, des.F_NO_LAST), (D.NO_PRIOR, des.F_NO_PRIOR), (D.NO_FIXED, des.F_NO_FIXED), (D.HP_ADMISSION, des.F_HP_ADMISSION)):
+        if flags & lf:
+            oflags |= of
+    m = des.SchedulerModel(n_streams, tasks, flags=oflags)
+    want = des.run_virtual(m, cmds, et)
+    with Session(HOST | flags):
+        register_plain_tasks(n_streams, [dict(period=t.period, deadline=t.deadline, prio=t.prio, afet=t.afet) for t in tasks])
+        load_et(et, len(n_streams))
+        dec = run_commands(cmds)
+        got = D.trace_read_all()
+        stats = [D.daris_get_stats(i) for i in range(len(tasks))]
+    return m, want, got, stats, dec
+
+
+@pytest.mark.parametrize("config,load,flags,ns", [
+    (1, 300.0, 0, 1), (2, 25.0, 0, 1), (3, 18.0, 0, 1), (4, 22.0, 0, 1), (2, 30.0, 0, 2), (3, 14.0, D.NO_LAST, 1), (2, 25.0, D.NO_PRIOR, 1),
+    (4, 22.0, D.NO_FIXED, 1), (2, 45.0, D.HP_ADMISSION, 1), (5, 12.0, 0, 1)])
+def test_trace_bit_exact_against_oracle(config, load, flags, ns):
+    ts = wl.make_taskset(config, n_jobs=80 if config != 5 else 40)
+    et = wl.virtual_et_table(ts, load_scale=load)
+    afet = [[int(np.mean(et[i][j][0][:8])) for j in range(t.n_stages)] for i, t in enumerate(ts.tasks)]
+    rel = ts.releases()
+    mig = [("migrate", rel[n][0], (n // 7) % len(ts.tasks), (n // 3) % len(ts.partitions)) for n in range(25, len(rel), 61)]
+    m, want, got, stats, dec = _oracle_and_library(ts, et, afet, flags, [ns] * len(ts.partitions), mig)
+    for a, b in zip(got, want):
+        assert a == b, f"first difference at seq {a[0]}: library {a}, oracle {b}"
+    assert len(got) == len(want) and len(got) > 100
+    check_trace_invariants(got, m.n_streams, [t.p.prio for t in m.tasks], [len(t.p.afet) for t in m.tasks],
+                           flags=m.flags)
+    for s, o in zip(stats, m.stats()):
+        assert (s["released"], s["accepted"], s["completed"], s["missed"], s["rejected_admission"], s["rejected_overrun"]) == \
+               (o["released"], o["accepted"], o["completed"], o["missed"], o["rejected_admission"], o["rejected_overrun"])
+        if o["responses"]:
+            assert (s["resp_min_ns"], s["resp_max_ns"], s["resp_sum_ns"]) == (min(o["responses"]), max(o["responses"]), sum(o["responses"]))
+        assert s["partition"] == o["ctx"]
+
+
+def test_run_periodic_equals_explicit_releases():
+    ts = wl.make_taskset(2, n_jobs=30)
+    et = wl.virtual_et_table(ts, load_scale=25.0)
+    afet = [[int(np.mean(et[i][j][0][:8])) for j in range(t.n_stages)] for i, t in enumerate(ts.tasks)]
+    m, want, got, stats, dec = _oracle_and_library(ts, et, afet)
+    with Session(HOST):
+        register_plain_tasks([1] * 3, [dict(period=t.period_ns, deadline=t.deadline_ns, prio=t.priority, afet=afet[i]) for i, t in enumerate(ts.tasks)])
+        load_et(et, 3)
+        for i in range(len(ts.tasks)):
+            D.daris_task_set_io(i, None, 4, None, 4)
+        D.daris_run_periodic(None, [30] * len(ts.tasks))
+        got2 = D.trace_read_all()
+    assert got2 == got == want
+
+
+def test_mret_accessor_and_window():
+    with Session(HOST):
+        register_plain_tasks([1], [dict(period=1000, deadline=1000, prio=D.LP, afet=[50])])
+        D.daris_set_window(3)
+        vals = [10, 90, 20, 20, 20, 20]
+        D.daris_set_virtual_time(0, 0, 0, 0, len(vals), np.array(vals))
+        assert D.daris_get_mret(0, 0) == 50          # AFET until the stage has run
+        seen = []
+        for m in range(len(vals)):
+            D.daris_release_job(0, None, None, m * 1000)
+            D.daris_run_until_idle()
+            seen.append(D.daris_get_mret(0, 0))
+        assert seen == [10, 90, 90, 90, 20, 20]      # window of 3 executions

@@ -194,7 +194,7 @@ def test_dispatch_choice_bruteforce_small():
 
 
 # ---- large seeded runs: invariants + qualitative direction ---------------------------------------------------
-@pytest.mark.parametrize("config,load", [(2, 12.0), (3, 6.0), (4, 3.0)])
+@pytest.mark.parametrize("config,load", [(2, 25.0), (3, 18.0), (4, 22.0)])
 def test_invariants_on_benchmark_shaped_sets(config, load):
     ts = wl.make_taskset(config, n_jobs=60)
     et = wl.virtual_et_table(ts, load_scale=load)
