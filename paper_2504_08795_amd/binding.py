@@ -89,6 +89,9 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise DarisError(ESTATE, f"{LIB_PATH} not built: run `python -m paper_2504_08795_amd.build`")
+        # PyTorch owns the device memory the caller passes in, so both must use ONE HIP runtime: import torch first,
+        # then libdaris.so binds to the libamdhip64.so.7 that torch has already mapped into the process.
+        import torch  # noqa: F401
         _lib = C.CDLL(LIB_PATH)
         for name, (res, args) in _SIGS.items():
             f = getattr(_lib, name)

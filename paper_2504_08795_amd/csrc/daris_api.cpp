@@ -294,8 +294,11 @@ void sched_loop() {
         S.busy = false;
         S.task = -1;
         const uint32_t job = G->core.active_job(task);
-        if (G->core.stage_done(now, task)) {
-          T.io.erase(job);
+        const bool job_done = G->core.stage_done(now, task);
+        if (job_done) T.io.erase(job);
+        // a dispatch pass follows every input event (completion, release, migration command)
+        if (dispatch_and_issue(now) != DARIS_OK && G->async_error.empty()) G->async_error = tl_error;
+        if (job_done) {
           // closed loop: the next job of the task is released the instant this one ends
           while (T.closed_left > 0 && !G->core.has_active(task)) {
             T.closed_left--;
@@ -305,7 +308,6 @@ void sched_loop() {
               G->async_error = tl_error;
           }
         }
-        if (dispatch_and_issue(now) != DARIS_OK && G->async_error.empty()) G->async_error = tl_error;
         if (G->core.idle()) G->cv_idle.notify_all();
       }
     }

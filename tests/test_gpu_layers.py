@@ -1,0 +1,128 @@
+"""GPU parity of every kernel against the CPU oracle, one or two layers at a time, through the C ABI.
+Shapes span several tiles, ragged M / N / K tails, split-K, both strides and both arithmetic types."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from gpu_helpers import GpuNet, oracle_logits, rel_err
+
+pytestmark = pytest.mark.gpu
+N = wl.nets
+RNG = np.random.default_rng(99)
+
+# per-layer bars, far inside the whole-network tolerances: fp32 accumulation over K <= 4608 terms versus a double sum
+# (~sqrt(K) * 2^-24 relative to the row norm), bf16 one final rounding (2^-9) on top
+LAYER_TOL = {"fp32": 2e-5, "bf16": 6e-3}
+
+
+def rand_w(L, scale=None):
+    cg = L.c_in // L.groups
+    if L.op == N.OP_CONV:
+        w = RNG.normal(0, np.sqrt(2.0 / (cg * L.k * L.k)), (L.c_out, cg, L.k, L.k))
+    else:
+        w = RNG.normal(0, np.sqrt(2.0 / L.c_in), (L.c_out, L.c_in))
+    return w.astype(np.float32), RNG.normal(0, 0.3, L.c_out).astype(np.float32)
+
+
+def run_case(layers, shp, dtype, tol=None):
+    weights = [rand_w(L) if L.op in (N.OP_CONV, N.OP_FC) else (None, None) for L in layers]
+    x = RNG.normal(0, 1, shp).astype(np.float32)
+    want = oracle_logits(layers, weights, x, dtype)
+    with GpuNet(layers, weights, shp, dtype) as net:
+        got = net.forward(x)
+    e_max, e_l2 = rel_err(got, want)
+    tol = tol or LAYER_TOL[dtype]
+    assert e_max <= tol and e_l2 <= tol, (e_max, e_l2)
+    return got, want
+
+
+CONV_CASES = [
+    # (cin, h, w, cout, k, s, p, act)  -- comment: what it stresses
+    (3, 32, 32, 16, 3, 1, 1, 1),      # Tiny c1: padded 3-channel input, N = 16 < tile
+    (16, 32, 32, 32, 3, 1, 1, 1),     # Tiny c2
+    (32, 16, 16, 64, 3, 1, 1, 1),     # Tiny c4
+    (3, 64, 64, 64, 7, 2, 3, 1),      # stem 7x7 s2 (quarter-size image)
+    (64, 28, 28, 64, 3, 1, 1, 1),     # layer1-like, M = 784
+    (64, 29, 27, 128, 3, 2, 1, 1),    # stride 2, odd sizes, ragged M
+    (64, 28, 28, 128, 1, 2, 0, 0),    # 1x1 s2 downsample, no activation
+    (128, 14, 14, 256, 3, 1, 1, 1),   # M = 196 -> split-K
+    (512, 7, 7, 512, 3, 1, 1, 1),     # M = 49, K = 4608 -> deep split-K
+    (256, 7, 7, 1024, 1, 1, 0, 1),    # 1x1 wide N
+    (24, 13, 13, 40, 1, 1, 0, 2),     # ragged everything, ReLU6
+    (40, 9, 11, 24, 3, 1, 1, 0),      # K = 360: K tail inside a tile
+    (8, 5, 5, 8, 3, 1, 1, 1),         # smaller than any tile
+    (32, 56, 56, 64, 3, 1, 1, 1),     # M = 3136: many M tiles
+    (16, 112, 112, 96, 1, 1, 0, 2),   # MobileNet expand: M = 12544, largest tile variant
+]
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("case", CONV_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_conv(case, dtype):
+    cin, h, w, cout, k, s, p, act = case
+    layers = [N.Layer(op=N.OP_CONV, c_in=cin, c_out=cout, k=k, stride=s, pad=p, act=act, in_from=-1)]
+    run_case(layers, (cin, h, w), dtype)
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("cin,hw,cout,s", [(64, 28, 128, 2), (64, 14, 64, 1), (256, 7, 512, 2)])
+def test_conv_residual_block(cin, hw, cout, s, dtype):
+    """downsample 1x1 (or identity) + 3x3 + 3x3 with residual add before ReLU: the basic-block epilogue."""
+    layers = []
+    if s != 1 or cin != cout:
+        layers.append(N.Layer(op=N.OP_CONV, c_in=cin, c_out=cout, k=1, stride=s, pad=0, act=0, in_from=-1))
+        skip, base = 0, 1
+    else:
+        layers.append(N.Layer(op=N.OP_MAXPOOL, c_in=cin, c_out=cin, k=1, stride=1, pad=0, in_from=-1))   # identity copy as tensor 0
+        skip, base = 0, 1
+    layers.append(N.Layer(op=N.OP_CONV, c_in=cin, c_out=cout, k=3, stride=s, pad=1, act=1, in_from=-1))
+    layers.append(N.Layer(op=N.OP_CONV, c_in=cout, c_out=cout, k=3, stride=1, pad=1, act=1, in_from=base, res_from=skip))
+    run_case(layers, (cin, hw, hw), dtype, tol={"fp32": 5e-5, "bf16": 1.2e-2}[dtype])
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("c,h,w,s", [(32, 112, 112, 1), (96, 57, 55, 2), (144, 28, 28, 1), (960, 7, 7, 1), (24, 9, 9, 2)])
+def test_depthwise(c, h, w, s, dtype):
+    layers = [N.Layer(op=N.OP_CONV, c_in=c, c_out=c, k=3, stride=s, pad=1, groups=c, act=2, in_from=-1)]
+    run_case(layers, (c, h, w), dtype)
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("c,h,w,k,s,p", [(64, 112, 112, 3, 2, 1), (32, 32, 32, 2, 2, 0), (3, 9, 7, 3, 2, 1), (16, 15, 15, 2, 2, 0)])
+def test_maxpool(c, h, w, k, s, p, dtype):
+    layers = [N.Layer(op=N.OP_MAXPOOL, c_in=c, c_out=c, k=k, stride=s, pad=p, in_from=-1)]
+    weights = [(None, None)]
+    x = (-np.abs(RNG.normal(0, 1, (c, h, w))) - 0.5).astype(np.float32)       # all negative: padding must not win
+    want = oracle_logits(layers, weights, x, dtype)
+    with GpuNet(layers, weights, (c, h, w), dtype) as net:
+        got = net.forward(x)
+    np.testing.assert_array_equal(got, want)                                  # selection only: bit exact
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("c,h,w", [(512, 7, 7), (1280, 7, 7), (20, 3, 5)])
+def test_gavgpool(c, h, w, dtype):
+    layers = [N.Layer(op=N.OP_GAVGPOOL, c_in=c, c_out=c, in_from=-1)]
+    run_case(layers, (c, h, w), dtype, tol={"fp32": 1e-6, "bf16": 4e-3}[dtype])
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("c,h,w,n,act", [(64, 8, 8, 10, 0), (512, 1, 1, 1000, 0), (32, 7, 7, 4096, 1), (3, 5, 5, 7, 0)])
+def test_fc(c, h, w, n, act, dtype):
+    layers = [N.Layer(op=N.OP_FC, c_in=c * h * w, c_out=n, act=act, in_from=-1)]
+    run_case(layers, (c, h, w), dtype)
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_fc_chain_with_padded_vector(dtype):
+    """FC -> FC where the intermediate vector length (10) is not a multiple of the 16-byte vector."""
+    layers = [N.Layer(op=N.OP_FC, c_in=16 * 4 * 4, c_out=10, act=1, in_from=-1), N.Layer(op=N.OP_FC, c_in=10, c_out=6, in_from=0)]
+    run_case(layers, (16, 4, 4), dtype, tol={"fp32": 2e-5, "bf16": 1e-2}[dtype])
+
+
+def test_identity_passthrough_is_exact():
+    """ingest + 1x1 max-pool + egress moves every value unchanged (layout conversions only)."""
+    layers = [N.Layer(op=N.OP_MAXPOOL, c_in=5, c_out=5, k=1, stride=1, pad=0, in_from=-1)]
+    x = RNG.normal(0, 1, (5, 6, 7)).astype(np.float32)
+    with GpuNet(layers, [(None, None)], (5, 6, 7), "fp32") as net:
+        np.testing.assert_array_equal(net.forward(x), x.reshape(-1))

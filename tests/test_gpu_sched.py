@@ -1,0 +1,174 @@
+"""The whole hot path on the GPU: periodic task sets released through the scheduler on CU-masked streams.
+Virtual-time mode: trace bit-exact against the oracle's event model AND every job's logits against the oracle.
+Real-time mode: the recorded trace is replayed through the oracle, which must reproduce every decision."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2504_08795_amd as D
+import workloads as wl
+from gpu_helpers import TOL, rel_err
+from lib_helpers import load_et
+from oracle import des
+from oracle import forward as F
+from sched_helpers import check_trace_invariants
+
+pytestmark = pytest.mark.gpu
+
+
+class GpuTaskSet:
+    def __init__(self, ts, flags=0, afet=None):
+        self.ts = ts
+        D.daris_init(0, wl.tasksets.SEED, flags)
+        for n in ts.partitions:
+            D.daris_create_partition(n)
+        self.keep, self.inputs, self.logits, self.want = [], [], [], []
+        self.nets = []
+        for i, t in enumerate(ts.tasks):
+            layers, shp = wl.build_net(t.net)
+            weights = wl.make_weights(layers, t.seed)
+            dnn, keep = D.make_dnn(layers, weights, shp, t.dtype)
+            self.keep.append(keep)
+            h = D.daris_register_task(dnn, t.period_ns, t.deadline_ns, t.priority)
+            assert h == i
+            D.daris_split_stages(h, t.n_stages)
+            xs = wl.make_inputs(shp, t.seed, ts.n_inputs, t.input_dist)
+            self.nets.append((layers, weights, xs, t.dtype))
+            n_out = layers[-1].c_out
+            self.inputs.append(torch.from_numpy(xs).cuda())
+            self.logits.append(torch.full((ts.n_jobs, n_out), float("nan"), dtype=torch.float32, device="cuda"))
+            D.daris_task_set_io(h, self.inputs[i], ts.n_inputs, self.logits[i], ts.n_jobs)
+            if afet is not None:
+                for j, a in enumerate(afet[i]):
+                    D.daris_set_afet(h, j, a)
+
+    def oracle_logits(self):
+        if not self.want:
+            for layers, weights, xs, dtype in self.nets:
+                self.want.append([F.forward(layers, weights, x, dtype) for x in xs])
+        return self.want
+
+    def check_logits(self, trace):
+        """Every completed job's logits row against the oracle entry of the input it used."""
+        want = self.oracle_logits()
+        done = [(r[6], r[8]) for r in trace if r[2] == des.JOB_DONE]
+        assert done
+        worst = 0.0
+        outs = [l.cpu().numpy() for l in self.logits]
+        for task, job in done:
+            dtype = self.ts.tasks[task].dtype
+            e_max, e_l2 = rel_err(outs[task][job], want[task][job % self.ts.n_inputs])
+            worst = max(worst, e_max)
+            assert e_max <= TOL[dtype] and e_l2 <= TOL[dtype], (task, job, e_max, e_l2)
+        # rows of rejected jobs were never written
+        rejected = [(r[6], r[8]) for r in trace if r[2] == des.REJECT]
+        for task, job in rejected:
+            assert np.isnan(outs[task][job]).all()
+        return worst, len(done)
+
+    def close(self):
+        D.daris_shutdown()
+
+
+def oracle_model(ts, afet, n_streams=None):
+    tasks = [des.TaskParam(t.period_ns, t.deadline_ns, t.priority, list(afet[i])) for i, t in enumerate(ts.tasks)]
+    return des.SchedulerModel(n_streams or [1] * len(ts.partitions), tasks)
+
+
+@pytest.mark.parametrize("config,n_jobs,load", [(1, 20, 300.0), (2, 12, 25.0)])
+def test_virtual_time_trace_and_logits(config, n_jobs, load):
+    ts = wl.make_taskset(config, n_jobs=n_jobs)
+    et = wl.virtual_et_table(ts, load_scale=load)
+    afet = [[int(np.mean(et[i][j][0][:8])) for j in range(t.n_stages)] for i, t in enumerate(ts.tasks)]
+    g = GpuTaskSet(ts, flags=D.VIRTUAL_TIME, afet=afet)
+    try:
+        load_et(et, len(ts.partitions))
+        D.daris_run_periodic(None, [n_jobs] * len(ts.tasks))
+        got = D.trace_read_all()
+        m = oracle_model(ts, afet)
+        want = des.run_virtual(m, [("release", t, i) for t, i, _ in ts.releases()], et)
+        for a, b in zip(got, want):
+            assert a == b, f"first difference at seq {a[0]}: library {a}, oracle {b}"
+        assert len(got) == len(want)
+        worst, n = g.check_logits(got)
+        print(f"config {config}: {n} jobs checked, worst logits error {worst:.3e}")
+    finally:
+        g.close()
+
+
+def _replay_and_check(ts, afet, got):
+    m = oracle_model(ts, afet)
+    again = des.run_replay(m, got)
+    for a, b in zip(got, again):
+        assert a == b, f"first difference at seq {a[0]}: library {a}, oracle replay {b}"
+    assert len(got) == len(again)
+    check_trace_invariants(got, m.n_streams, [t.priority for t in ts.tasks], [t.n_stages for t in ts.tasks])
+    return m
+
+
+@pytest.mark.parametrize("config,n_jobs", [(1, 20), (2, 25)])
+def test_real_time_periodic_run_replays_through_oracle(config, n_jobs):
+    ts = wl.make_taskset(config, n_jobs=n_jobs)
+    g = GpuTaskSet(ts)
+    try:
+        for i in range(len(ts.tasks)):
+            D.daris_calibrate_afet(i, i % len(ts.partitions), 3)
+        afet = [[D.daris_get_mret(i, j) for j in range(t.n_stages)] for i, t in enumerate(ts.tasks)]
+        D.daris_run_periodic(None, [n_jobs] * len(ts.tasks))
+        got = D.trace_read_all()
+        stats = [D.daris_get_stats(i) for i in range(len(ts.tasks))]
+        m = _replay_and_check(ts, afet, got)
+        worst, n = g.check_logits(got)
+        for s, o in zip(stats, m.stats()):
+            assert (s["accepted"], s["completed"], s["missed"]) == (o["accepted"], o["completed"], o["missed"])
+        hp = [s for s, t in zip(stats, ts.tasks) if t.priority == wl.HP]
+        assert all(s["missed"] == 0 and s["completed"] == n_jobs for s in hp), hp
+        print(f"config {config}: {n} jobs, worst logits error {worst:.3e}, responses (ms) "
+              + ", ".join(f"{s['resp_sum_ns'] / max(s['completed'], 1) / 1e6:.3f}" for s in stats))
+    finally:
+        g.close()
+
+
+def test_closed_loop_with_forced_migrations():
+    ts = wl.make_taskset(2, n_jobs=40)
+    g = GpuTaskSet(ts)
+    try:
+        for i in range(len(ts.tasks)):
+            D.daris_calibrate_afet(i, 0, 2)
+        afet = [[D.daris_get_mret(i, j) for j in range(t.n_stages)] for i, t in enumerate(ts.tasks)]
+        D.daris_commit()
+        D.daris_migrate(3, (D.daris_get_partition(3) + 1) % 3)      # while idle: applies at once
+        D.daris_run_closed_loop([40] * 4)
+        D.daris_migrate(2, (D.daris_get_partition(2) + 1) % 3)
+        D.daris_run_closed_loop([10] * 4)
+        got = D.trace_read_all()
+        m = _replay_and_check(ts, afet, got)
+        assert sum(1 for r in got if r[2] == des.MIGRATE and (r[9] >> 8)) == 2
+        # logits rows are reused modulo n_jobs in the second run: check the rows that hold a final value
+        st = [D.daris_get_stats(i) for i in range(4)]
+        assert all(s["completed"] + s["rejected_admission"] + s["rejected_overrun"] == 50 for s in st)
+        outs = [l.cpu().numpy() for l in g.logits]
+        want = g.oracle_logits()
+        for task in range(4):
+            for job in range(10, 40):
+                if not np.isnan(outs[task][job]).any():
+                    e_max, _ = rel_err(outs[task][job], want[task][job % ts.n_inputs])
+                    assert e_max <= TOL["fp32"]
+    finally:
+        g.close()
+
+
+def test_cu_masks_are_honoured():
+    """Workgroups launched on a partition's stream run only on as many distinct CUs as the partition owns."""
+    D.daris_init(0, 0, 0)
+    try:
+        sizes = (32, 128, 256)
+        parts = [D.daris_create_partition(n) for n in sizes]
+        for p, n in zip(parts, sizes):
+            ids = D.daris_probe_cus(p, 4096, 3000)
+            distinct = {(int(x), (int(h) >> 8) & 0xFF) for x, h in ids}      # HW_ID bits 8..15: CU, shader array, shader engine
+            xccs = sorted({int(x) for x, _ in ids})
+            print(f"partition of {n} CUs: {len(distinct)} distinct (xcc, se/sh/cu) triples over XCCs {xccs}")
+            assert len(distinct) <= n
+    finally:
+        D.daris_shutdown()
