@@ -55,6 +55,7 @@ struct TaskRt {
   NetPlan net;
   std::vector<void*> slots;
   float* ws = nullptr;
+  int* counters = nullptr;
   std::vector<void*> owned;  // every device allocation of the task
   // I/O
   const void* pool_in = nullptr;
@@ -142,12 +143,12 @@ hipError_t launch_layer(TaskRt& T, int l, void* d_logits, hipStream_t s) {
         return launch_dwconv(a, net.bf16, s);
       } else {
         ConvArgs a;
-        a.x = x; a.w = L.w_dev; a.bias = L.b_dev; a.y = y; a.ws = T.ws;
+        a.x = x; a.w = L.w_dev; a.bias = L.b_dev; a.y = y; a.ws = T.ws; a.counters = T.counters;
         a.res = L.res_t >= 0 ? T.slots[net.tensor(L.res_t).slot] : nullptr;
         a.H = in.H; a.W = in.W; a.Cin = in.Cs; a.Ho = L.out.H; a.Wo = L.out.W; a.Cout = L.out.Cs;
         a.kh = a.kw = L.d.k; a.stride = L.d.stride; a.pad = L.d.pad;
         a.K = L.K; a.Kpad = L.Kpad; a.M = L.out.H * L.out.W; a.act = L.d.act;
-        a.splitk = L.cp.splitk; a.kchunk = L.cp.kchunk;
+        a.splitk = L.cp.splitk; a.kchunk = L.cp.kchunk; a.S = L.cp.S; a.sz = L.cp.sz; a.sw = L.cp.sw;
         return launch_conv(L.cp, a, net.bf16, s);
       }
     case DARIS_OP_MAXPOOL:
@@ -510,6 +511,14 @@ daris_task daris_register_task(const daris_dnn* dnn, int64_t period_ns, int64_t 
       if (e != hipSuccess) {
         free_task(*T);
         return fail(DARIS_ENOMEM, "split-K workspace: %s", hipGetErrorString(e));
+      }
+    }
+    if (net.n_counters) {
+      hipError_t e = dev_alloc((size_t)net.n_counters * sizeof(int), (void**)&T->counters);
+      if (e == hipSuccess) e = hipMemset(T->counters, 0, (size_t)net.n_counters * sizeof(int));
+      if (e != hipSuccess) {
+        free_task(*T);
+        return fail(DARIS_ENOMEM, "tile counters: %s", hipGetErrorString(e));
       }
     }
     hipError_t e = hipEventCreateWithFlags(&T->chain, hipEventDisableTiming);

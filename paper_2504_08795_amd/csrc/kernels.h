@@ -11,8 +11,12 @@ namespace daris {
 
 enum KernelId : int32_t {
   K_NONE = 0,
+  // LDS-tiled implicit GEMM, BMxBN workgroup tiles
   K_CONV_F32_128x64, K_CONV_F32_64x64, K_CONV_F32_64x32, K_CONV_F32_32x64, K_CONV_F32_32x32,
   K_CONV_BF16_128x64, K_CONV_BF16_64x64, K_CONV_BF16_64x32, K_CONV_BF16_32x64, K_CONV_BF16_32x32,
+  // wave-tile implicit GEMM: TN 32-channel blocks per wave, NW waves splitting K inside the workgroup
+  K_CONVW_F32_T1W2, K_CONVW_F32_T1W4, K_CONVW_F32_T1W8, K_CONVW_F32_T2W2, K_CONVW_F32_T2W4, K_CONVW_F32_T2W8,
+  K_CONVW_BF16_T1W2, K_CONVW_BF16_T1W4, K_CONVW_BF16_T1W8, K_CONVW_BF16_T2W2, K_CONVW_BF16_T2W4, K_CONVW_BF16_T2W8,
   K_SPLITK_REDUCE, K_DWCONV, K_MAXPOOL, K_GAVGPOOL, K_FC, K_INGEST, K_EGRESS,
   K_COUNT
 };
@@ -20,17 +24,19 @@ const char* kernel_name(int32_t id);
 
 struct ConvArgs {
   const void* x;      // [H][W][Cin]
-  const void* w;      // packed [Cout][Kpad], k = (ky*kw + kx)*Cin + ci, zero padded to Kpad
+  const void* w;      // packed weights, layout per kernel family (see pack_conv)
   const float* bias;  // [Cout]
   const void* res;    // [Ho*Wo][Cout] or nullptr
   void* y;            // [Ho*Wo][Cout]
-  float* ws;          // split-K partial sums [splitk][M][Cout] (splitk > 1)
+  float* ws;          // split-K partial sums (splitk > 1)
+  int* counters;      // wave-tile family: one arrival counter per output tile, all zero between launches
   int H, W, Cin, Ho, Wo, Cout;
   int kh, kw, stride, pad;
   int K, Kpad, M;
   int act;
   int splitk;  // grid.z
-  int kchunk;  // k range per split, multiple of the kernel's BK
+  int kchunk;  // LDS-tiled family: k range per split, multiple of the kernel's BK
+  int S, sz, sw;  // wave-tile family: K steps in total, per grid.z slice, per wave
 };
 
 struct DwArgs {
@@ -55,14 +61,19 @@ struct FcArgs {
   int K, N, Ns, act, out_f32;
 };
 
-// Tile configuration chosen on the host for one dense convolution.
+// Kernel and tile configuration chosen on the host for one dense convolution.
 struct ConvPlan {
   int32_t kernel;  // KernelId
-  int bm, bn, bk, splitk, kchunk;
+  int wave;        // 1 = wave-tile family, 0 = LDS-tiled family
+  int bm, bn, bk, splitk, kchunk;  // LDS-tiled family
+  int tn, nw, S, sz, sw;           // wave-tile family
+  int tiles;                       // output tiles per grid.z slice
+  size_t ws_bytes;                 // split-K workspace this launch needs
   dim3 grid;
   int threads;
 };
-// bf16 = 0/1.  Chooses tile shape and split-K from (M, N, K) only, so results do not depend on the partition.
+// bf16 = 0/1.  Chooses family, tile shape and split-K from (M, N, Kpad) only, so results do not depend on the
+// partition a stage runs in.  Environment variable DARIS_CONV_KERNEL = tile | wave forces one family.
 ConvPlan plan_conv(int M, int N, int Kpad, int bf16);
 
 hipError_t launch_conv(const ConvPlan& pl, const ConvArgs& a, int bf16, hipStream_t s);

@@ -4,6 +4,9 @@
 // (Sec. I, Sec. III-B1), a sequence of such kernels cut into stages.
 #include "kernels.h"
 
+#include <cstdlib>
+#include <cstring>
+
 namespace daris {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -37,6 +40,16 @@ template <bool BF16>
 __device__ __forceinline__ void store_elem(void* p, size_t i, float v) {
   if (BF16) ((uint16_t*)p)[i] = (uint16_t)f32_to_bf16_bits(v);
   else ((float*)p)[i] = v;
+}
+
+// v if ok, else all zero bits; component-wise so that it stays a register select (a select between two uint4
+// objects would be done through their addresses and push the access to scratch / flat memory).
+__device__ __forceinline__ uint4 keep_if(bool ok, uint4 v) {
+  v.x = ok ? v.x : 0u;
+  v.y = ok ? v.y : 0u;
+  v.z = ok ? v.z : 0u;
+  v.w = ok ? v.w : 0u;
+  return v;
 }
 
 // Unpack one 16-byte vector into VEC floats (4 for fp32, 8 for bf16).
@@ -129,18 +142,21 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void conv_igemm_kernel(
   int ky = tap / p.kw, kx = tap - ky * p.kw;
 
   uint4 areg[A_LD], breg[B_LD];
-  const uint4 zero4 = make_uint4(0, 0, 0, 0);
 
   auto gload = [&]() {
 #pragma unroll
     for (int r = 0; r < A_LD; ++r) {
       const int iy = a_iy0[r] + ky, ix = a_ix0[r] + kx;
       const bool ok = a_ok[r] && ky < p.kh && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
-      areg[r] = ok ? *(const uint4*)(xb + ((size_t)(iy * p.W + ix) * p.Cin + ci) * ES) : zero4;
+      // always load from a valid address and blank the value afterwards: keeps the access a plain global load
+      const size_t off = ok ? ((size_t)(iy * p.W + ix) * p.Cin + ci) * ES : 0;
+      const uint4 v = *(const uint4*)(xb + off);
+      areg[r] = keep_if(ok, v);
     }
 #pragma unroll
     for (int r = 0; r < B_LD; ++r) {
-      breg[r] = b_ok[r] ? *(const uint4*)(wb + b_off[r]) : zero4;
+      const uint4 v = *(const uint4*)(wb + (b_ok[r] ? b_off[r] : (size_t)0));
+      breg[r] = keep_if(b_ok[r], v);
       b_off[r] += (size_t)BK * ES;
     }
     ci += BK;
@@ -264,6 +280,140 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
     *(uint2*)((uint16_t*)y + o) = out;
   } else {
     *(float4*)((float*)y + o) = make_float4(v[0], v[1], v[2], v[3]);
+  }
+}
+
+// ---- wave-tile implicit GEMM ---------------------------------------------------------------------------------------
+//
+// For the small-M, deep-K convolutions of batch-1 inference an output tile shared through LDS buys nothing: there
+// are too few tiles to fill a partition, so K has to be split anyway.  Here one wave owns a 32 x (32*TN) output
+// tile over a slice of K and feeds the MFMA straight from registers: lane (i, h) loads the 16 bytes of pixel
+// m0+i at k = step*KS + h*VEC.. from the NHWC input and, per channel block, 16 bytes of weights that were packed
+// at registration in exactly this order ([channel block][step][lane][16 B]: one fully coalesced 1 KiB read per
+// step, consecutive steps consecutive in memory).  No barrier and no LDS in the K loop; D steps are in flight.
+// The NW waves of a workgroup split the K slice of the workgroup; their partial tiles are summed through LDS in
+// wave order.  With grid.z > 1 the workgroups of one tile also split K and write partial sums to the workspace,
+// which splitk_reduce_kernel adds in z order (a device-wide fence per workgroup for an in-kernel reduction was
+// measured to cost several times the extra launch).
+template <bool BF16, int TN, int NW>
+__global__ __launch_bounds__(NW * 64) void conv_wave_kernel(const ConvArgs p) {
+  constexpr int ES = BF16 ? 2 : 4;
+  constexpr int VEC = 16 / ES;
+  constexpr int KS = 2 * VEC;
+  constexpr int NT = NW * 64;
+  constexpr int TILE = TN * 1024;
+  constexpr int PER = TILE / NT;
+  constexpr int D = 4;
+  static_assert(TILE % NT == 0, "tile / thread mismatch");
+
+  __shared__ float red[NW * TILE];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 31, lh = lane >> 5;
+  const int m0 = blockIdx.x * 32, nb0 = blockIdx.y * TN;
+
+  const int s_wg0 = blockIdx.z * p.sz;
+  const int s_wg1 = min(s_wg0 + p.sz, p.S);
+  const int sbeg = min(s_wg0 + wave * p.sw, s_wg1);
+  const int nsteps = min(sbeg + p.sw, s_wg1) - sbeg;
+
+  const unsigned char* xb = (const unsigned char*)p.x;
+  const int m = m0 + li;
+  const bool a_ok = m < p.M;
+  const int oy = m / p.Wo, ox = m - oy * p.Wo;
+  const int iy0 = oy * p.stride - p.pad, ix0 = ox * p.stride - p.pad;
+  const int k0 = sbeg * KS + lh * VEC;
+  int tap = k0 / p.Cin;
+  int ci = k0 - tap * p.Cin;
+  int ky = tap / p.kw, kx = tap - ky * p.kw;
+  const unsigned char* wptr[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+    wptr[j] = (const unsigned char*)p.w + (((size_t)(nb0 + j) * p.S + sbeg) * 64 + lane) * 16;
+
+  uint4 ar[D], br[D][TN];
+  auto load = [&](int d) {
+    const int iy = iy0 + ky, ix = ix0 + kx;
+    const bool ok = a_ok && ky < p.kh && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
+    // always load from a valid address and blank the value afterwards: keeps the access a plain global load
+    const size_t off = ok ? ((size_t)(iy * p.W + ix) * p.Cin + ci) * ES : 0;
+    const uint4 v = *(const uint4*)(xb + off);
+    ar[d] = keep_if(ok, v);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      br[d][j] = *(const uint4*)wptr[j];
+      wptr[j] += 1024;
+    }
+    ci += KS;
+    while (ci >= p.Cin) {
+      ci -= p.Cin;
+      if (++kx == p.kw) { kx = 0; ++ky; }
+    }
+  };
+
+  f32x16 acc[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+
+#pragma unroll
+  for (int d = 0; d < D; ++d)
+    if (d < nsteps) load(d);
+  for (int base = 0; base < nsteps; base += D) {
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+      if (base + d < nsteps) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          if (BF16) {
+            acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ar[d]), __builtin_bit_cast(bf16x8, br[d][j]),
+                                                             acc[j], 0, 0, 0);
+          } else {
+            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(ar[d].x), __uint_as_float(br[d][j].x), acc[j], 0, 0, 0);
+            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(ar[d].y), __uint_as_float(br[d][j].y), acc[j], 0, 0, 0);
+            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(ar[d].z), __uint_as_float(br[d][j].z), acc[j], 0, 0, 0);
+            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(ar[d].w), __uint_as_float(br[d][j].w), acc[j], 0, 0, 0);
+          }
+        }
+        if (base + d + D < nsteps) load(d);
+      }
+    }
+  }
+
+  // --- sum the NW partial tiles in wave order; tile element e = (j*16 + v)*64 + lane --------------------------------
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) red[wave * TILE + (j * 16 + v) * 64 + lane] = acc[j][v];
+  __syncthreads();
+  float vals[PER];
+#pragma unroll
+  for (int r = 0; r < PER; ++r) {
+    const int e = tid + r * NT;
+    float s = red[e];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) s += red[w * TILE + e];
+    vals[r] = s;
+  }
+
+  // --- epilogue: element e of the tile is pixel m0 + 8*(v/4) + 4*(lane/32) + v%4, channel 32*(nb0+j) + lane%32 ------
+#pragma unroll
+  for (int r = 0; r < PER; ++r) {
+    const int e = tid + r * NT;
+    const int j = e >> 10, v = (e >> 6) & 15, l = e & 63;
+    const int mm = m0 + (v >> 2) * 8 + (l >> 5) * 4 + (v & 3);
+    const int n = (nb0 + j) * 32 + (l & 31);
+    if (mm < p.M && n < p.Cout) {
+      const size_t o = (size_t)mm * p.Cout + n;
+      if (p.splitk > 1) {  // partial sums of this K slice; splitk_reduce_kernel finishes the layer
+        p.ws[(size_t)blockIdx.z * p.M * p.Cout + o] = vals[r];
+      } else {
+        float val = vals[r] + p.bias[n];
+        if (p.res) val += load_elem<BF16>(p.res, o);
+        store_elem<BF16>(p.y, o, apply_act(val, p.act));
+      }
+    }
   }
 }
 
@@ -414,20 +564,23 @@ static const char* const kNames[K_COUNT] = {
     "none",
     "conv_igemm_f32_128x64", "conv_igemm_f32_64x64", "conv_igemm_f32_64x32", "conv_igemm_f32_32x64", "conv_igemm_f32_32x32",
     "conv_igemm_bf16_128x64", "conv_igemm_bf16_64x64", "conv_igemm_bf16_64x32", "conv_igemm_bf16_32x64", "conv_igemm_bf16_32x32",
+    "conv_wave_f32_t1w2", "conv_wave_f32_t1w4", "conv_wave_f32_t1w8", "conv_wave_f32_t2w2", "conv_wave_f32_t2w4", "conv_wave_f32_t2w8",
+    "conv_wave_bf16_t1w2", "conv_wave_bf16_t1w4", "conv_wave_bf16_t1w8", "conv_wave_bf16_t2w2", "conv_wave_bf16_t2w4", "conv_wave_bf16_t2w8",
     "splitk_reduce", "dwconv", "maxpool", "gavgpool", "fc", "ingest", "egress"};
 
 const char* kernel_name(int32_t id) { return (id >= 0 && id < K_COUNT) ? kNames[id] : "?"; }
 
 static inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
-ConvPlan plan_conv(int M, int N, int Kpad, int bf16) {
-  ConvPlan pl;
+static const int kNominalWaveSlots = 512;  // 128 CUs x 4 SIMDs: the partition size the plans are tuned for
+
+static ConvPlan plan_conv_tile(int M, int N, int Kpad, int bf16) {
+  ConvPlan pl = ConvPlan();
   const int bk = bf16 ? 32 : 16;  // KV = 4 vectors of 16 bytes per tile row
   pl.bk = bk;
   const int blocks32 = cdiv(M, 32) * cdiv(N, 32);  // 32x32 MFMA tiles in the output
-  const int wave_slots = 512;                      // 128 CUs x 4 SIMDs: the nominal partition
   int variant;                                     // 0: 128x64, 1: 64x64, 2: 64x32, 3: 32x64, 4: 32x32
-  if (blocks32 >= 4 * wave_slots && N >= 64) variant = 0;
+  if (blocks32 >= 4 * kNominalWaveSlots && N >= 64) variant = 0;
   else if (N <= 32) variant = (M > 32) ? 2 : 4;
   else if (M <= 32) variant = 3;
   else variant = 1;
@@ -438,8 +591,8 @@ ConvPlan plan_conv(int M, int N, int Kpad, int bf16) {
   pl.kernel = (bf16 ? K_CONV_BF16_128x64 : K_CONV_F32_128x64) + variant;
   // split-K until the launch has about one wave per SIMD of the nominal partition
   int splitk = 1;
-  if (variant != 0 && blocks32 < wave_slots) {
-    splitk = cdiv(wave_slots, blocks32);
+  if (variant != 0 && blocks32 < kNominalWaveSlots) {
+    splitk = cdiv(kNominalWaveSlots, blocks32);
     const int max_by_k = Kpad / (4 * bk) > 0 ? Kpad / (4 * bk) : 1;  // at least four K steps per split
     if (splitk > max_by_k) splitk = max_by_k;
     if (splitk > 16) splitk = 16;
@@ -449,11 +602,74 @@ ConvPlan plan_conv(int M, int N, int Kpad, int bf16) {
   pl.splitk = splitk;
   pl.kchunk = kchunk;
   pl.grid = dim3(cdiv(M, pl.bm), cdiv(N, pl.bn), splitk);
+  pl.tiles = pl.grid.x * pl.grid.y;
+  pl.ws_bytes = splitk > 1 ? (size_t)splitk * M * N * sizeof(float) : 0;
   return pl;
+}
+
+static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16) {
+  // Measured on a 128-CU partition (fp32, ResNet-18 shapes): the K loop itself runs near the MFMA rate; what a
+  // launch pays for is its fixed cost and idle CUs.  Best found: 8 waves per workgroup splitting K, and enough
+  // grid.z slices that tiles * z is about the number of CUs, while a wave keeps at least ~6 steps.
+  ConvPlan pl = ConvPlan();
+  pl.wave = 1;
+  const int ks = bf16 ? 16 : 8;  // k per step: two 16-byte vectors
+  const int S = Kpad / ks;
+  const int nb = cdiv(N, 32);
+  const int tn = (nb % 2 == 0) ? 2 : 1;
+  const int tiles = cdiv(M, 32) * (nb / tn);
+  const int nominal_cus = kNominalWaveSlots / 4;
+  int nw = 8;
+  while (nw > 2 && (S / nw < 4 || tiles * nw > 8 * kNominalWaveSlots)) nw /= 2;  // >= 4 steps per wave, <= 8 waves per SIMD
+  int z = nominal_cus / tiles;
+  if (z < 1) z = 1;
+  const int max_by_k = S / (nw * 6) > 0 ? S / (nw * 6) : 1;
+  if (z > max_by_k) z = max_by_k;
+  if (z > 16) z = 16;
+  if (const char* e = getenv("DARIS_W_NW")) nw = atoi(e);
+  if (const char* e = getenv("DARIS_W_Z")) z = atoi(e) < S ? atoi(e) : S;
+  const int sz = cdiv(S, z);
+  z = cdiv(S, sz);
+  pl.tn = tn;
+  pl.nw = nw;
+  pl.S = S;
+  pl.sz = sz;
+  pl.sw = cdiv(sz, nw);
+  pl.splitk = z;
+  pl.tiles = tiles;
+  pl.threads = nw * 64;
+  pl.grid = dim3(cdiv(M, 32), nb / tn, z);
+  pl.ws_bytes = z > 1 ? (size_t)z * M * N * sizeof(float) : 0;
+  const int wi = nw == 2 ? 0 : (nw == 4 ? 1 : 2);
+  pl.kernel = (bf16 ? K_CONVW_BF16_T1W2 : K_CONVW_F32_T1W2) + (tn - 1) * 3 + wi;
+  return pl;
+}
+
+ConvPlan plan_conv(int M, int N, int Kpad, int bf16) {
+  const char* force = getenv("DARIS_CONV_KERNEL");
+  if (force && !strcmp(force, "tile")) return plan_conv_tile(M, N, Kpad, bf16);
+  if (force && !strcmp(force, "wave")) return plan_conv_wave(M, N, Kpad, bf16);
+  // Large outputs fill the partition with LDS-shared 128x64 tiles and read each operand far fewer times;
+  // everything smaller is latency bound and goes to the wave-tile family.
+  const int blocks32 = cdiv(M, 32) * cdiv(N, 32);
+  if (blocks32 >= 4 * kNominalWaveSlots && N >= 64) return plan_conv_tile(M, N, Kpad, bf16);
+  return plan_conv_wave(M, N, Kpad, bf16);
 }
 
 template <bool BF16>
 static hipError_t launch_conv_t(const ConvPlan& pl, const ConvArgs& a, hipStream_t s) {
+  if (pl.wave) {
+    const int variant = pl.kernel - (BF16 ? K_CONVW_BF16_T1W2 : K_CONVW_F32_T1W2);
+    switch (variant) {
+      case 0: hipLaunchKernelGGL((conv_wave_kernel<BF16, 1, 2>), pl.grid, dim3(128), 0, s, a); break;
+      case 1: hipLaunchKernelGGL((conv_wave_kernel<BF16, 1, 4>), pl.grid, dim3(256), 0, s, a); break;
+      case 2: hipLaunchKernelGGL((conv_wave_kernel<BF16, 1, 8>), pl.grid, dim3(512), 0, s, a); break;
+      case 3: hipLaunchKernelGGL((conv_wave_kernel<BF16, 2, 2>), pl.grid, dim3(128), 0, s, a); break;
+      case 4: hipLaunchKernelGGL((conv_wave_kernel<BF16, 2, 4>), pl.grid, dim3(256), 0, s, a); break;
+      case 5: hipLaunchKernelGGL((conv_wave_kernel<BF16, 2, 8>), pl.grid, dim3(512), 0, s, a); break;
+      default: return hipErrorInvalidValue;
+    }
+  } else {
   const int variant = pl.kernel - (BF16 ? K_CONV_BF16_128x64 : K_CONV_F32_128x64);
   switch (variant) {
     case 0: hipLaunchKernelGGL((conv_igemm_kernel<BF16, 128, 64, 64, 32, 4>), pl.grid, dim3(256), 0, s, a); break;
@@ -462,6 +678,7 @@ static hipError_t launch_conv_t(const ConvPlan& pl, const ConvArgs& a, hipStream
     case 3: hipLaunchKernelGGL((conv_igemm_kernel<BF16, 32, 64, 32, 32, 4>), pl.grid, dim3(128), 0, s, a); break;
     case 4: hipLaunchKernelGGL((conv_igemm_kernel<BF16, 32, 32, 32, 32, 4>), pl.grid, dim3(64), 0, s, a); break;
     default: return hipErrorInvalidValue;
+  }
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -65,8 +65,7 @@ std::string build_plan(const daris_dnn& dnn, bool keep_activations, NetPlan* out
           L.Kpad = round_up(L.K, 32);
           L.cp = plan_conv(o.H * o.W, o.Cs, L.Kpad, net.bf16);
           L.kernel_id = L.cp.kernel;
-          if (L.cp.splitk > 1)
-            net.ws_bytes = std::max(net.ws_bytes, (size_t)L.cp.splitk * o.H * o.W * o.Cs * sizeof(float));
+          net.ws_bytes = std::max(net.ws_bytes, L.cp.ws_bytes);
         } else {
           L.kernel_id = K_DWCONV;
         }
@@ -215,7 +214,24 @@ void pack_conv(const NetPlan& net, const LayerPlan& L, const float* w, const flo
       for (int t = 0; t < kk; ++t) put<float>(wp, (size_t)t * in.Cs + c, w[(size_t)c * kk + t], bf);
     return;
   }
-  // [Cs_out][Kpad], k = tap * Cs_in + ci
+  if (L.cp.wave) {
+    // wave-tile family: [channel block of 32][step][lane = i + 32 h][VEC], element e of lane (i, h) at step s is
+    // W[n = 32 nb + i][k = s*KS + h*VEC + e], k = tap * Cs_in + ci; blocks padded to a multiple of TN, zeros elsewhere
+    const int vec = bf ? 8 : 4, ks = 2 * vec, S = L.cp.S;
+    const int nblocks = (L.out.Cs + 31) / 32;
+    const int nb_alloc = (nblocks + L.cp.tn - 1) / L.cp.tn * L.cp.tn;
+    wp->assign((size_t)nb_alloc * S * 64 * 16, 0);
+    for (int o = 0; o < d.c_out; ++o)
+      for (int ci = 0; ci < d.c_in; ++ci)
+        for (int t = 0; t < kk; ++t) {
+          const int k = t * in.Cs + ci;
+          const int st = k / ks, h = (k % ks) / vec, e = k % vec;
+          const size_t lane = (size_t)(o % 32) + 32 * h;
+          put<float>(wp, (((size_t)(o / 32) * S + st) * 64 + lane) * vec + e, w[((size_t)o * d.c_in + ci) * kk + t], bf);
+        }
+    return;
+  }
+  // LDS-tiled family: [Cs_out][Kpad], k = tap * Cs_in + ci
   wp->assign((size_t)L.out.Cs * L.Kpad * es, 0);
   for (int o = 0; o < d.c_out; ++o)
     for (int ci = 0; ci < d.c_in; ++ci)
