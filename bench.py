@@ -8,7 +8,9 @@ Workload (the configuration the headline metric is quoted on): 4 periodic tasks 
 A "step" is one pass of the whole hot path for every task: each task releases one job, which goes through
 admission, stage dispatch on the CU-masked streams, the conv/pool/FC kernels and the stage-boundary
 synchronisations.  The timed region runs the saturated (closed-loop) variant: every task releases its next job
-the instant the previous one finishes, K jobs per task; value = completed inferences / wall time.  The periodic
+the instant the previous one finishes, until K steps = K x 4 jobs have been released over all tasks (tasks that
+own a partition alone therefore contribute more jobs than the two that share one); value = completed
+inferences / wall time.  The periodic
 run at the nominal periods (HP 20 ms, LP 40 ms) follows and supplies the deadline-miss rates and response times.
 """
 import argparse
@@ -23,6 +25,19 @@ sys.path.insert(0, ROOT)
 PEAK_FP32_MFMA_TFLOPS = 157.3
 
 
+def read_traffic(kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE, scaled by
+    the copy-kernel calibration); None if the summary does not cover this kernel."""
+    path = os.path.join(ROOT, "profiles", "conv_kernels_resnet18_hbm_traffic.md")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch[") and line.split("[")[1].split("]")[0] == kernel:
+                return int(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -31,6 +46,10 @@ def main():
     ap.add_argument("--periodic-jobs", type=int, default=100, help="jobs per task of the periodic (deadline) run; 0 skips it")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU-oracle baseline; 0 skips it")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--sample-every", type=int, default=8, help="kernel timing: bracket the conv launches of every n-th job")
+    ap.add_argument("--pmc-pass", action="store_true",
+                    help="counter-collection helper for `rocprofv3 --pmc`: three 64 MiB device copies (the known-size reference "
+                         "kernel), then 20 forward passes of task 0 alone; prints nothing, times nothing")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -40,7 +59,7 @@ def main():
     import paper_2504_08795_amd as D
     import workloads as wl
 
-    ts = wl.make_taskset(2, n_jobs=max(args.steps + args.warmup, args.periodic_jobs, 1))
+    ts = wl.make_taskset(2, n_jobs=max(min(args.steps, 2000), args.periodic_jobs, 1))
     D.daris_init(0, wl.tasksets.SEED, 0)
     for n in ts.partitions:
         D.daris_create_partition(n)
@@ -58,19 +77,32 @@ def main():
         outs.append(torch.zeros((ts.n_jobs, layers[-1].c_out), dtype=torch.float32, device="cuda"))
         D.daris_task_set_io(h, ins[i], ts.n_inputs, outs[i], ts.n_jobs)
     nt = len(ts.tasks)
+    if args.pmc_pass:
+        a = torch.zeros(16 << 20, dtype=torch.float32, device="cuda")      # 64 MiB read + 64 MiB written per copy
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        for _ in range(20):
+            D.daris_forward(0, ins[0][0], outs[0][0], 0)
+        D.daris_shutdown()
+        return
     for i in range(nt):
         D.daris_calibrate_afet(i, i % len(ts.partitions), 3)
     D.daris_commit()
 
     # ---- saturated run: warm-up, then exactly K steps between synchronisations --------------------------------
-    D.daris_run_closed_loop([args.warmup] * nt)
+    D.daris_run_closed_loop([args.warmup * nt] * nt, args.warmup * nt)
     torch.cuda.synchronize()
+    if not args.no_profile:
+        D.daris_kernel_timing_start(args.sample_every, 20000)   # HIP-event pairs around sampled conv launches, on their streams
     before = [D.daris_get_stats(i) for i in range(nt)]
     t0 = time.perf_counter()
-    D.daris_run_closed_loop([args.steps] * nt)
+    D.daris_run_closed_loop([args.steps * nt] * nt, args.steps * nt)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     after = [D.daris_get_stats(i) for i in range(nt)]
+    timing, pair_ms = (None, 0.0) if args.no_profile else D.daris_kernel_timing_read()
     completed = sum(a["completed"] - b["completed"] for a, b in zip(after, before))
     rejected = sum((a["rejected_admission"] + a["rejected_overrun"]) - (b["rejected_admission"] + b["rejected_overrun"])
                    for a, b in zip(after, before))
@@ -98,25 +130,31 @@ def main():
         done_all = sum(a2[i]["completed"] - b2[i]["completed"] for i in range(nt))
         periodic = dict(jobs_per_task=args.periodic_jobs, inferences_per_s=round(done_all / wall, 2), hp=agg(wl.HP), lp=agg(wl.LP))
 
-    # ---- roofline of the dominant kernel: per-layer HIP-event timing on the partition's own stream ------------------------
+    # ---- roofline of the dominant kernel --------------------------------------------------------------------------------
+    # Durations come from HIP-event pairs recorded on the partition streams around every dense-convolution launch of
+    # each `sample_every`-th job INSIDE the timed region above (three DNNs running concurrently on overlapping
+    # partitions).  FLOPs are the algorithmic 2*MACs of the layers those launches computed.
     roofline = None
-    if not args.no_profile:
-        layers = nets[0][0]
-        ms, kid, fl = D.daris_profile_layers(0, 0, 20, len(layers))
-        per_kernel = {}
-        for m, k, f in zip(ms, kid, fl):
-            e = per_kernel.setdefault(int(k), [0.0, 0.0, 0])
-            e[0] += float(m)
-            e[1] += float(f)
-            e[2] += 1
-        dom = max(per_kernel, key=lambda k: per_kernel[k][0])
-        t_ms, flops, n_launch = per_kernel[dom]
+    if timing:
+        dom = max(timing, key=lambda k: timing[k][1])
+        n_launch, t_raw_ms, flops = timing[dom]
+        # an event pair with nothing inside already reads pair_ms (command-processor marker latency): take it out
+        t_ms = max(t_raw_ms - n_launch * pair_ms, 1e-9)
         achieved = flops / (t_ms * 1e-3) / 1e12
-        roofline = dict(bound="mfma", kernel=D.daris_kernel_name(dom), launches_per_inference=n_launch,
-                        avg_launch_us=round(t_ms * 1e3 / n_launch, 3), achieved=round(achieved, 3), peak=PEAK_FP32_MFMA_TFLOPS,
-                        unit="TFLOP/s", frac=round(achieved / PEAK_FP32_MFMA_TFLOPS, 5), traffic=None,
-                        network_kernel_time_ms=round(float(ms.sum()), 4),
-                        per_kernel_ms={D.daris_kernel_name(k): round(v[0], 4) for k, v in per_kernel.items()})
+        layers = nets[0][0]
+        ms, kid, fl = D.daris_profile_layers(0, 0, 20, len(layers))          # the same task alone, for reference
+        solo = {}
+        for m, k, f in zip(ms, kid, fl):
+            e = solo.setdefault(D.daris_kernel_name(int(k)), [0.0, 0])
+            e[0] += float(m)
+            e[1] += 1
+        roofline = dict(bound="mfma", kernel=dom, sampled_launches=n_launch, avg_launch_us=round(t_ms * 1e3 / n_launch, 3),
+                        avg_launch_us_raw_event_pair=round(t_raw_ms * 1e3 / n_launch, 3), empty_event_pair_us=round(pair_ms * 1e3, 3),
+                        achieved=round(achieved, 3), peak=PEAK_FP32_MFMA_TFLOPS, unit="TFLOP/s",
+                        frac=round(achieved / PEAK_FP32_MFMA_TFLOPS, 5), traffic=read_traffic(dom),
+                        all_sampled_kernels={k: dict(launches=v[0], avg_us=round((v[1] / v[0] - pair_ms) * 1e3, 3)) for k, v in timing.items()},
+                        solo_layer_ms_per_inference={k: round(v[0], 4) for k, v in solo.items()},
+                        solo_network_kernel_time_ms=round(float(ms.sum()), 4))
     D.daris_shutdown()
 
     # ---- CPU oracle on the host cores, bounded sample of the same workload ----------------------------------------------------

@@ -194,8 +194,9 @@ daris_status daris_task_set_io(daris_task t, const void* d_inputs, int32_t n_inp
  * (time, task) order, and return when every job has finished or was rejected. */
 daris_status daris_run_periodic(const int64_t* phase_ns, const int32_t* n_jobs);
 /* Saturated variant: every task with n_jobs[i] > 0 releases its next job the instant the previous one finishes
- * (or is rejected) until n_jobs[i] were released.  Real-time mode only. */
-daris_status daris_run_closed_loop(const int32_t* n_jobs);
+ * (or is rejected) until n_jobs[i] were released or, if total_jobs > 0, until total_jobs were released over all
+ * tasks together (tasks in faster partitions then contribute more jobs).  Real-time mode only. */
+daris_status daris_run_closed_loop(const int32_t* n_jobs, int64_t total_jobs);
 
 /* ---- observation ------------------------------------------------------------------------------------------- */
 
@@ -218,6 +219,15 @@ daris_status daris_read_layer(daris_task t, int layer, float* host_out, int64_t 
 daris_status daris_profile_layers(daris_task t, daris_part p, int reps, float* ms_per_layer, int32_t* kernel_id,
                                   double* flops);
 const char* daris_kernel_name(int32_t kernel_id);
+/* Kernel timing by sampling, for roofline figures measured inside a scheduled run: from now on every `every`-th job
+ * of each task (0 = off) has each dense-convolution kernel bracketed by a pair of HIP events recorded on the stream
+ * it is launched on (the split-K reduction kernel is outside the bracket), for at most max_samples launches. */
+daris_status daris_kernel_timing_start(int every, int max_samples);
+/* Waits until idle, stops the sampling and sums the samples per kernel id: launches[id], total_ms[id], total_flops[id]
+ * (algorithmic FLOPs, 2*MACs) for id < the returned count; the arrays (host) must hold `cap` >= 64 entries.
+ * *empty_pair_ms (may be NULL) receives what a pair of events with nothing between them reported on a partition
+ * stream when the sampling was started (median of 65): the marker latency contained in every sample. */
+int32_t daris_kernel_timing_read(int32_t cap, int64_t* launches, double* total_ms, double* total_flops, double* empty_pair_ms);
 /* Measure per-stage execution times of task t alone on partition p (`reps` runs, the maximum is kept) and store
  * them as the task's AFET values. */
 daris_status daris_calibrate_afet(daris_task t, daris_part p, int reps);

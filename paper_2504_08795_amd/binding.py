@@ -69,7 +69,7 @@ _SIGS = {
     "daris_run_until_idle": (C.c_int32, []),
     "daris_task_set_io": (C.c_int32, [C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32]),
     "daris_run_periodic": (C.c_int32, [C.POINTER(C.c_int64), C.POINTER(C.c_int32)]),
-    "daris_run_closed_loop": (C.c_int32, [C.POINTER(C.c_int32)]),
+    "daris_run_closed_loop": (C.c_int32, [C.POINTER(C.c_int32), C.c_int64]),
     "daris_get_stats": (C.c_int32, [C.c_int32, C.POINTER(daris_task_stats)]),
     "daris_trace_read": (C.c_int64, [C.c_void_p, C.c_int64]),
     "daris_get_mret": (C.c_int64, [C.c_int32, C.c_int]),
@@ -78,6 +78,8 @@ _SIGS = {
     "daris_profile_layers": (C.c_int32, [C.c_int32, C.c_int32, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_int32), C.POINTER(C.c_double)]),
     "daris_kernel_name": (C.c_char_p, [C.c_int32]),
     "daris_calibrate_afet": (C.c_int32, [C.c_int32, C.c_int32, C.c_int]),
+    "daris_kernel_timing_start": (C.c_int32, [C.c_int, C.c_int]),
+    "daris_kernel_timing_read": (C.c_int32, [C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "daris_probe_cus": (C.c_int32, [C.c_int32, C.c_int, C.c_int, C.POINTER(C.c_uint32)]),
 }
 EXPORTS = sorted(_SIGS)
@@ -224,9 +226,9 @@ def daris_run_periodic(phase_ns, n_jobs):
                                          n.ctypes.data_as(C.POINTER(C.c_int32))))
 
 
-def daris_run_closed_loop(n_jobs):
+def daris_run_closed_loop(n_jobs, total_jobs=0):
     n = np.ascontiguousarray(n_jobs, np.int32)
-    return _chk(lib().daris_run_closed_loop(n.ctypes.data_as(C.POINTER(C.c_int32))))
+    return _chk(lib().daris_run_closed_loop(n.ctypes.data_as(C.POINTER(C.c_int32)), int(total_jobs)))
 
 
 def daris_get_stats(t):
@@ -276,6 +278,19 @@ def daris_profile_layers(t, p, reps, n_layers):
 
 def daris_kernel_name(kernel_id):
     return lib().daris_kernel_name(int(kernel_id)).decode()
+
+
+def daris_kernel_timing_start(every, max_samples):
+    return _chk(lib().daris_kernel_timing_start(every, max_samples))
+
+
+def daris_kernel_timing_read():
+    """({kernel name: (launches, total_ms, total_flops)}, empty_pair_ms) of the sampled launches since daris_kernel_timing_start."""
+    n, ms, fl = np.zeros(64, np.int64), np.zeros(64, np.float64), np.zeros(64, np.float64)
+    ov = C.c_double(0.0)
+    k = _chk(lib().daris_kernel_timing_read(64, n.ctypes.data_as(C.POINTER(C.c_int64)), ms.ctypes.data_as(C.POINTER(C.c_double)),
+                                            fl.ctypes.data_as(C.POINTER(C.c_double)), C.byref(ov)))
+    return {daris_kernel_name(i): (int(n[i]), float(ms[i]), float(fl[i])) for i in range(k) if n[i] > 0}, ov.value
 
 
 def daris_calibrate_afet(t, p, reps=5):

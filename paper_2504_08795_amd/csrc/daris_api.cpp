@@ -69,6 +69,12 @@ struct TaskRt {
   int32_t closed_left = 0;
 };
 
+struct TimingPair {  // one sampled kernel launch: events recorded around it on its own stream
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  int32_t kernel = 0;
+  double flops = 0;
+};
+
 struct StreamRt {
   hipStream_t s = nullptr;
   hipEvent_t done = nullptr;
@@ -116,6 +122,11 @@ struct Global {
   bool stop = false;
   std::chrono::steady_clock::time_point epoch;
   std::string async_error;
+  int tm_every = 0;                 // kernel timing: sample every n-th job of a task, 0 = off
+  std::vector<TimingPair> tm_pairs;
+  size_t tm_used = 0;
+  double tm_overhead_ms = 0;        // what an empty event pair reports on a partition stream
+  int64_t closed_total_left = -1;  // closed-loop runs: releases left over all tasks, -1 = no common budget
 };
 
 Global* G = nullptr;
@@ -126,7 +137,7 @@ int64_t now_ns() {
 
 // ---- stage execution ----------------------------------------------------------------------------------------------
 
-hipError_t launch_layer(TaskRt& T, int l, void* d_logits, hipStream_t s) {
+hipError_t launch_layer(TaskRt& T, int l, void* d_logits, hipStream_t s, bool sample = false) {
   NetPlan& net = T.net;
   LayerPlan& L = net.layers[l];
   const TensorInfo& in = net.tensor(L.in_t);
@@ -149,6 +160,13 @@ hipError_t launch_layer(TaskRt& T, int l, void* d_logits, hipStream_t s) {
         a.kh = a.kw = L.d.k; a.stride = L.d.stride; a.pad = L.d.pad;
         a.K = L.K; a.Kpad = L.Kpad; a.M = L.out.H * L.out.W; a.act = L.d.act;
         a.splitk = L.cp.splitk; a.kchunk = L.cp.kchunk; a.S = L.cp.S; a.sz = L.cp.sz; a.sw = L.cp.sw;
+        a.MT = L.cp.MT; a.NTn = L.cp.NTn; a.G = L.cp.G; a.xmode = L.cp.xmode;
+        if (sample && G->tm_used < G->tm_pairs.size()) {
+          TimingPair& tp = G->tm_pairs[G->tm_used++];
+          tp.kernel = L.kernel_id;
+          tp.flops = 2.0 * (double)L.macs;
+          return launch_conv(L.cp, a, net.bf16, s, tp.e0, tp.e1);
+        }
         return launch_conv(L.cp, a, net.bf16, s);
       }
     case DARIS_OP_MAXPOOL:
@@ -169,7 +187,7 @@ hipError_t launch_layer(TaskRt& T, int l, void* d_logits, hipStream_t s) {
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_stage(TaskRt& T, int stage, const JobIo& io, hipStream_t s) {
+hipError_t launch_stage(TaskRt& T, int stage, const JobIo& io, hipStream_t s, bool sample = false) {
   NetPlan& net = T.net;
   const int n = (int)net.layers.size();
   const int first = net.stage_first[stage];
@@ -181,7 +199,7 @@ hipError_t launch_stage(TaskRt& T, int stage, const JobIo& io, hipStream_t s) {
     if (e != hipSuccess) return e;
   }
   for (int l = first; l < end; ++l) {
-    e = launch_layer(T, l, io.out, s);
+    e = launch_layer(T, l, io.out, s, sample);
     if (e != hipSuccess) return e;
   }
   if (end == n && !net.final_direct) {
@@ -210,7 +228,7 @@ daris_status issue(const std::vector<Launch>& ls, int64_t t) {
       auto io = T.io.find(l.job);
       if (io == T.io.end()) return fail(DARIS_ESTATE, "job %u of task %d has no I/O buffers", l.job, l.task);
       if (G->vt) HIP_TRY(hipStreamWaitEvent(S.s, T.chain, 0));
-      HIP_TRY(launch_stage(T, l.stage, io->second, S.s));
+      HIP_TRY(launch_stage(T, l.stage, io->second, S.s, G->tm_every > 0 && l.job % (uint32_t)G->tm_every == 0));
       if (G->vt) {
         HIP_TRY(hipEventRecord(T.chain, S.s));
       } else {
@@ -301,8 +319,9 @@ void sched_loop() {
         if (dispatch_and_issue(now) != DARIS_OK && G->async_error.empty()) G->async_error = tl_error;
         if (job_done) {
           // closed loop: the next job of the task is released the instant this one ends
-          while (T.closed_left > 0 && !G->core.has_active(task)) {
+          while (T.closed_left > 0 && G->closed_total_left != 0 && !G->core.has_active(task)) {
             T.closed_left--;
+            if (G->closed_total_left > 0) G->closed_total_left--;
             const uint32_t next = (uint32_t)G->core.stats(task).released;
             int32_t dec = 0;
             if (rt_release_locked(task, pool_io(T, next), now, now, &dec) != DARIS_OK && G->async_error.empty())
@@ -413,6 +432,10 @@ daris_status daris_shutdown(void) {
   if (!G->nodev) {
     (void)hipDeviceSynchronize();
     for (auto& T : G->tasks) free_task(*T);
+    for (TimingPair& tp : G->tm_pairs) {
+      (void)hipEventDestroy(tp.e0);
+      (void)hipEventDestroy(tp.e1);
+    }
     for (PartRt& P : G->parts)
       for (StreamRt& S : P.streams) {
         if (S.done) (void)hipEventDestroy(S.done);
@@ -747,7 +770,7 @@ daris_status daris_run_periodic(const int64_t* phase_ns, const int32_t* n_jobs) 
   return daris_run_until_idle();
 }
 
-daris_status daris_run_closed_loop(const int32_t* n_jobs) {
+daris_status daris_run_closed_loop(const int32_t* n_jobs, int64_t total_jobs) {
   if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
   if (G->vt) return fail(DARIS_ESTATE, "closed-loop runs need real-time mode");
   if (!n_jobs) return fail(DARIS_EINVAL, "n_jobs is NULL");
@@ -758,12 +781,14 @@ daris_status daris_run_closed_loop(const int32_t* n_jobs) {
   {
     std::lock_guard<std::mutex> lk(G->mu);
     const int64_t now = now_ns();
+    G->closed_total_left = total_jobs > 0 ? total_jobs : -1;
+    for (int i = 0; i < (int)G->tasks.size(); ++i) G->tasks[i]->closed_left = n_jobs[i];
     for (int i = 0; i < (int)G->tasks.size(); ++i) {
       TaskRt& T = *G->tasks[i];
-      T.closed_left = n_jobs[i];
       // a rejected release ends no job, so keep releasing until one is admitted or the budget is spent
-      while (T.closed_left > 0 && !G->core.has_active(i)) {
+      while (T.closed_left > 0 && G->closed_total_left != 0 && !G->core.has_active(i)) {
         T.closed_left--;
+        if (G->closed_total_left > 0) G->closed_total_left--;
         const uint32_t job = (uint32_t)G->core.stats(i).released;
         st = rt_release_locked(i, pool_io(T, job), now, now, nullptr);
         if (st != DARIS_OK) return st;
@@ -771,7 +796,13 @@ daris_status daris_run_closed_loop(const int32_t* n_jobs) {
     }
   }
   G->cv_work.notify_all();
-  return wait_idle();
+  daris_status st2 = wait_idle();
+  {
+    std::lock_guard<std::mutex> lk(G->mu);
+    for (auto& T : G->tasks) T->closed_left = 0;
+    G->closed_total_left = -1;
+  }
+  return st2;
 }
 
 daris_status daris_get_stats(daris_task t, daris_task_stats* out) {
@@ -897,6 +928,70 @@ daris_status daris_profile_layers(daris_task t, daris_part p, int reps, float* m
 }
 
 const char* daris_kernel_name(int32_t kernel_id) { return kernel_name(kernel_id); }
+
+daris_status daris_kernel_timing_start(int every, int max_samples) {
+  if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
+  if (G->nodev) return fail(DARIS_ESTATE, "no device in DARIS_NO_DEVICE mode");
+  if (every < 0 || max_samples < 0 || max_samples > 1000000) return fail(DARIS_EINVAL, "bad arguments");
+  std::lock_guard<std::mutex> lk(G->mu);
+  if (!G->core.idle()) return fail(DARIS_ESTATE, "jobs are active");
+  while ((int)G->tm_pairs.size() < max_samples) {
+    TimingPair tp;
+    HIP_TRY(hipEventCreate(&tp.e0));
+    HIP_TRY(hipEventCreate(&tp.e1));
+    G->tm_pairs.push_back(tp);
+  }
+  G->tm_used = 0;
+  // What an event pair reports for NO work between its two records, on a partition stream: the command processor's
+  // own marker latency, which every sampled launch carries as well.  Median of 65 empty pairs.
+  daris_status st = make_streams();
+  if (st != DARIS_OK) return st;
+  G->tm_overhead_ms = 0;
+  if (G->tm_pairs.size() >= 65) {
+    hipStream_t s0 = G->parts[0].streams[0].s;
+    std::vector<float> v;
+    for (int i = 0; i < 65; ++i) {
+      HIP_TRY(hipEventRecord(G->tm_pairs[i].e0, s0));
+      HIP_TRY(hipEventRecord(G->tm_pairs[i].e1, s0));
+    }
+    HIP_TRY(hipStreamSynchronize(s0));
+    for (int i = 0; i < 65; ++i) {
+      float ms = 0.f;
+      HIP_TRY(hipEventElapsedTime(&ms, G->tm_pairs[i].e0, G->tm_pairs[i].e1));
+      v.push_back(ms);
+    }
+    std::sort(v.begin(), v.end());
+    G->tm_overhead_ms = v[32];
+  }
+  G->tm_every = every;
+  return DARIS_OK;
+}
+
+int32_t daris_kernel_timing_read(int32_t cap, int64_t* launches, double* total_ms, double* total_flops, double* empty_pair_ms) {
+  if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
+  if (cap < K_COUNT || !launches || !total_ms || !total_flops) return fail(DARIS_EINVAL, "arrays must hold %d entries", (int)K_COUNT);
+  daris_status st = daris_run_until_idle();
+  if (st != DARIS_OK) return st;
+  std::lock_guard<std::mutex> lk(G->mu);
+  G->tm_every = 0;
+  for (int i = 0; i < K_COUNT; ++i) {
+    launches[i] = 0;
+    total_ms[i] = 0;
+    total_flops[i] = 0;
+  }
+  for (size_t i = 0; i < G->tm_used; ++i) {
+    TimingPair& tp = G->tm_pairs[i];
+    HIP_TRY(hipEventSynchronize(tp.e1));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, tp.e0, tp.e1));
+    launches[tp.kernel]++;
+    total_ms[tp.kernel] += ms;
+    total_flops[tp.kernel] += tp.flops;
+  }
+  G->tm_used = 0;
+  if (empty_pair_ms) *empty_pair_ms = G->tm_overhead_ms;
+  return K_COUNT;
+}
 
 daris_status daris_probe_cus(daris_part p, int n_groups, int spin, uint32_t* out) {
   daris_status st = check_part(p);

@@ -36,7 +36,8 @@ struct ConvArgs {
   int act;
   int splitk;  // grid.z
   int kchunk;  // LDS-tiled family: k range per split, multiple of the kernel's BK
-  int S, sz, sw;  // wave-tile family: K steps in total, per grid.z slice, per wave
+  int S, sz, sw;  // wave-tile family: K steps in total, per K slice of a workgroup, per wave
+  int MT, NTn, G, xmode;  // wave-tile family: pixel tiles, channel tiles, weight groups (= NTn * splitk), XCD mapping mode
 };
 
 struct DwArgs {
@@ -66,7 +67,7 @@ struct ConvPlan {
   int32_t kernel;  // KernelId
   int wave;        // 1 = wave-tile family, 0 = LDS-tiled family
   int bm, bn, bk, splitk, kchunk;  // LDS-tiled family
-  int tn, nw, S, sz, sw;           // wave-tile family
+  int tn, nw, S, sz, sw, MT, NTn, G, xmode;  // wave-tile family
   int tiles;                       // output tiles per grid.z slice
   size_t ws_bytes;                 // split-K workspace this launch needs
   dim3 grid;
@@ -76,7 +77,8 @@ struct ConvPlan {
 // partition a stage runs in.  Environment variable DARIS_CONV_KERNEL = tile | wave forces one family.
 ConvPlan plan_conv(int M, int N, int Kpad, int bf16);
 
-hipError_t launch_conv(const ConvPlan& pl, const ConvArgs& a, int bf16, hipStream_t s);
+// If t0/t1 are given they are recorded on `s` immediately before and after the main kernel (not the split-K reduce).
+hipError_t launch_conv(const ConvPlan& pl, const ConvArgs& a, int bf16, hipStream_t s, hipEvent_t t0 = nullptr, hipEvent_t t1 = nullptr);
 hipError_t launch_dwconv(const DwArgs& a, int bf16, hipStream_t s);
 hipError_t launch_maxpool(const PoolArgs& a, int bf16, hipStream_t s);
 hipError_t launch_gavgpool(const PoolArgs& a, int bf16, hipStream_t s);

@@ -310,9 +310,30 @@ __global__ __launch_bounds__(NW * 64) void conv_wave_kernel(const ConvArgs p) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int li = lane & 31, lh = lane >> 5;
-  const int m0 = blockIdx.x * 32, nb0 = blockIdx.y * TN;
+  // Workgroup -> (pixel tile mt, weight group g = channel tile + n_tiles * K slice).  Workgroups are handed to the
+  // 8 XCDs round-robin by linear id, and each XCD has its own L2: the mapping keeps all pixel tiles that read the
+  // same weights on one XCD (xmode 1: groups are a multiple of 8) or on 8/G of them (xmode 2), so that a weight
+  // byte is fetched from memory once per XCD that needs it instead of once per pixel tile.
+  int mt, g;
+  {
+    const int L = blockIdx.x, x = L & 7, q = L >> 3;
+    if (p.xmode == 1) {
+      g = (q / p.MT) * 8 + x;
+      mt = q % p.MT;
+    } else if (p.xmode == 2) {
+      const int r = 8 / p.G;
+      g = x / r;
+      mt = q * r + (x % r);
+      if (mt >= p.MT) return;
+    } else {
+      g = L / p.MT;
+      mt = L % p.MT;
+    }
+  }
+  const int zi = g / p.NTn;
+  const int m0 = mt * 32, nb0 = (g - zi * p.NTn) * TN;
 
-  const int s_wg0 = blockIdx.z * p.sz;
+  const int s_wg0 = zi * p.sz;
   const int s_wg1 = min(s_wg0 + p.sz, p.S);
   const int sbeg = min(s_wg0 + wave * p.sw, s_wg1);
   const int nsteps = min(sbeg + p.sw, s_wg1) - sbeg;
@@ -407,7 +428,7 @@ __global__ __launch_bounds__(NW * 64) void conv_wave_kernel(const ConvArgs p) {
     if (mm < p.M && n < p.Cout) {
       const size_t o = (size_t)mm * p.Cout + n;
       if (p.splitk > 1) {  // partial sums of this K slice; splitk_reduce_kernel finishes the layer
-        p.ws[(size_t)blockIdx.z * p.M * p.Cout + o] = vals[r];
+        p.ws[(size_t)zi * p.M * p.Cout + o] = vals[r];
       } else {
         float val = vals[r] + p.bias[n];
         if (p.res) val += load_elem<BF16>(p.res, o);
@@ -483,15 +504,19 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const PoolArgs a) {
   *(uint4*)((unsigned char*)a.y + ((size_t)m * a.C + c0) * ES) = pack<BF16>(best);
 }
 
-// ---- global average pooling: one thread per channel, coalesced across channels ---------------------------------------
+// ---- global average pooling: 64 channels per workgroup, 4 threads per channel over the pixels, LDS sum --------------
 template <bool BF16>
 __global__ __launch_bounds__(256) void gavgpool_kernel(const PoolArgs a) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= a.C) return;
+  __shared__ float part[4][64];
+  const int cl = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + cl;
   const int hw = a.H * a.W;
   float s = 0.f;
-  for (int i = 0; i < hw; ++i) s += load_elem<BF16>(a.x, (size_t)i * a.C + c);
-  store_elem<BF16>(a.y, c, s / (float)hw);
+  if (c < a.C)
+    for (int i = q; i < hw; i += 4) s += load_elem<BF16>(a.x, (size_t)i * a.C + c);
+  part[q][cl] = s;
+  __syncthreads();
+  if (q == 0 && c < a.C) store_elem<BF16>(a.y, c, (part[0][cl] + part[1][cl] + part[2][cl] + part[3][cl]) / (float)hw);
 }
 
 // ---- FC, batch 1: one wave per output, 16-byte loads along K, butterfly reduction ------------------------------------
@@ -638,7 +663,23 @@ static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16) {
   pl.splitk = z;
   pl.tiles = tiles;
   pl.threads = nw * 64;
-  pl.grid = dim3(cdiv(M, 32), nb / tn, z);
+  pl.MT = cdiv(M, 32);
+  pl.NTn = nb / tn;
+  pl.G = pl.NTn * z;
+  if (pl.G % 8 == 0) {
+    pl.xmode = 1;
+    pl.grid = dim3(pl.G * pl.MT, 1, 1);
+  } else if (8 % pl.G == 0) {
+    pl.xmode = 2;
+    pl.grid = dim3(8 * cdiv(pl.MT, 8 / pl.G), 1, 1);
+  } else {
+    pl.xmode = 0;
+    pl.grid = dim3(pl.G * pl.MT, 1, 1);
+  }
+  if (getenv("DARIS_W_XMODE0")) {
+    pl.xmode = 0;
+    pl.grid = dim3(pl.G * pl.MT, 1, 1);
+  }
   pl.ws_bytes = z > 1 ? (size_t)z * M * N * sizeof(float) : 0;
   const int wi = nw == 2 ? 0 : (nw == 4 ? 1 : 2);
   pl.kernel = (bf16 ? K_CONVW_BF16_T1W2 : K_CONVW_F32_T1W2) + (tn - 1) * 3 + wi;
@@ -657,7 +698,8 @@ ConvPlan plan_conv(int M, int N, int Kpad, int bf16) {
 }
 
 template <bool BF16>
-static hipError_t launch_conv_t(const ConvPlan& pl, const ConvArgs& a, hipStream_t s) {
+static hipError_t launch_conv_t(const ConvPlan& pl, const ConvArgs& a, hipStream_t s, hipEvent_t t0, hipEvent_t t1) {
+  if (t0) (void)hipEventRecord(t0, s);
   if (pl.wave) {
     const int variant = pl.kernel - (BF16 ? K_CONVW_BF16_T1W2 : K_CONVW_F32_T1W2);
     switch (variant) {
@@ -681,6 +723,7 @@ static hipError_t launch_conv_t(const ConvPlan& pl, const ConvArgs& a, hipStream
   }
   }
   hipError_t e = hipGetLastError();
+  if (t1) (void)hipEventRecord(t1, s);
   if (e != hipSuccess) return e;
   if (pl.splitk > 1) {
     const size_t total4 = (size_t)a.M * a.Cout / 4;
@@ -691,8 +734,8 @@ static hipError_t launch_conv_t(const ConvPlan& pl, const ConvArgs& a, hipStream
   return e;
 }
 
-hipError_t launch_conv(const ConvPlan& pl, const ConvArgs& a, int bf16, hipStream_t s) {
-  return bf16 ? launch_conv_t<true>(pl, a, s) : launch_conv_t<false>(pl, a, s);
+hipError_t launch_conv(const ConvPlan& pl, const ConvArgs& a, int bf16, hipStream_t s, hipEvent_t t0, hipEvent_t t1) {
+  return bf16 ? launch_conv_t<true>(pl, a, s, t0, t1) : launch_conv_t<false>(pl, a, s, t0, t1);
 }
 
 #define DARIS_LAUNCH_1D(kern, total, ...)                                                                   \
@@ -710,7 +753,7 @@ hipError_t launch_dwconv(const DwArgs& a, int bf16, hipStream_t s) {
 hipError_t launch_maxpool(const PoolArgs& a, int bf16, hipStream_t s) {
   DARIS_LAUNCH_1D(maxpool_kernel, (size_t)a.Ho * a.Wo * (a.C / (bf16 ? 8 : 4)), a);
 }
-hipError_t launch_gavgpool(const PoolArgs& a, int bf16, hipStream_t s) { DARIS_LAUNCH_1D(gavgpool_kernel, (size_t)a.C, a); }
+hipError_t launch_gavgpool(const PoolArgs& a, int bf16, hipStream_t s) { DARIS_LAUNCH_1D(gavgpool_kernel, (size_t)cdiv(a.C, 64) * 256, a); }
 hipError_t launch_fc(const FcArgs& a, int bf16, hipStream_t s) { DARIS_LAUNCH_1D(fc_kernel, (size_t)cdiv(a.Ns, 4) * 256, a); }
 hipError_t launch_ingest(const float* x, void* y, int C, int Cs, int H, int W, int bf16, hipStream_t s) {
   DARIS_LAUNCH_1D(ingest_kernel, (size_t)H * W * Cs, x, y, C, Cs, H * W);
