@@ -1,6 +1,6 @@
 // C ABI of the library: global state, partitions as CU-masked HIP streams, task registration, and the two
-// drivers around the decision core -- a virtual-time event loop and the real-time loop (API thread + one polling
-// scheduler thread) in which a stage boundary is a completion event observed by the host (Sec. III-B1).
+// drivers around the decision core -- a virtual-time event loop and the real-time driver (API thread + one worker
+// thread per stream) in which a stage boundary is a completion event observed by the host (Sec. III-B1).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -75,17 +75,21 @@ struct TimingPair {  // one sampled kernel launch: events recorded around it on 
   double flops = 0;
 };
 
-struct StreamRt {
+struct StreamRt {  // one CU-masked stream and, in real-time mode, the worker thread that feeds and watches it
   hipStream_t s = nullptr;
   hipEvent_t done = nullptr;
-  bool busy = false;
-  int task = -1;
+  std::thread thr;
+  std::condition_variable cv;
+  bool has_work = false;  // a stage handed over by a dispatch pass, not yet picked up by the worker
+  Launch work;
+  JobIo work_io;
+  bool work_sample = false;
 };
 
 struct PartRt {
   int n_cu = 0, start = 0, n_streams = 1;
   uint32_t mask[8] = {0};
-  std::vector<StreamRt> streams;
+  std::vector<std::shared_ptr<StreamRt>> streams;
 };
 
 struct VtEvent {
@@ -117,14 +121,13 @@ struct Global {
   std::priority_queue<VtEvent, std::vector<VtEvent>, std::greater<VtEvent>> heap;
   // real time
   std::mutex mu;
-  std::condition_variable cv_work, cv_idle;
-  std::thread thr;
+  std::condition_variable cv_idle;
   bool stop = false;
   std::chrono::steady_clock::time_point epoch;
   std::string async_error;
   int tm_every = 0;                 // kernel timing: sample every n-th job of a task, 0 = off
   std::vector<TimingPair> tm_pairs;
-  size_t tm_used = 0;
+  std::atomic<size_t> tm_used{0};
   double tm_overhead_ms = 0;        // what an empty event pair reports on a partition stream
   int64_t closed_total_left = -1;  // closed-loop runs: releases left over all tasks, -1 = no common budget
 };
@@ -161,8 +164,9 @@ hipError_t launch_layer(TaskRt& T, int l, void* d_logits, hipStream_t s, bool sa
         a.K = L.K; a.Kpad = L.Kpad; a.M = L.out.H * L.out.W; a.act = L.d.act;
         a.splitk = L.cp.splitk; a.kchunk = L.cp.kchunk; a.S = L.cp.S; a.sz = L.cp.sz; a.sw = L.cp.sw;
         a.MT = L.cp.MT; a.NTn = L.cp.NTn; a.G = L.cp.G; a.xmode = L.cp.xmode;
-        if (sample && G->tm_used < G->tm_pairs.size()) {
-          TimingPair& tp = G->tm_pairs[G->tm_used++];
+        const size_t slot = sample ? G->tm_used.fetch_add(1) : (size_t)-1;
+        if (sample && slot < G->tm_pairs.size()) {
+          TimingPair& tp = G->tm_pairs[slot];
           tp.kernel = L.kernel_id;
           tp.flops = 2.0 * (double)L.macs;
           return launch_conv(L.cp, a, net.bf16, s, tp.e0, tp.e1);
@@ -224,17 +228,21 @@ daris_status issue(const std::vector<Launch>& ls, int64_t t) {
       G->heap.push(VtEvent{t + it->second.second[idx], l.task, l.job});
     }
     if (!G->nodev) {
-      StreamRt& S = G->parts[l.part].streams[l.stream];
+      StreamRt& S = *G->parts[l.part].streams[l.stream];
       auto io = T.io.find(l.job);
       if (io == T.io.end()) return fail(DARIS_ESTATE, "job %u of task %d has no I/O buffers", l.job, l.task);
-      if (G->vt) HIP_TRY(hipStreamWaitEvent(S.s, T.chain, 0));
-      HIP_TRY(launch_stage(T, l.stage, io->second, S.s, G->tm_every > 0 && l.job % (uint32_t)G->tm_every == 0));
+      const bool sample = G->tm_every > 0 && l.job % (uint32_t)G->tm_every == 0;
       if (G->vt) {
+        HIP_TRY(hipStreamWaitEvent(S.s, T.chain, 0));
+        HIP_TRY(launch_stage(T, l.stage, io->second, S.s, sample));
         HIP_TRY(hipEventRecord(T.chain, S.s));
       } else {
-        HIP_TRY(hipEventRecord(S.done, S.s));
-        S.busy = true;
-        S.task = l.task;
+        // real time: the stream's own worker enqueues the kernels and watches the boundary event
+        S.work = l;
+        S.work_io = io->second;
+        S.work_sample = sample;
+        S.has_work = true;
+        S.cv.notify_one();
       }
     }
   }
@@ -294,50 +302,50 @@ JobIo pool_io(TaskRt& T, uint32_t job) {
   return io;
 }
 
-void sched_loop() {
+// Worker of one stream (real-time mode).  It enqueues the kernels of the stage a dispatch pass gave to its stream,
+// records the boundary event, spins on it, and then -- under the scheduler lock -- feeds the completion into the
+// decision core and runs the dispatch pass that follows every input event.  The enqueue and the wait happen
+// outside the lock, so the partitions' launch paths do not serialise.
+void worker_loop(StreamRt* S) {
   (void)hipSetDevice(G->device);
   std::unique_lock<std::mutex> lk(G->mu);
-  while (!G->stop) {
-    bool any_busy = false;
-    for (size_t k = 0; k < G->parts.size(); ++k) {
-      for (StreamRt& S : G->parts[k].streams) {
-        if (!S.busy) continue;
-        any_busy = true;
-        hipError_t q = hipEventQuery(S.done);
-        if (q == hipErrorNotReady) continue;
-        if (q != hipSuccess && G->async_error.empty())
-          G->async_error = std::string("stage completion event: ") + hipGetErrorString(q);
-        const int64_t now = now_ns();
-        const int task = S.task;
-        TaskRt& T = *G->tasks[task];
-        S.busy = false;
-        S.task = -1;
-        const uint32_t job = G->core.active_job(task);
-        const bool job_done = G->core.stage_done(now, task);
-        if (job_done) T.io.erase(job);
-        // a dispatch pass follows every input event (completion, release, migration command)
-        if (dispatch_and_issue(now) != DARIS_OK && G->async_error.empty()) G->async_error = tl_error;
-        if (job_done) {
-          // closed loop: the next job of the task is released the instant this one ends
-          while (T.closed_left > 0 && G->closed_total_left != 0 && !G->core.has_active(task)) {
-            T.closed_left--;
-            if (G->closed_total_left > 0) G->closed_total_left--;
-            const uint32_t next = (uint32_t)G->core.stats(task).released;
-            int32_t dec = 0;
-            if (rt_release_locked(task, pool_io(T, next), now, now, &dec) != DARIS_OK && G->async_error.empty())
-              G->async_error = tl_error;
-          }
-        }
-        if (G->core.idle()) G->cv_idle.notify_all();
+  for (;;) {
+    S->cv.wait(lk, [&] { return G->stop || S->has_work; });
+    if (G->stop) return;
+    const Launch l = S->work;
+    const JobIo io = S->work_io;
+    const bool sample = S->work_sample;
+    S->has_work = false;
+    TaskRt& T = *G->tasks[l.task];
+    lk.unlock();
+    hipError_t e = launch_stage(T, l.stage, io, S->s, sample);
+    if (e == hipSuccess) e = hipEventRecord(S->done, S->s);
+    if (e == hipSuccess) {
+      while ((e = hipEventQuery(S->done)) == hipErrorNotReady) {
+        for (int i = 0; i < 16; ++i) __builtin_ia32_pause();
       }
     }
-    if (!any_busy) {
-      G->cv_work.wait_for(lk, std::chrono::microseconds(500));
-    } else {
-      lk.unlock();
-      std::this_thread::yield();
-      lk.lock();
+    lk.lock();
+    if (e != hipSuccess && G->async_error.empty()) G->async_error = std::string("stage execution: ") + hipGetErrorString(e);
+    const int64_t now = now_ns();
+    const int task = l.task;
+    const uint32_t job = G->core.active_job(task);
+    const bool job_done = G->core.stage_done(now, task);
+    if (job_done) T.io.erase(job);
+    // a dispatch pass follows every input event (completion, release, migration command)
+    if (dispatch_and_issue(now) != DARIS_OK && G->async_error.empty()) G->async_error = tl_error;
+    if (job_done) {
+      // closed loop: the next job of the task is released the instant this one ends
+      while (T.closed_left > 0 && G->closed_total_left != 0 && !G->core.has_active(task)) {
+        T.closed_left--;
+        if (G->closed_total_left > 0) G->closed_total_left--;
+        const uint32_t next = (uint32_t)G->core.stats(task).released;
+        int32_t dec = 0;
+        if (rt_release_locked(task, pool_io(T, next), now, now, &dec) != DARIS_OK && G->async_error.empty())
+          G->async_error = tl_error;
+      }
     }
+    if (G->core.idle()) G->cv_idle.notify_all();
   }
 }
 
@@ -421,14 +429,15 @@ daris_status daris_init(int device, uint64_t seed, int flags) {
 
 daris_status daris_shutdown(void) {
   if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
-  if (G->thr.joinable()) {
-    {
-      std::lock_guard<std::mutex> lk(G->mu);
-      G->stop = true;
-    }
-    G->cv_work.notify_all();
-    G->thr.join();
+  {
+    std::lock_guard<std::mutex> lk(G->mu);
+    G->stop = true;
   }
+  for (PartRt& P : G->parts)
+    for (auto& S : P.streams) {
+      S->cv.notify_all();
+      if (S->thr.joinable()) S->thr.join();
+    }
   if (!G->nodev) {
     (void)hipDeviceSynchronize();
     for (auto& T : G->tasks) free_task(*T);
@@ -437,9 +446,9 @@ daris_status daris_shutdown(void) {
       (void)hipEventDestroy(tp.e1);
     }
     for (PartRt& P : G->parts)
-      for (StreamRt& S : P.streams) {
-        if (S.done) (void)hipEventDestroy(S.done);
-        if (S.s) (void)hipStreamDestroy(S.s);
+      for (auto& S : P.streams) {
+        if (S->done) (void)hipEventDestroy(S->done);
+        if (S->s) (void)hipStreamDestroy(S->s);
       }
   }
   delete G;
@@ -612,8 +621,9 @@ static daris_status make_streams(void) {
   if (G->parts.empty()) return fail(DARIS_ESTATE, "no partition");
   if (!G->nodev) {
     for (PartRt& P : G->parts) {
-      P.streams.resize(P.n_streams);
-      for (StreamRt& S : P.streams) {
+      for (int i = 0; i < P.n_streams; ++i) {
+        P.streams.emplace_back(new StreamRt());
+        StreamRt& S = *P.streams.back();
         HIP_TRY(hipExtStreamCreateWithCUMask(&S.s, 8, P.mask));
         HIP_TRY(hipEventCreateWithFlags(&S.done, hipEventDisableTiming));
       }
@@ -632,7 +642,9 @@ daris_status daris_commit(void) {
   G->core.commit();
   G->committed = true;
   G->epoch = std::chrono::steady_clock::now();
-  if (!G->vt) G->thr = std::thread(sched_loop);
+  if (!G->vt)
+    for (PartRt& P : G->parts)
+      for (auto& S : P.streams) S->thr = std::thread(worker_loop, S.get());
   return DARIS_OK;
 }
 
@@ -673,7 +685,6 @@ daris_status daris_release_job(daris_task t, const void* d_input, void* d_logits
     const int64_t now = now_ns();
     st = rt_release_locked(t, io, now, release_ns < 0 ? now : release_ns, decision);
   }
-  G->cv_work.notify_all();
   return st;
 }
 
@@ -764,8 +775,7 @@ daris_status daris_run_periodic(const int64_t* phase_ns, const int32_t* n_jobs) 
       const uint32_t job = (uint32_t)G->core.stats(r.task).released;
       st = rt_release_locked(r.task, pool_io(T, job), now_ns(), t, nullptr);
     }
-    G->cv_work.notify_all();
-    if (st != DARIS_OK) return st;
+      if (st != DARIS_OK) return st;
   }
   return daris_run_until_idle();
 }
@@ -795,7 +805,6 @@ daris_status daris_run_closed_loop(const int32_t* n_jobs, int64_t total_jobs) {
       }
     }
   }
-  G->cv_work.notify_all();
   daris_status st2 = wait_idle();
   {
     std::lock_guard<std::mutex> lk(G->mu);
@@ -864,7 +873,7 @@ daris_status daris_forward(daris_task t, const void* d_input, void* d_logits, da
   std::lock_guard<std::mutex> lk(G->mu);
   if (G->core.has_active(t)) return fail(DARIS_ESTATE, "task %d has an active job", t);
   TaskRt& T = *G->tasks[t];
-  hipStream_t s = G->parts[p].streams[0].s;
+  hipStream_t s = G->parts[p].streams[0]->s;
   JobIo io;
   io.in = d_input;
   io.out = d_logits;
@@ -900,7 +909,7 @@ daris_status daris_profile_layers(daris_task t, daris_part p, int reps, float* m
   std::lock_guard<std::mutex> lk(G->mu);
   if (G->core.has_active(t)) return fail(DARIS_ESTATE, "task %d has an active job", t);
   TaskRt& T = *G->tasks[t];
-  hipStream_t s = G->parts[p].streams[0].s;
+  hipStream_t s = G->parts[p].streams[0]->s;
   const int n = (int)T.net.layers.size();
   float* scratch_out = nullptr;
   HIP_TRY(hipMalloc((void**)&scratch_out, (size_t)std::max(T.net.n_out, 4) * sizeof(float)));
@@ -948,7 +957,7 @@ daris_status daris_kernel_timing_start(int every, int max_samples) {
   if (st != DARIS_OK) return st;
   G->tm_overhead_ms = 0;
   if (G->tm_pairs.size() >= 65) {
-    hipStream_t s0 = G->parts[0].streams[0].s;
+    hipStream_t s0 = G->parts[0].streams[0]->s;
     std::vector<float> v;
     for (int i = 0; i < 65; ++i) {
       HIP_TRY(hipEventRecord(G->tm_pairs[i].e0, s0));
@@ -1003,7 +1012,7 @@ daris_status daris_probe_cus(daris_part p, int n_groups, int spin, uint32_t* out
   uint32_t* d = nullptr;
   const size_t bytes = (size_t)n_groups * 2 * sizeof(uint32_t);
   HIP_TRY(hipMalloc((void**)&d, bytes));
-  hipStream_t s = G->parts[p].streams[0].s;
+  hipStream_t s = G->parts[p].streams[0]->s;
   hipError_t e = launch_cu_probe(d, n_groups, spin, s);
   if (e == hipSuccess) e = hipStreamSynchronize(s);
   if (e == hipSuccess) e = hipMemcpy(out, d, bytes, hipMemcpyDeviceToHost);
@@ -1019,7 +1028,7 @@ daris_status daris_calibrate_afet(daris_task t, daris_part p, int reps) {
   std::lock_guard<std::mutex> lk(G->mu);
   if (G->core.has_active(t) || G->core.stats(t).released > 0) return fail(DARIS_ESTATE, "calibrate before the first release of task %d", t);
   TaskRt& T = *G->tasks[t];
-  hipStream_t s = G->parts[p].streams[0].s;
+  hipStream_t s = G->parts[p].streams[0]->s;
   const int k = (int)T.net.stage_first.size();
   float* in = nullptr;
   float* out = nullptr;

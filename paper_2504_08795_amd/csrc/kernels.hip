@@ -343,10 +343,19 @@ __global__ __launch_bounds__(NW * 64) void conv_wave_kernel(const ConvArgs p) {
   const bool a_ok = m < p.M;
   const int oy = m / p.Wo, ox = m - oy * p.Wo;
   const int iy0 = oy * p.stride - p.pad, ix0 = ox * p.stride - p.pad;
+  // per-lane walk over k = (tap, ci): inside a tap a step only advances the pointer; a new tap recomputes it
   const int k0 = sbeg * KS + lh * VEC;
   int tap = k0 / p.Cin;
   int ci = k0 - tap * p.Cin;
   int ky = tap / p.kw, kx = tap - ky * p.kw;
+  bool a_valid;
+  const unsigned char* ap;
+  auto enter_tap = [&]() {
+    const int iy = iy0 + ky, ix = ix0 + kx;
+    a_valid = a_ok && ky < p.kh && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
+    ap = xb + ((size_t)(a_valid ? iy * p.W + ix : 0) * p.Cin + ci) * ES;  // always a valid address
+  };
+  enter_tap();
   const unsigned char* wptr[TN];
 #pragma unroll
   for (int j = 0; j < TN; ++j)
@@ -354,23 +363,30 @@ __global__ __launch_bounds__(NW * 64) void conv_wave_kernel(const ConvArgs p) {
 
   uint4 ar[D], br[D][TN];
   auto load = [&](int d) {
-    const int iy = iy0 + ky, ix = ix0 + kx;
-    const bool ok = a_ok && ky < p.kh && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
-    // always load from a valid address and blank the value afterwards: keeps the access a plain global load
-    const size_t off = ok ? ((size_t)(iy * p.W + ix) * p.Cin + ci) * ES : 0;
-    const uint4 v = *(const uint4*)(xb + off);
-    ar[d] = keep_if(ok, v);
+    ar[d] = keep_if(a_valid, *(const uint4*)ap);
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       br[d][j] = *(const uint4*)wptr[j];
       wptr[j] += 1024;
     }
     ci += KS;
-    while (ci >= p.Cin) {
-      ci -= p.Cin;
-      if (++kx == p.kw) { kx = 0; ++ky; }
+    ap += KS * ES;
+    if (ci >= p.Cin) {
+      do {
+        ci -= p.Cin;
+        if (++kx == p.kw) { kx = 0; ++ky; }
+      } while (ci >= p.Cin);
+      enter_tap();
     }
   };
+
+  // bias of this thread's epilogue columns, fetched before the K loop so that its latency is hidden
+  float bias_j[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int n = (nb0 + j) * 32 + li;
+    bias_j[j] = (n < p.Cout) ? p.bias[n] : 0.f;
+  }
 
   f32x16 acc[TN];
 #pragma unroll
@@ -385,17 +401,25 @@ __global__ __launch_bounds__(NW * 64) void conv_wave_kernel(const ConvArgs p) {
 #pragma unroll
     for (int d = 0; d < D; ++d) {
       if (base + d < nsteps) {
+        if (BF16) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          if (BF16) {
+          for (int j = 0; j < TN; ++j)
             acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ar[d]), __builtin_bit_cast(bf16x8, br[d][j]),
                                                              acc[j], 0, 0, 0);
-          } else {
+        } else {
+          // the TN accumulators alternate so that consecutive MFMAs are independent
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
             acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(ar[d].x), __uint_as_float(br[d][j].x), acc[j], 0, 0, 0);
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
             acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(ar[d].y), __uint_as_float(br[d][j].y), acc[j], 0, 0, 0);
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
             acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(ar[d].z), __uint_as_float(br[d][j].z), acc[j], 0, 0, 0);
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
             acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(ar[d].w), __uint_as_float(br[d][j].w), acc[j], 0, 0, 0);
-          }
         }
         if (base + d + D < nsteps) load(d);
       }
@@ -430,7 +454,7 @@ __global__ __launch_bounds__(NW * 64) void conv_wave_kernel(const ConvArgs p) {
       if (p.splitk > 1) {  // partial sums of this K slice; splitk_reduce_kernel finishes the layer
         p.ws[(size_t)zi * p.M * p.Cout + o] = vals[r];
       } else {
-        float val = vals[r] + p.bias[n];
+        float val = vals[r] + bias_j[j];
         if (p.res) val += load_elem<BF16>(p.res, o);
         store_elem<BF16>(p.y, o, apply_act(val, p.act));
       }
