@@ -1,0 +1,152 @@
+"""Experiment driver (the paper's Sec. V protocol on this library): builds a task set on the GPU, runs it
+periodically or saturated, and reports jobs/s, deadline-miss rates (missed / accepted) and response times.
+
+    python -m paper_2504_08795_amd.harness --config 2 --jobs 200
+    python -m paper_2504_08795_amd.harness --config 5 --rate 1.5 --oversub 2.0 --jobs 100 --migrate-every 100
+
+Only argument marshalling and bookkeeping live here; every step of the path runs inside libdaris.so.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import time
+
+import numpy as np
+
+from . import binding as D
+
+
+class GpuTaskSet:
+    """Registers every task of a `workloads.TaskSet` (weights, stages, I/O pools) on device 0."""
+
+    def __init__(self, ts, flags=0, afet=None, streams_per_partition=None, seed=0):
+        import torch
+        import workloads as wl
+        self.ts = ts
+        D.daris_init(0, seed, flags)
+        ns = streams_per_partition or ts.streams_per_partition
+        for n in ts.partitions:
+            p = D.daris_create_partition(n)
+            if ns != 1:
+                D.daris_partition_set_streams(p, ns)
+        self.keep, self.inputs, self.logits, self.nets = [], [], [], []
+        for i, t in enumerate(ts.tasks):
+            layers, shp = wl.build_net(t.net)
+            weights = wl.make_weights(layers, t.seed)
+            dnn, keep = D.make_dnn(layers, weights, shp, t.dtype)
+            h = D.daris_register_task(dnn, t.period_ns, t.deadline_ns, t.priority)
+            assert h == i
+            D.daris_split_stages(h, t.n_stages)
+            xs = wl.make_inputs(shp, t.seed, ts.n_inputs, t.input_dist)
+            self.nets.append((layers, weights, xs, t.dtype))
+            self.inputs.append(torch.from_numpy(xs).cuda())
+            self.logits.append(torch.full((ts.n_jobs, layers[-1].c_out), float("nan"), dtype=torch.float32, device="cuda"))
+            D.daris_task_set_io(h, self.inputs[i], ts.n_inputs, self.logits[i], ts.n_jobs)
+            if afet is not None:
+                for j, a in enumerate(afet[i]):
+                    D.daris_set_afet(h, j, a)
+            del keep
+        self.n_tasks = len(ts.tasks)
+
+    def calibrate(self, reps=3):
+        """AFET of every stage, each task alone on partition (index mod N_c); returns the values."""
+        for i in range(self.n_tasks):
+            D.daris_calibrate_afet(i, i % len(self.ts.partitions), reps)
+        return [[D.daris_get_mret(i, j) for j in range(t.n_stages)] for i, t in enumerate(self.ts.tasks)]
+
+    def stats(self):
+        return [D.daris_get_stats(i) for i in range(self.n_tasks)]
+
+    def close(self):
+        D.daris_shutdown()
+
+
+def summarise(ts, before, after, wall_s):
+    """Per-priority metrics between two `stats()` snapshots."""
+    out = {}
+    for name, prio in (("hp", 1), ("lp", 0)):
+        idx = [i for i, t in enumerate(ts.tasks) if t.priority == prio]
+        d = lambda k: sum(after[i][k] - before[i][k] for i in idx)  # noqa: E731
+        acc, done = d("accepted"), d("completed")
+        out[name] = dict(released=d("released"), accepted=acc, completed=done, missed=d("missed"),
+                         rejected_admission=d("rejected_admission"), rejected_overrun=d("rejected_overrun"),
+                         miss_pct=100.0 * d("missed") / max(acc, 1),
+                         mean_response_ms=round(d("resp_sum_ns") / max(done, 1) / 1e6, 4),
+                         max_response_ms=round(max([after[i]["resp_max_ns"] for i in idx] or [0]) / 1e6, 4))
+    total = sum(after[i]["completed"] - before[i]["completed"] for i in range(len(ts.tasks)))
+    out["completed"] = total
+    out["inferences_per_s"] = round(total / wall_s, 2)
+    out["wall_s"] = round(wall_s, 4)
+    return out
+
+
+def run_periodic(g: GpuTaskSet, n_jobs, migrate_every=0, seed=1):
+    """Periodic releases at the nominal periods.  With migrate_every > 0 the run is cut into chunks and a seeded LP
+    task is forced to a seeded other partition between chunks (one migration per `migrate_every` completed jobs)."""
+    ts = g.ts
+    before = g.stats()
+    t0 = time.perf_counter()
+    if migrate_every <= 0:
+        D.daris_run_periodic(None, [n_jobs] * g.n_tasks)
+    else:
+        rng = np.random.Generator(np.random.PCG64(seed))
+        lp = [i for i, t in enumerate(ts.tasks) if t.priority == 0]
+        chunk = max(1, migrate_every // g.n_tasks)
+        done = 0
+        while done < n_jobs:
+            step = min(chunk, n_jobs - done)
+            D.daris_run_periodic(None, [step] * g.n_tasks)
+            done += step
+            if lp and done < n_jobs:
+                t = int(rng.choice(lp))
+                cur = D.daris_get_partition(t)
+                others = [p for p in range(len(ts.partitions)) if p != cur]
+                if others:
+                    D.daris_migrate(t, int(rng.choice(others)))
+    wall = time.perf_counter() - t0
+    return summarise(ts, before, g.stats(), wall)
+
+
+def run_saturated(g: GpuTaskSet, total_jobs):
+    before = g.stats()
+    t0 = time.perf_counter()
+    D.daris_run_closed_loop([total_jobs] * g.n_tasks, total_jobs)
+    wall = time.perf_counter() - t0
+    return summarise(g.ts, before, g.stats(), wall)
+
+
+def main():
+    import workloads as wl
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--jobs", type=int, default=100, help="jobs per task (periodic) / total jobs x tasks (saturated)")
+    ap.add_argument("--rate", type=float, default=1.0, help="config 5: release-rate scale")
+    ap.add_argument("--oversub", type=float, default=2.0, help="config 5: oversubscription level")
+    ap.add_argument("--streams", type=int, default=1, help="streams per partition (N_s)")
+    ap.add_argument("--stages", type=int, default=0, help="override the stage count of every task (1 = no staging)")
+    ap.add_argument("--flags", default="", help="comma list of no_last,no_prior,no_fixed,hp_admission")
+    ap.add_argument("--migrate-every", type=int, default=0)
+    ap.add_argument("--saturated", action="store_true")
+    a = ap.parse_args()
+    ts = wl.make_taskset(a.config, n_jobs=a.jobs, rate_scale=a.rate, oversub=a.oversub)
+    if a.stages:
+        for t in ts.tasks:
+            t.n_stages = a.stages
+    fl = 0
+    for name in filter(None, a.flags.split(",")):
+        fl |= {"no_last": D.NO_LAST, "no_prior": D.NO_PRIOR, "no_fixed": D.NO_FIXED, "hp_admission": D.HP_ADMISSION}[name]
+    g = GpuTaskSet(ts, flags=fl, streams_per_partition=a.streams)
+    try:
+        g.calibrate()
+        D.daris_commit()
+        res = run_saturated(g, a.jobs * g.n_tasks) if a.saturated else run_periodic(g, a.jobs, a.migrate_every)
+        res["config"] = dict(name=ts.name, partitions=ts.partitions, streams=a.streams, tasks=g.n_tasks, rate=a.rate, oversub=a.oversub,
+                             stages=[t.n_stages for t in ts.tasks], flags=a.flags)
+        print(json.dumps(res))
+    finally:
+        g.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -8,6 +8,7 @@ import torch
 import paper_2504_08795_amd as D
 import workloads as wl
 from gpu_helpers import TOL, rel_err
+from paper_2504_08795_amd import harness
 from lib_helpers import load_et
 from oracle import des
 from oracle import forward as F
@@ -16,31 +17,12 @@ from sched_helpers import check_trace_invariants
 pytestmark = pytest.mark.gpu
 
 
-class GpuTaskSet:
+class GpuTaskSet(harness.GpuTaskSet):
+    """The harness's task-set registration plus the oracle-side checks."""
+
     def __init__(self, ts, flags=0, afet=None):
-        self.ts = ts
-        D.daris_init(0, wl.tasksets.SEED, flags)
-        for n in ts.partitions:
-            D.daris_create_partition(n)
-        self.keep, self.inputs, self.logits, self.want = [], [], [], []
-        self.nets = []
-        for i, t in enumerate(ts.tasks):
-            layers, shp = wl.build_net(t.net)
-            weights = wl.make_weights(layers, t.seed)
-            dnn, keep = D.make_dnn(layers, weights, shp, t.dtype)
-            self.keep.append(keep)
-            h = D.daris_register_task(dnn, t.period_ns, t.deadline_ns, t.priority)
-            assert h == i
-            D.daris_split_stages(h, t.n_stages)
-            xs = wl.make_inputs(shp, t.seed, ts.n_inputs, t.input_dist)
-            self.nets.append((layers, weights, xs, t.dtype))
-            n_out = layers[-1].c_out
-            self.inputs.append(torch.from_numpy(xs).cuda())
-            self.logits.append(torch.full((ts.n_jobs, n_out), float("nan"), dtype=torch.float32, device="cuda"))
-            D.daris_task_set_io(h, self.inputs[i], ts.n_inputs, self.logits[i], ts.n_jobs)
-            if afet is not None:
-                for j, a in enumerate(afet[i]):
-                    D.daris_set_afet(h, j, a)
+        super().__init__(ts, flags=flags, afet=afet, seed=wl.tasksets.SEED)
+        self.want = []
 
     def oracle_logits(self):
         if not self.want:
@@ -65,10 +47,6 @@ class GpuTaskSet:
         for task, job in rejected:
             assert np.isnan(outs[task][job]).all()
         return worst, len(done)
-
-    def close(self):
-        D.daris_shutdown()
-
 
 def oracle_model(ts, afet, n_streams=None):
     tasks = [des.TaskParam(t.period_ns, t.deadline_ns, t.priority, list(afet[i])) for i, t in enumerate(ts.tasks)]
@@ -106,9 +84,13 @@ def _replay_and_check(ts, afet, got):
     return m
 
 
-@pytest.mark.parametrize("config,n_jobs", [(1, 20), (2, 25)])
+@pytest.mark.parametrize("config,n_jobs", [(1, 20), (2, 25), (3, 8), (4, 5)])
 def test_real_time_periodic_run_replays_through_oracle(config, n_jobs):
+    """Configs 3 (6x ResNet-50 bf16, 4 partitions) and 4 (mixed 8 tasks incl. VGG-16 and MobileNetV2) run with few
+    jobs and two inputs per task so that the oracle's share stays within seconds."""
     ts = wl.make_taskset(config, n_jobs=n_jobs)
+    if config >= 3:
+        ts.n_inputs = 2
     g = GpuTaskSet(ts)
     try:
         for i in range(len(ts.tasks)):
@@ -172,3 +154,25 @@ def test_cu_masks_are_honoured():
             assert len(distinct) <= n
     finally:
         D.daris_shutdown()
+
+
+def test_stress_set_with_forced_migrations_between_chunks():
+    """Config 5 shape at one sweep point (rate 1.0, oversubscription 2.0): 4 HP ResNet-50 bf16 + 12 LP fp32 tasks on 4
+    partitions, periodic releases in two chunks with forced migrations between them; trace replays through the oracle and
+    every completed job's logits match."""
+    ts = wl.make_taskset(5, n_jobs=4, rate_scale=1.0, oversub=2.0)
+    ts.n_inputs = 1
+    g = GpuTaskSet(ts)
+    try:
+        for i in range(len(ts.tasks)):
+            D.daris_calibrate_afet(i, i % 4, 2)
+        afet = [[D.daris_get_mret(i, j) for j in range(t.n_stages)] for i, t in enumerate(ts.tasks)]
+        res = harness.run_periodic(g, 4, migrate_every=32, seed=3)
+        got = D.trace_read_all()
+        m = _replay_and_check(ts, afet, got)
+        assert sum(1 for r in got if r[2] == des.CMD_MIGRATE) >= 1
+        worst, n = g.check_logits(got)
+        assert res["hp"]["missed"] == 0 and res["hp"]["completed"] == 16
+        print(f"stress point: {n} jobs, worst logits error {worst:.3e}, {res['inferences_per_s']} inf/s, LP miss {res['lp']['miss_pct']:.1f} %")
+    finally:
+        g.close()
