@@ -232,6 +232,10 @@ int32_t daris_kernel_timing_read(int32_t cap, int64_t* launches, double* total_m
  * them as the task's AFET values. */
 daris_status daris_calibrate_afet(daris_task t, daris_part p, int reps);
 
+/* Average full-load execution time (Sec. IV-A1): like daris_calibrate_afet, but while every other stream of every
+ * partition runs one forward pass of a distinct other task drawn with the generator seeded by daris_init's seed;
+ * the per-stage averages over `reps` runs become the task's AFET values.  Call while no job is active. */
+daris_status daris_calibrate_afet_loaded(daris_task t, daris_part p, int reps);
 /* Mask probing: launch n_groups (<= 65536) short workgroups on stream 0 of partition p; out = host
  * uint32[2 * n_groups] receives, per workgroup, the XCC (die) id and the hardware id register of the compute unit
  * it ran on.  `spin` (0..100000) bounds a sleep loop that keeps workgroups resident so that they spread over

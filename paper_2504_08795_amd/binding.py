@@ -78,6 +78,7 @@ _SIGS = {
     "daris_profile_layers": (C.c_int32, [C.c_int32, C.c_int32, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_int32), C.POINTER(C.c_double)]),
     "daris_kernel_name": (C.c_char_p, [C.c_int32]),
     "daris_calibrate_afet": (C.c_int32, [C.c_int32, C.c_int32, C.c_int]),
+    "daris_calibrate_afet_loaded": (C.c_int32, [C.c_int32, C.c_int32, C.c_int]),
     "daris_kernel_timing_start": (C.c_int32, [C.c_int, C.c_int]),
     "daris_kernel_timing_read": (C.c_int32, [C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "daris_probe_cus": (C.c_int32, [C.c_int32, C.c_int, C.c_int, C.POINTER(C.c_uint32)]),
@@ -295,6 +296,10 @@ def daris_kernel_timing_read():
 
 def daris_calibrate_afet(t, p, reps=5):
     return _chk(lib().daris_calibrate_afet(t, p, reps))
+
+
+def daris_calibrate_afet_loaded(t, p, reps=5):
+    return _chk(lib().daris_calibrate_afet_loaded(t, p, reps))
 
 
 def daris_probe_cus(p, n_groups=2048, spin=2000):

@@ -1062,4 +1062,79 @@ daris_status daris_calibrate_afet(daris_task t, daris_part p, int reps) {
   return DARIS_OK;
 }
 
+// Sec. IV-A1: AFET = average execution time of the target while other tasks run in the remaining streams.
+daris_status daris_calibrate_afet_loaded(daris_task t, daris_part p, int reps) {
+  daris_status st = direct_checks(t, p);
+  if (st != DARIS_OK) return st;
+  if (reps < 1) return fail(DARIS_EINVAL, "reps must be >= 1");
+  std::lock_guard<std::mutex> lk(G->mu);
+  for (int i = 0; i < (int)G->tasks.size(); ++i)
+    if (G->core.has_active(i)) return fail(DARIS_ESTATE, "calibrate while no job is active");
+  if (G->core.stats(t).released > 0) return fail(DARIS_ESTATE, "calibrate before the first release of task %d", t);
+  const int nt = (int)G->tasks.size();
+  // one zero-filled input and one logits buffer per task
+  std::vector<float*> in(nt, nullptr), out(nt, nullptr);
+  auto cleanup = [&]() {
+    for (float* q : in) if (q) (void)hipFree(q);
+    for (float* q : out) if (q) (void)hipFree(q);
+  };
+  for (int i = 0; i < nt; ++i) {
+    const NetPlan& n = G->tasks[i]->net;
+    const size_t ie = (size_t)n.in_c * n.in_h * n.in_w;
+    hipError_t e = hipMalloc((void**)&in[i], ie * sizeof(float));
+    if (e == hipSuccess) e = hipMemset(in[i], 0, ie * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc((void**)&out[i], (size_t)std::max(n.n_out, 4) * sizeof(float));
+    if (e != hipSuccess) {
+      cleanup();
+      return fail(DARIS_ENOMEM, "calibration buffers: %s", hipGetErrorString(e));
+    }
+  }
+  TaskRt& T = *G->tasks[t];
+  hipStream_t s = G->parts[p].streams[0]->s;
+  const int k = (int)T.net.stage_first.size();
+  std::vector<int64_t> sum(k, 0);
+  uint64_t rng = G->seed * 6364136223846793005ull + 1442695040888963407ull + (uint64_t)t;
+  daris_status result = DARIS_OK;
+  for (int r = 0; r <= reps && result == DARIS_OK; ++r) {  // run 0 is a warm-up
+    // every other stream gets one whole forward pass of a distinct, randomly drawn other task
+    std::vector<int> others;
+    for (int i = 0; i < nt; ++i)
+      if (i != t) others.push_back(i);
+    for (size_t q = 0; q < G->parts.size() && result == DARIS_OK; ++q)
+      for (size_t si = 0; si < G->parts[q].streams.size() && result == DARIS_OK; ++si) {
+        if ((int)q == p && si == 0) continue;
+        if (others.empty()) break;
+        rng = rng * 6364136223846793005ull + 1442695040888963407ull;
+        const size_t pick = (size_t)((rng >> 33) % others.size());
+        const int o = others[pick];
+        others.erase(others.begin() + pick);
+        TaskRt& O = *G->tasks[o];
+        JobIo io;
+        io.in = in[o];
+        io.out = out[o];
+        for (int j = 0; j < (int)O.net.stage_first.size(); ++j) {
+          hipError_t e = launch_stage(O, j, io, G->parts[q].streams[si]->s);
+          if (e != hipSuccess) result = fail(DARIS_EHIP, "calibration load: %s", hipGetErrorString(e));
+        }
+      }
+    JobIo io;
+    io.in = in[t];
+    io.out = out[t];
+    for (int j = 0; j < k && result == DARIS_OK; ++j) {
+      auto t0 = std::chrono::steady_clock::now();
+      hipError_t e = launch_stage(T, j, io, s);
+      if (e == hipSuccess) e = hipStreamSynchronize(s);
+      auto t1 = std::chrono::steady_clock::now();
+      if (e != hipSuccess) result = fail(DARIS_EHIP, "calibration: %s", hipGetErrorString(e));
+      if (r > 0) sum[j] += std::chrono::duration_cast<std::chrono::nanoseconds>(t1 - t0).count();
+    }
+    hipError_t e = hipDeviceSynchronize();
+    if (e != hipSuccess && result == DARIS_OK) result = fail(DARIS_EHIP, "calibration: %s", hipGetErrorString(e));
+  }
+  cleanup();
+  if (result != DARIS_OK) return result;
+  for (int j = 0; j < k; ++j) G->core.set_afet(t, j, std::max<int64_t>(sum[j] / reps, 1));
+  return DARIS_OK;
+}
+
 }  // extern "C"

@@ -31,9 +31,12 @@ class GpuTaskSet:
             if ns != 1:
                 D.daris_partition_set_streams(p, ns)
         self.keep, self.inputs, self.logits, self.nets = [], [], [], []
+        cache = {}
         for i, t in enumerate(ts.tasks):
             layers, shp = wl.build_net(t.net)
-            weights = wl.make_weights(layers, t.seed)
+            if (t.net, t.seed) not in cache:
+                cache[(t.net, t.seed)] = wl.make_weights(layers, t.seed)
+            weights = cache[(t.net, t.seed)]
             dnn, keep = D.make_dnn(layers, weights, shp, t.dtype)
             h = D.daris_register_task(dnn, t.period_ns, t.deadline_ns, t.priority)
             assert h == i
@@ -49,10 +52,11 @@ class GpuTaskSet:
             del keep
         self.n_tasks = len(ts.tasks)
 
-    def calibrate(self, reps=3):
-        """AFET of every stage, each task alone on partition (index mod N_c); returns the values."""
+    def calibrate(self, reps=3, loaded=False):
+        """AFET of every stage, each task on partition (index mod N_c), alone or (Sec. IV-A1) while the other
+        streams run other tasks; returns the values."""
         for i in range(self.n_tasks):
-            D.daris_calibrate_afet(i, i % len(self.ts.partitions), reps)
+            (D.daris_calibrate_afet_loaded if loaded else D.daris_calibrate_afet)(i, i % len(self.ts.partitions), reps)
         return [[D.daris_get_mret(i, j) for j in range(t.n_stages)] for i, t in enumerate(self.ts.tasks)]
 
     def stats(self):
@@ -128,8 +132,21 @@ def main():
     ap.add_argument("--flags", default="", help="comma list of no_last,no_prior,no_fixed,hp_admission")
     ap.add_argument("--migrate-every", type=int, default=0)
     ap.add_argument("--saturated", action="store_true")
+    ap.add_argument("--loaded-afet", action="store_true", help="AFET measured while the other streams run other tasks (Sec. IV-A1)")
+    ap.add_argument("--paper-set", default="", help="Table-II-shaped set of this DNN type instead of --config (e.g. resnet18)")
+    ap.add_argument("--n-high", type=int, default=17)
+    ap.add_argument("--n-low", type=int, default=34)
+    ap.add_argument("--task-jps", type=float, default=30.0, help="jobs per second released by every task of a --paper-set")
+    ap.add_argument("--nc", type=int, default=6, help="--paper-set: number of partitions N_c")
+    ap.add_argument("--os", default="2", help="--paper-set: oversubscription OS as a fraction, e.g. 3/2 (1 <= OS <= N_c)")
     a = ap.parse_args()
-    ts = wl.make_taskset(a.config, n_jobs=a.jobs, rate_scale=a.rate, oversub=a.oversub)
+    if a.paper_set:
+        # Table II shape: N_c equal partitions of ceil_even(OS * 256 / N_c) CUs (Sec. III-C2), OS given as a fraction
+        num, den = (int(v) for v in (a.os.split("/") + ["1"])[:2])
+        n_cu = min(256, D.daris_cu_per_partition(num, den, 256, a.nc))
+        ts = wl.make_paper_taskset(a.paper_set, a.n_high, a.n_low, a.task_jps, [n_cu] * a.nc, n_jobs=a.jobs, n_stages=a.stages or 4)
+    else:
+        ts = wl.make_taskset(a.config, n_jobs=a.jobs, rate_scale=a.rate, oversub=a.oversub)
     if a.stages:
         for t in ts.tasks:
             t.n_stages = a.stages
@@ -138,7 +155,7 @@ def main():
         fl |= {"no_last": D.NO_LAST, "no_prior": D.NO_PRIOR, "no_fixed": D.NO_FIXED, "hp_admission": D.HP_ADMISSION}[name]
     g = GpuTaskSet(ts, flags=fl, streams_per_partition=a.streams)
     try:
-        g.calibrate()
+        g.calibrate(loaded=a.loaded_afet)
         D.daris_commit()
         res = run_saturated(g, a.jobs * g.n_tasks) if a.saturated else run_periodic(g, a.jobs, a.migrate_every)
         res["config"] = dict(name=ts.name, partitions=ts.partitions, streams=a.streams, tasks=g.n_tasks, rate=a.rate, oversub=a.oversub,

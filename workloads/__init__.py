@@ -6,4 +6,4 @@ oracle receive what it produces as plain arrays and integers.
 """
 from .nets import Layer, NETS, build_net, layer_shapes, net_macs, net_params  # noqa: F401
 from .tensors import make_weights, make_inputs, fold_bn  # noqa: F401
-from .tasksets import TaskSpec, TaskSet, make_taskset, virtual_et_table, HP, LP  # noqa: F401
+from .tasksets import TaskSpec, TaskSet, make_taskset, make_paper_taskset, virtual_et_table, HP, LP  # noqa: F401

@@ -109,3 +109,15 @@ def virtual_et_table(ts: TaskSet, seed: int = SEED, *, load_scale: float = 1.0, 
             per_stage.append(arr)
         table.append(per_stage)
     return table
+
+
+def make_paper_taskset(net: str, n_high: int, n_low: int, task_jps: float, partitions, *, n_jobs: int = 100, seed: int = SEED,
+                       dtype: str = "fp32", n_stages: int = 4, weight_sets: int = 8) -> TaskSet:
+    """Task set shaped like the paper's Table II: n_high HP + n_low LP tasks of one DNN type, each releasing `task_jps`
+    jobs per second (implicit deadlines), on the given partition sizes.  Tasks cycle through `weight_sets` distinct seeds
+    so that set-up time stays bounded for dozens of tasks."""
+    period = int(round(1e9 / task_jps))
+    tasks = []
+    for i in range(n_high + n_low):
+        tasks.append(TaskSpec(net, dtype, HP if i < n_high else LP, period, period, n_stages, seed + 50_000 + (i % weight_sets)))
+    return TaskSet(f"paper_{net}_{n_high}h{n_low}l_{task_jps:g}jps", tasks, list(partitions), n_jobs, n_inputs=2)
