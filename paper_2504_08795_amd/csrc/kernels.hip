@@ -142,6 +142,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void conv_igemm_kernel(
   int ky = tap / p.kw, kx = tap - ky * p.kw;
 
   uint4 areg[A_LD], breg[B_LD];
+  bool aval[A_LD];
 
   auto gload = [&]() {
 #pragma unroll
@@ -150,13 +151,12 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void conv_igemm_kernel(
       const bool ok = a_ok[r] && ky < p.kh && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
       // always load from a valid address and blank the value afterwards: keeps the access a plain global load
       const size_t off = ok ? ((size_t)(iy * p.W + ix) * p.Cin + ci) * ES : 0;
-      const uint4 v = *(const uint4*)(xb + off);
-      areg[r] = keep_if(ok, v);
+      areg[r] = *(const uint4*)(xb + off);
+      aval[r] = ok;
     }
 #pragma unroll
     for (int r = 0; r < B_LD; ++r) {
-      const uint4 v = *(const uint4*)(wb + (b_ok[r] ? b_off[r] : (size_t)0));
-      breg[r] = keep_if(b_ok[r], v);
+      breg[r] = *(const uint4*)(wb + (b_ok[r] ? b_off[r] : (size_t)0));
       b_off[r] += (size_t)BK * ES;
     }
     ci += BK;
@@ -169,12 +169,12 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void conv_igemm_kernel(
 #pragma unroll
     for (int r = 0; r < A_LD; ++r) {
       const int row = (tid + r * NT) / KV;
-      *(uint4*)(&lds[buf][row * ROWB + kv * 16]) = areg[r];
+      *(uint4*)(&lds[buf][row * ROWB + kv * 16]) = keep_if(aval[r], areg[r]);  // blanked here, not at the load
     }
 #pragma unroll
     for (int r = 0; r < B_LD; ++r) {
       const int row = (tid + r * NT) / KV;
-      *(uint4*)(&lds[buf][(BM + row) * ROWB + kv * 16]) = breg[r];
+      *(uint4*)(&lds[buf][(BM + row) * ROWB + kv * 16]) = keep_if(b_ok[r], breg[r]);
     }
   };
 
@@ -295,7 +295,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 // wave order.  With grid.z > 1 the workgroups of one tile also split K and write partial sums to the workspace,
 // which splitk_reduce_kernel adds in z order (a device-wide fence per workgroup for an in-kernel reduction was
 // measured to cost several times the extra launch).
-template <bool BF16, int TN, int NW>
+template <bool BF16, int TN, int NW, bool ALIGNED>
 __global__ __launch_bounds__(NW * 64) void conv_wave_kernel(const ConvArgs p) {
   constexpr int ES = BF16 ? 2 : 4;
   constexpr int VEC = 16 / ES;
@@ -308,7 +308,8 @@ __global__ __launch_bounds__(NW * 64) void conv_wave_kernel(const ConvArgs p) {
 
   __shared__ float red[NW * TILE];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the K loop's control flow scalar
   const int li = lane & 31, lh = lane >> 5;
   // Workgroup -> (pixel tile mt, weight group g = channel tile + n_tiles * K slice).  Workgroups are handed to the
   // 8 XCDs round-robin by linear id, and each XCD has its own L2: the mapping keeps all pixel tiles that read the
@@ -343,8 +344,11 @@ __global__ __launch_bounds__(NW * 64) void conv_wave_kernel(const ConvArgs p) {
   const bool a_ok = m < p.M;
   const int oy = m / p.Wo, ox = m - oy * p.Wo;
   const int iy0 = oy * p.stride - p.pad, ix0 = ox * p.stride - p.pad;
-  // per-lane walk over k = (tap, ci): inside a tap a step only advances the pointer; a new tap recomputes it
-  const int k0 = sbeg * KS + lh * VEC;
+  // Walk over k = (tap, ci).  ALIGNED (Cin a multiple of KS): both lane halves are always in the same tap, so the
+  // walk state (ky, kx, ci) is wave-uniform and lives in scalars; a lane adds its half's offset lh*VEC.  Otherwise
+  // (the padded network input, Cin < KS) every lane walks on its own.  Inside a tap a step only advances the
+  // pointer; a new tap recomputes pointer and validity.
+  const int k0 = sbeg * KS + (ALIGNED ? 0 : lh * VEC);
   int tap = k0 / p.Cin;
   int ci = k0 - tap * p.Cin;
   int ky = tap / p.kw, kx = tap - ky * p.kw;
@@ -353,7 +357,7 @@ __global__ __launch_bounds__(NW * 64) void conv_wave_kernel(const ConvArgs p) {
   auto enter_tap = [&]() {
     const int iy = iy0 + ky, ix = ix0 + kx;
     a_valid = a_ok && ky < p.kh && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
-    ap = xb + ((size_t)(a_valid ? iy * p.W + ix : 0) * p.Cin + ci) * ES;  // always a valid address
+    ap = xb + ((size_t)(a_valid ? iy * p.W + ix : 0) * p.Cin + ci + (ALIGNED ? lh * VEC : 0)) * ES;  // always a valid address
   };
   enter_tap();
   const unsigned char* wptr[TN];
@@ -362,21 +366,25 @@ __global__ __launch_bounds__(NW * 64) void conv_wave_kernel(const ConvArgs p) {
     wptr[j] = (const unsigned char*)p.w + (((size_t)(nb0 + j) * p.S + sbeg) * 64 + lane) * 16;
 
   uint4 ar[D], br[D][TN];
+  bool av[D];  // validity of slot d's A vector; the blanking is applied when the slot is consumed, so that a load's
+               // result is not touched (and not waited for) until D-1 later steps have been issued
   auto load = [&](int d) {
-    ar[d] = keep_if(a_valid, *(const uint4*)ap);
+    ar[d] = *(const uint4*)ap;
+    av[d] = a_valid;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       br[d][j] = *(const uint4*)wptr[j];
       wptr[j] += 1024;
     }
     ci += KS;
-    ap += KS * ES;
-    if (ci >= p.Cin) {
+    if (ci >= p.Cin) {  // uniform branch when ALIGNED
       do {
         ci -= p.Cin;
         if (++kx == p.kw) { kx = 0; ++ky; }
-      } while (ci >= p.Cin);
+      } while (!ALIGNED && ci >= p.Cin);
       enter_tap();
+    } else {
+      ap += KS * ES;
     }
   };
 
@@ -394,37 +402,48 @@ __global__ __launch_bounds__(NW * 64) void conv_wave_kernel(const ConvArgs p) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
 
+  auto compute = [&](int d) {
+    const uint4 a4 = keep_if(av[d], ar[d]);
+    if (BF16) {
 #pragma unroll
-  for (int d = 0; d < D; ++d)
-    if (d < nsteps) load(d);
-  for (int base = 0; base < nsteps; base += D) {
+      for (int j = 0; j < TN; ++j)
+        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a4), __builtin_bit_cast(bf16x8, br[d][j]),
+                                                         acc[j], 0, 0, 0);
+    } else {
+      // the TN accumulators alternate so that consecutive MFMAs are independent
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a4.x), __uint_as_float(br[d][j].x), acc[j], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a4.y), __uint_as_float(br[d][j].y), acc[j], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a4.z), __uint_as_float(br[d][j].z), acc[j], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a4.w), __uint_as_float(br[d][j].w), acc[j], 0, 0, 0);
+    }
+  };
+
+  // Software pipeline, D steps deep.  Every load in the prologue and in the steady-state loop is unconditional and
+  // the loop is straight-line (compute slot d, refill slot d), so the compiler can count the loads in flight and
+  // wait only for the oldest slot.  Refills past the end of the wave's K slice fetch valid memory that is never used
+  // (the weight buffer carries D KiB of slack; the A pointer always points into the input); only the computes of the
+  // ragged tail are conditional.
+#pragma unroll
+  for (int d = 0; d < D; ++d) load(d);
+  int done = 0;
+  for (; done + D <= nsteps; done += D) {
 #pragma unroll
     for (int d = 0; d < D; ++d) {
-      if (base + d < nsteps) {
-        if (BF16) {
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ar[d]), __builtin_bit_cast(bf16x8, br[d][j]),
-                                                             acc[j], 0, 0, 0);
-        } else {
-          // the TN accumulators alternate so that consecutive MFMAs are independent
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(ar[d].x), __uint_as_float(br[d][j].x), acc[j], 0, 0, 0);
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(ar[d].y), __uint_as_float(br[d][j].y), acc[j], 0, 0, 0);
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(ar[d].z), __uint_as_float(br[d][j].z), acc[j], 0, 0, 0);
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(ar[d].w), __uint_as_float(br[d][j].w), acc[j], 0, 0, 0);
-        }
-        if (base + d + D < nsteps) load(d);
-      }
+      compute(d);
+      load(d);
     }
   }
+#pragma unroll
+  for (int d = 0; d < D; ++d)
+    if (done + d < nsteps) compute(d);
 
   // --- sum the NW partial tiles in wave order; tile element e = (j*16 + v)*64 + lane --------------------------------
 #pragma unroll
@@ -726,15 +745,22 @@ static hipError_t launch_conv_t(const ConvPlan& pl, const ConvArgs& a, hipStream
   if (t0) (void)hipEventRecord(t0, s);
   if (pl.wave) {
     const int variant = pl.kernel - (BF16 ? K_CONVW_BF16_T1W2 : K_CONVW_F32_T1W2);
+    const bool aligned = a.Cin % (BF16 ? 16 : 8) == 0;  // a K step never straddles a filter tap
+#define DARIS_WAVE_CASE(idx, TN_, NW_)                                                                            \
+  case idx:                                                                                                       \
+    if (aligned) hipLaunchKernelGGL((conv_wave_kernel<BF16, TN_, NW_, true>), pl.grid, dim3(NW_ * 64), 0, s, a);    \
+    else hipLaunchKernelGGL((conv_wave_kernel<BF16, TN_, NW_, false>), pl.grid, dim3(NW_ * 64), 0, s, a);           \
+    break;
     switch (variant) {
-      case 0: hipLaunchKernelGGL((conv_wave_kernel<BF16, 1, 2>), pl.grid, dim3(128), 0, s, a); break;
-      case 1: hipLaunchKernelGGL((conv_wave_kernel<BF16, 1, 4>), pl.grid, dim3(256), 0, s, a); break;
-      case 2: hipLaunchKernelGGL((conv_wave_kernel<BF16, 1, 8>), pl.grid, dim3(512), 0, s, a); break;
-      case 3: hipLaunchKernelGGL((conv_wave_kernel<BF16, 2, 2>), pl.grid, dim3(128), 0, s, a); break;
-      case 4: hipLaunchKernelGGL((conv_wave_kernel<BF16, 2, 4>), pl.grid, dim3(256), 0, s, a); break;
-      case 5: hipLaunchKernelGGL((conv_wave_kernel<BF16, 2, 8>), pl.grid, dim3(512), 0, s, a); break;
+      DARIS_WAVE_CASE(0, 1, 2)
+      DARIS_WAVE_CASE(1, 1, 4)
+      DARIS_WAVE_CASE(2, 1, 8)
+      DARIS_WAVE_CASE(3, 2, 2)
+      DARIS_WAVE_CASE(4, 2, 4)
+      DARIS_WAVE_CASE(5, 2, 8)
       default: return hipErrorInvalidValue;
     }
+#undef DARIS_WAVE_CASE
   } else {
   const int variant = pl.kernel - (BF16 ? K_CONV_BF16_128x64 : K_CONV_F32_128x64);
   switch (variant) {

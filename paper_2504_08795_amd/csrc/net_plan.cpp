@@ -220,7 +220,7 @@ void pack_conv(const NetPlan& net, const LayerPlan& L, const float* w, const flo
     const int vec = bf ? 8 : 4, ks = 2 * vec, S = L.cp.S;
     const int nblocks = (L.out.Cs + 31) / 32;
     const int nb_alloc = (nblocks + L.cp.tn - 1) / L.cp.tn * L.cp.tn;
-    wp->assign((size_t)nb_alloc * S * 64 * 16, 0);
+    wp->assign((size_t)nb_alloc * S * 64 * 16 + 8 * 1024, 0);  // + slack for the kernel's pipeline refills past the last step
     for (int o = 0; o < d.c_out; ++o)
       for (int ci = 0; ci < d.c_in; ++ci)
         for (int t = 0; t < kk; ++t) {
