@@ -164,6 +164,7 @@ hipError_t launch_layer(TaskRt& T, int l, void* d_logits, hipStream_t s, bool sa
         a.K = L.K; a.Kpad = L.Kpad; a.M = L.out.H * L.out.W; a.act = L.d.act;
         a.splitk = L.cp.splitk; a.kchunk = L.cp.kchunk; a.S = L.cp.S; a.sz = L.cp.sz; a.sw = L.cp.sw;
         a.MT = L.cp.MT; a.NTn = L.cp.NTn; a.G = L.cp.G; a.xmode = L.cp.xmode;
+        a.mg_wo = div_magic((uint32_t)a.Wo); a.mg_cin = div_magic((uint32_t)a.Cin); a.mg_kw = div_magic((uint32_t)a.kw);
         const size_t slot = sample ? G->tm_used.fetch_add(1) : (size_t)-1;
         if (sample && slot < G->tm_pairs.size()) {
           TimingPair& tp = G->tm_pairs[slot];

@@ -37,6 +37,7 @@ struct ConvArgs {
   int splitk;  // grid.z
   int kchunk;  // LDS-tiled family: k range per split, multiple of the kernel's BK
   int S, sz, sw;  // wave-tile family: K steps in total, per K slice of a workgroup, per wave
+  uint32_t mg_wo, mg_cin, mg_kw;  // wave-tile family: multipliers for division by Wo, Cin, kw (see div_magic)
   int MT, NTn, G, xmode;  // wave-tile family: pixel tiles, channel tiles, weight groups (= NTn * splitk), XCD mapping mode
 };
 
@@ -79,6 +80,9 @@ ConvPlan plan_conv(int M, int N, int Kpad, int bf16);
 
 // If t0/t1 are given they are recorded on `s` immediately before and after the main kernel (not the split-K reduce).
 hipError_t launch_conv(const ConvPlan& pl, const ConvArgs& a, int bf16, hipStream_t s, hipEvent_t t0 = nullptr, hipEvent_t t1 = nullptr);
+// Multiplier for fast_div: floor(2^32 / d) + 1, or 0 for d == 1.  Exact for every n >= 0 with n * d < 2^32.
+inline uint32_t div_magic(uint32_t d) { return d <= 1 ? 0u : (uint32_t)((1ull << 32) / d) + 1u; }
+
 hipError_t launch_dwconv(const DwArgs& a, int bf16, hipStream_t s);
 hipError_t launch_maxpool(const PoolArgs& a, int bf16, hipStream_t s);
 hipError_t launch_gavgpool(const PoolArgs& a, int bf16, hipStream_t s);

@@ -42,6 +42,10 @@ __device__ __forceinline__ void store_elem(void* p, size_t i, float v) {
   else ((float*)p)[i] = v;
 }
 
+// n / d for 0 <= n with n * d < 2^32, through the host-made multiplier magic = floor(2^32 / d) + 1 (0 stands for d = 1):
+// the quotient is the high word of n * magic, a handful of cycles instead of the ~40-instruction division sequence.
+__device__ __forceinline__ int fast_div(int n, uint32_t magic) { return magic ? (int)__umulhi((uint32_t)n, magic) : n; }
+
 // v if ok, else all zero bits; component-wise so that it stays a register select (a select between two uint4
 // objects would be done through their addresses and push the access to scratch / flat memory).
 __device__ __forceinline__ uint4 keep_if(bool ok, uint4 v) {
@@ -342,16 +346,16 @@ __global__ __launch_bounds__(NW * 64) void conv_wave_kernel(const ConvArgs p) {
   const unsigned char* xb = (const unsigned char*)p.x;
   const int m = m0 + li;
   const bool a_ok = m < p.M;
-  const int oy = m / p.Wo, ox = m - oy * p.Wo;
+  const int oy = fast_div(m, p.mg_wo), ox = m - oy * p.Wo;
   const int iy0 = oy * p.stride - p.pad, ix0 = ox * p.stride - p.pad;
   // Walk over k = (tap, ci).  ALIGNED (Cin a multiple of KS): both lane halves are always in the same tap, so the
   // walk state (ky, kx, ci) is wave-uniform and lives in scalars; a lane adds its half's offset lh*VEC.  Otherwise
   // (the padded network input, Cin < KS) every lane walks on its own.  Inside a tap a step only advances the
   // pointer; a new tap recomputes pointer and validity.
   const int k0 = sbeg * KS + (ALIGNED ? 0 : lh * VEC);
-  int tap = k0 / p.Cin;
+  int tap = fast_div(k0, p.mg_cin);
   int ci = k0 - tap * p.Cin;
-  int ky = tap / p.kw, kx = tap - ky * p.kw;
+  int ky = fast_div(tap, p.mg_kw), kx = tap - ky * p.kw;
   bool a_valid;
   const unsigned char* ap;
   auto enter_tap = [&]() {
@@ -706,7 +710,7 @@ static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16) {
   pl.splitk = z;
   pl.tiles = tiles;
   pl.threads = nw * 64;
-  pl.MT = cdiv(M, 32);
+  pl.MT = cdiv(M, 32);  // (the division multipliers are filled in by the caller, which knows Wo, Cin and kw)
   pl.NTn = nb / tn;
   pl.G = pl.NTn * z;
   if (pl.G % 8 == 0) {

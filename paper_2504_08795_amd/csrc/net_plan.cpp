@@ -63,6 +63,9 @@ std::string build_plan(const daris_dnn& dnn, bool keep_activations, NetPlan* out
         if (!L.depthwise) {
           L.K = d.k * d.k * in.Cs;
           L.Kpad = round_up(L.K, 32);
+          // the kernels divide pixel and k indices by Wo, Cin and kw with 32-bit multipliers: operands must stay small
+          if ((uint64_t)(o.H * (uint64_t)o.W + 64) * (uint64_t)o.W >= (1ull << 32) || (uint64_t)(L.Kpad + 64) * (uint64_t)in.Cs >= (1ull << 32))
+            return "layer " + std::to_string(l) + ": tensor too large for the kernels' index arithmetic";
           L.cp = plan_conv(o.H * o.W, o.Cs, L.Kpad, net.bf16);
           L.kernel_id = L.cp.kernel;
           net.ws_bytes = std::max(net.ws_bytes, L.cp.ws_bytes);
