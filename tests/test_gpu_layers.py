@@ -53,6 +53,13 @@ CONV_CASES = [
     (8, 5, 5, 8, 3, 1, 1, 1),         # smaller than any tile
     (32, 56, 56, 64, 3, 1, 1, 1),     # M = 3136: many M tiles
     (16, 112, 112, 96, 1, 1, 0, 2),   # MobileNet expand: M = 12544, largest tile variant
+    (1, 7, 7, 4, 3, 1, 1, 0),         # degenerate: one input channel, four outputs
+    (4, 3, 3, 8, 3, 1, 0, 1),         # output is a single pixel (M = 1)
+    (8, 1, 1, 12, 1, 1, 0, 0),        # 1x1 image, 1x1 kernel: a plain mat-vec
+    (4, 9, 9, 4, 3, 3, 0, 0),         # stride equal to the kernel size: no window overlap
+    (8, 6, 6, 8, 3, 1, 2, 1),         # padding larger than half the kernel: whole windows of zeros at the border
+    (64, 224, 224, 64, 3, 1, 1, 1),   # the largest layer of any configuration (VGG-16 conv1_2): M = 50176, LDS-tiled kernel
+    (3, 224, 224, 64, 3, 1, 1, 1),    # VGG-16 conv1_1: K = 27, M = 50176
 ]
 
 

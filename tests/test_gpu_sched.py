@@ -20,8 +20,8 @@ pytestmark = pytest.mark.gpu
 class GpuTaskSet(harness.GpuTaskSet):
     """The harness's task-set registration plus the oracle-side checks."""
 
-    def __init__(self, ts, flags=0, afet=None):
-        super().__init__(ts, flags=flags, afet=afet, seed=wl.tasksets.SEED)
+    def __init__(self, ts, flags=0, afet=None, streams=None):
+        super().__init__(ts, flags=flags, afet=afet, seed=wl.tasksets.SEED, streams_per_partition=streams)
         self.want = []
 
     def oracle_logits(self):
@@ -48,9 +48,9 @@ class GpuTaskSet(harness.GpuTaskSet):
             assert np.isnan(outs[task][job]).all()
         return worst, len(done)
 
-def oracle_model(ts, afet, n_streams=None):
+def oracle_model(ts, afet, n_streams=None, flags=0):
     tasks = [des.TaskParam(t.period_ns, t.deadline_ns, t.priority, list(afet[i])) for i, t in enumerate(ts.tasks)]
-    return des.SchedulerModel(n_streams or [1] * len(ts.partitions), tasks)
+    return des.SchedulerModel(n_streams or [1] * len(ts.partitions), tasks, flags=flags)
 
 
 @pytest.mark.parametrize("config,n_jobs,load", [(1, 20, 300.0), (2, 12, 25.0)])
@@ -74,13 +74,13 @@ def test_virtual_time_trace_and_logits(config, n_jobs, load):
         g.close()
 
 
-def _replay_and_check(ts, afet, got):
-    m = oracle_model(ts, afet)
+def _replay_and_check(ts, afet, got, n_streams=None, flags=0):
+    m = oracle_model(ts, afet, n_streams, flags)
     again = des.run_replay(m, got)
     for a, b in zip(got, again):
         assert a == b, f"first difference at seq {a[0]}: library {a}, oracle replay {b}"
     assert len(got) == len(again)
-    check_trace_invariants(got, m.n_streams, [t.priority for t in ts.tasks], [t.n_stages for t in ts.tasks])
+    check_trace_invariants(got, m.n_streams, [t.priority for t in ts.tasks], [t.n_stages for t in ts.tasks], flags=flags)
     return m
 
 
@@ -174,5 +174,25 @@ def test_stress_set_with_forced_migrations_between_chunks():
         worst, n = g.check_logits(got)
         assert res["hp"]["missed"] == 0 and res["hp"]["completed"] == 16
         print(f"stress point: {n} jobs, worst logits error {worst:.3e}, {res['inferences_per_s']} inf/s, LP miss {res['lp']['miss_pct']:.1f} %")
+    finally:
+        g.close()
+
+
+@pytest.mark.parametrize("streams,lib_flags,des_flags", [(2, 0, 0), (1, D.NO_FIXED, des.F_NO_FIXED), (2, D.NO_LAST | D.NO_PRIOR, des.F_NO_LAST | des.F_NO_PRIOR)])
+def test_saturated_run_with_streams_and_ablation_flags(streams, lib_flags, des_flags):
+    """Two streams per partition (the paper's MPS+STR shape) and the ablation switches, saturated so that stages really
+    compete: the recorded trace replays through the oracle with the same switches, logits match."""
+    ts = wl.make_taskset(2, n_jobs=30)
+    g = GpuTaskSet(ts, flags=lib_flags, streams=streams)
+    try:
+        afet = g.calibrate(2)
+        D.daris_commit()
+        D.daris_run_closed_loop([30] * 4, 0)
+        got = D.trace_read_all()
+        _replay_and_check(ts, afet, got, [streams] * 3, des_flags)
+        worst, n = g.check_logits(got)
+        assert n == 120
+        if streams == 2:
+            assert any(r[2] == des.DISPATCH and r[7] == 1 for r in got), "second stream never used"
     finally:
         g.close()

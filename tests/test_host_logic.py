@@ -238,3 +238,61 @@ def test_mret_accessor_and_window():
             D.daris_run_until_idle()
             seen.append(D.daris_get_mret(0, 0))
         assert seen == [10, 90, 90, 90, 20, 20]      # window of 3 executions
+
+
+def test_limits_and_degenerate_schedules():
+    """Maximum stream count, one-job and zero-job runs, a window of one, the deepest legal split of a network."""
+    with Session(HOST):
+        p = D.daris_create_partition(1)                   # smallest partition
+        D.daris_partition_set_streams(p, 8)               # largest stream count
+        with pytest.raises(D.DarisError):
+            D.daris_partition_set_streams(p, 9)
+        layers, shp = wl.build_net("resnet18")
+        legal = staging.legal_cuts(layers)
+        dnn, keep = D.make_dnn(layers, None, shp, "fp32")
+        t = D.daris_register_task(dnn, 1000, 1000, D.LP)
+        kmax = len(legal) + 1
+        D.daris_split_stages(t, kmax)                     # every legal cut taken
+        assert D.daris_get_stage_cuts(t) == [0] + [c + 1 for c in legal]
+        D.daris_set_window(1)
+        for j in range(kmax):
+            D.daris_set_afet(t, j, 1)
+            D.daris_set_virtual_time(t, j, p, 0, 3, np.array([1, 1, 1]))
+        D.daris_task_set_io(t, None, 1, None, 1)
+        D.daris_run_periodic(None, [0])                   # nothing to release: returns at once
+        assert D.trace_read_all() == []
+        D.daris_run_periodic(None, [3])
+        st = D.daris_get_stats(t)
+        assert (st["released"], st["completed"], st["missed"]) == (3, 3, 0) and st["resp_max_ns"] == kmax
+        tr = D.trace_read_all()
+        assert sum(1 for r in tr if r[2] == D.T_DISPATCH) == 3 * kmax
+    with Session(HOST):
+        for _ in range(255):
+            D.daris_create_partition(256)                 # as many fully overlapping partitions as the handle type allows
+        with pytest.raises(D.DarisError):
+            D.daris_create_partition(256)
+
+
+def test_overrun_and_hp_queue_order():
+    """A period far shorter than the execution time: LP releases are rejected as overruns, HP releases queue up FIFO and
+    every one of them is eventually served in release order."""
+    # the LP task's AFET (5) under-estimates its real time (25): job 0 is admitted (u = 0.5), the releases at 10 and 20
+    # find it still active (overrun), and from then on MRET = 25 makes u = 2.5, which eq. 11 rejects
+    tasks = [dict(period=10, deadline=10, prio=D.HP, afet=[25]), dict(period=10, deadline=10, prio=D.LP, afet=[5])]
+    with Session(HOST):
+        register_plain_tasks([1, 1], tasks)
+        for i in range(2):
+            for k in range(2):
+                D.daris_set_virtual_time(i, 0, k, 0, 6, np.full(6, 25))
+        dec = []
+        for m in range(6):
+            for i in range(2):
+                dec.append((i, D.daris_release_job(i, None, None, m * 10)))
+        D.daris_run_until_idle()
+        hp, lp = D.daris_get_stats(0), D.daris_get_stats(1)
+        assert hp["completed"] == 6 and hp["rejected_overrun"] == 0 and hp["missed"] >= 4
+        assert (lp["completed"], lp["rejected_overrun"], lp["rejected_admission"]) == (1, 2, 3)
+        assert [d for i, d in dec if i == 0][:3] == [D.ACCEPTED, D.QUEUED, D.QUEUED]
+        tr = D.trace_read_all()
+        started = [r[8] for r in tr if r[2] == D.T_ACCEPT and r[6] == 0]
+        assert started == sorted(started) == list(range(6))
