@@ -201,7 +201,8 @@ daris_status daris_run_closed_loop(const int32_t* n_jobs, int64_t total_jobs);
 /* ---- observation ------------------------------------------------------------------------------------------- */
 
 daris_status daris_get_stats(daris_task t, daris_task_stats* out);
-/* Copies up to cap_bytes / 32 not-yet-read trace records into buf (host); returns the byte count copied. */
+/* Copies up to cap_bytes / 32 not-yet-read trace records into buf (host), releases them, and returns the byte count
+ * copied.  A trace nobody reads is capped at 4 Mi records: the older half is dropped (seq numbers show the gap). */
 int64_t daris_trace_read(void* buf, int64_t cap_bytes);
 /* Current MRET of a stage (eq. 1), ns. */
 int64_t daris_get_mret(daris_task t, int stage);

@@ -112,7 +112,6 @@ struct Global {
   std::vector<PartRt> parts;
   std::vector<std::unique_ptr<TaskRt>> tasks;
   int cu_cursor = 0;
-  size_t trace_cursor = 0;
   bool committed = false;  // Algorithm 1 has run, the online phase has begun
   bool frozen = false;     // streams exist, the partition set can no longer change
   // virtual time
@@ -842,9 +841,9 @@ int64_t daris_trace_read(void* buf, int64_t cap_bytes) {
   if (!buf || cap_bytes < 0) return fail(DARIS_EINVAL, "bad buffer");
   std::lock_guard<std::mutex> lk(G->mu);
   std::vector<TraceRec>& tr = G->core.trace();
-  size_t n = std::min<size_t>((size_t)cap_bytes / sizeof(TraceRec), tr.size() - G->trace_cursor);
-  std::memcpy(buf, tr.data() + G->trace_cursor, n * sizeof(TraceRec));
-  G->trace_cursor += n;
+  const size_t n = std::min<size_t>((size_t)cap_bytes / sizeof(TraceRec), tr.size());
+  std::memcpy(buf, tr.data(), n * sizeof(TraceRec));
+  tr.erase(tr.begin(), tr.begin() + n);  // consumed records are released
   return (int64_t)(n * sizeof(TraceRec));
 }
 

@@ -46,8 +46,14 @@ void SchedCore::set_afet(int task, int stage, int64_t ns) { tasks_[task].afet[st
 
 void SchedCore::rec(int64_t t, uint8_t type, int level, int stage, int part, int task, int stream, uint32_t job,
                     uint32_t aux) {
+  // an unread trace is capped at 4 Mi records (128 MiB): the older half is dropped and counted
+  if (trace_.size() >= (size_t)4 << 20) {
+    const size_t half = trace_.size() / 2;
+    trace_.erase(trace_.begin(), trace_.begin() + half);
+    dropped_ += half;
+  }
   TraceRec r;
-  r.seq = trace_.size();
+  r.seq = seq_++;
   r.t_ns = t;
   r.type = type;
   r.level = (uint8_t)level;

@@ -72,7 +72,8 @@ class SchedCore {
   int64_t mret_task(int task) const;
   bool idle() const;  // no active and no queued job anywhere
   const TaskStats& stats(int task) const { return tasks_[task].st; }
-  std::vector<TraceRec>& trace() { return trace_; }
+  std::vector<TraceRec>& trace() { return trace_; }  // records not yet consumed by the reader; `seq` keeps counting
+  uint64_t dropped() const { return dropped_; }       // records discarded because nobody read the trace
 
  private:
   struct Job {
@@ -115,6 +116,7 @@ class SchedCore {
   std::vector<Part> parts_;
   std::vector<Task> tasks_;
   std::vector<TraceRec> trace_;
+  uint64_t seq_ = 0, dropped_ = 0;
   int ws_ = 5, flags_ = 0;
   bool committed_ = false;
 };

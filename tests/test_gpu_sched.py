@@ -196,3 +196,27 @@ def test_saturated_run_with_streams_and_ablation_flags(streams, lib_flags, des_f
             assert any(r[2] == des.DISPATCH and r[7] == 1 for r in got), "second stream never used"
     finally:
         g.close()
+
+
+def test_config2_full_size_periodic_run():
+    """The benchmark configuration at its full size (500 jobs per task at 20 / 40 ms periods, about 20 s of wall time):
+    trace replays through the oracle, no HP miss, LP misses under 2 %, and every 20th job's logits are checked."""
+    ts = wl.make_taskset(2)
+    assert ts.n_jobs == 500
+    g = GpuTaskSet(ts)
+    try:
+        afet = g.calibrate(3)
+        res = harness.run_periodic(g, ts.n_jobs)
+        got = D.trace_read_all()
+        _replay_and_check(ts, afet, got)
+        assert res["hp"]["completed"] == 1000 and res["hp"]["missed"] == 0
+        assert res["lp"]["miss_pct"] < 2.0 and res["lp"]["rejected_admission"] == 0
+        want = g.oracle_logits()
+        outs = [l.cpu().numpy() for l in g.logits]
+        for task in range(4):
+            for job in range(0, 500, 20):
+                e_max, e_l2 = rel_err(outs[task][job], want[task][job % ts.n_inputs])
+                assert e_max <= TOL["fp32"] and e_l2 <= TOL["fp32"], (task, job, e_max)
+        print(f"config 2 full size: {res['inferences_per_s']} inf/s, HP resp {res['hp']['mean_response_ms']} ms, LP resp {res['lp']['mean_response_ms']} ms")
+    finally:
+        g.close()
