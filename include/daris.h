@@ -229,6 +229,15 @@ daris_status daris_kernel_timing_start(int every, int max_samples);
  * *empty_pair_ms (may be NULL) receives what a pair of events with nothing between them reported on a partition
  * stream when the sampling was started (median of 65): the marker latency contained in every sample. */
 int32_t daris_kernel_timing_read(int32_t cap, int64_t* launches, double* total_ms, double* total_flops, double* empty_pair_ms);
+/* Where the wall time of a stage goes in real-time mode (the price of the synchronisation point at each stage
+ * boundary, Sec. III-B1).  Waits until idle, copies the totals gathered since the last call to out (host int64[8], may
+ * be NULL), clears them, and switches the gathering on (enable != 0) or off.  While it is on, each stage is bracketed by
+ * two extra timed events on its stream.  out[0] stages executed; [1] host ns enqueueing the stage's kernels and events;
+ * [2] host ns from the last enqueue until the boundary event was seen; [3] host ns from then until the scheduler lock
+ * was held; [4] host ns in the decision core and the hand-over of the next stages; [5] GPU ns between the two markers
+ * (first kernel may start .. last kernel ended); [6] host ns between a dispatch pass handing a stage to a stream's
+ * worker and the worker starting to enqueue it; [7] reserved. */
+daris_status daris_driver_profile(int enable, int64_t* out);
 /* Measure per-stage execution times of task t alone on partition p (`reps` runs, the maximum is kept) and store
  * them as the task's AFET values. */
 daris_status daris_calibrate_afet(daris_task t, daris_part p, int reps);

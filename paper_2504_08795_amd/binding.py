@@ -80,6 +80,7 @@ _SIGS = {
     "daris_calibrate_afet": (C.c_int32, [C.c_int32, C.c_int32, C.c_int]),
     "daris_calibrate_afet_loaded": (C.c_int32, [C.c_int32, C.c_int32, C.c_int]),
     "daris_kernel_timing_start": (C.c_int32, [C.c_int, C.c_int]),
+    "daris_driver_profile": (C.c_int32, [C.c_int, C.POINTER(C.c_int64)]),
     "daris_kernel_timing_read": (C.c_int32, [C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "daris_probe_cus": (C.c_int32, [C.c_int32, C.c_int, C.c_int, C.POINTER(C.c_uint32)]),
 }
@@ -292,6 +293,14 @@ def daris_kernel_timing_read():
     k = _chk(lib().daris_kernel_timing_read(64, n.ctypes.data_as(C.POINTER(C.c_int64)), ms.ctypes.data_as(C.POINTER(C.c_double)),
                                             fl.ctypes.data_as(C.POINTER(C.c_double)), C.byref(ov)))
     return {daris_kernel_name(i): (int(n[i]), float(ms[i]), float(fl[i])) for i in range(k) if n[i] > 0}, ov.value
+
+
+def daris_driver_profile(enable):
+    """Totals since the last call (dict, ns) of where the stages' wall time went; switches the gathering on or off."""
+    out = np.zeros(8, np.int64)
+    _chk(lib().daris_driver_profile(int(bool(enable)), out.ctypes.data_as(C.POINTER(C.c_int64))))
+    keys = ("stages", "enqueue_ns", "wait_ns", "lock_ns", "sched_ns", "gpu_ns", "handover_ns")
+    return {k: int(out[i]) for i, k in enumerate(keys)}
 
 
 def daris_calibrate_afet(t, p, reps=5):

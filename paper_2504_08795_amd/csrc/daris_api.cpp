@@ -78,12 +78,14 @@ struct TimingPair {  // one sampled kernel launch: events recorded around it on 
 struct StreamRt {  // one CU-masked stream and, in real-time mode, the worker thread that feeds and watches it
   hipStream_t s = nullptr;
   hipEvent_t done = nullptr;
+  hipEvent_t begin = nullptr, end = nullptr;  // driver profile only: timed markers around a stage
   std::thread thr;
   std::condition_variable cv;
   bool has_work = false;  // a stage handed over by a dispatch pass, not yet picked up by the worker
   Launch work;
   JobIo work_io;
   bool work_sample = false;
+  int64_t work_t = 0;  // host clock at the hand-over
 };
 
 struct PartRt {
@@ -129,6 +131,8 @@ struct Global {
   std::atomic<size_t> tm_used{0};
   double tm_overhead_ms = 0;        // what an empty event pair reports on a partition stream
   int64_t closed_total_left = -1;  // closed-loop runs: releases left over all tasks, -1 = no common budget
+  bool prof = false;                // driver profile: where a stage's wall time goes (host clock and GPU markers)
+  int64_t prof_acc[8] = {0};
 };
 
 Global* G = nullptr;
@@ -241,6 +245,7 @@ daris_status issue(const std::vector<Launch>& ls, int64_t t) {
         S.work = l;
         S.work_io = io->second;
         S.work_sample = sample;
+        S.work_t = G->prof ? now_ns() : 0;
         S.has_work = true;
         S.cv.notify_one();
       }
@@ -317,17 +322,35 @@ void worker_loop(StreamRt* S) {
     const bool sample = S->work_sample;
     S->has_work = false;
     TaskRt& T = *G->tasks[l.task];
+    const bool prof = G->prof;
+    const int64_t t_handed = S->work_t;
     lk.unlock();
-    hipError_t e = launch_stage(T, l.stage, io, S->s, sample);
+    const int64_t t0 = prof ? now_ns() : 0;
+    hipError_t e = hipSuccess;
+    if (prof) e = hipEventRecord(S->begin, S->s);
+    if (e == hipSuccess) e = launch_stage(T, l.stage, io, S->s, sample);
+    if (e == hipSuccess && prof) e = hipEventRecord(S->end, S->s);
     if (e == hipSuccess) e = hipEventRecord(S->done, S->s);
+    const int64_t t1 = prof ? now_ns() : 0;
     if (e == hipSuccess) {
       while ((e = hipEventQuery(S->done)) == hipErrorNotReady) {
         for (int i = 0; i < 16; ++i) __builtin_ia32_pause();
       }
     }
+    const int64_t t2 = prof ? now_ns() : 0;
+    float gpu_ms = 0.f;
+    if (prof && e == hipSuccess) e = hipEventElapsedTime(&gpu_ms, S->begin, S->end);
     lk.lock();
     if (e != hipSuccess && G->async_error.empty()) G->async_error = std::string("stage execution: ") + hipGetErrorString(e);
     const int64_t now = now_ns();
+    if (prof) {
+      G->prof_acc[0] += 1;
+      G->prof_acc[1] += t1 - t0;
+      G->prof_acc[2] += t2 - t1;
+      G->prof_acc[3] += now - t2;
+      G->prof_acc[5] += (int64_t)(gpu_ms * 1e6);
+      G->prof_acc[6] += t0 - t_handed;
+    }
     const int task = l.task;
     const uint32_t job = G->core.active_job(task);
     const bool job_done = G->core.stage_done(now, task);
@@ -345,6 +368,7 @@ void worker_loop(StreamRt* S) {
           G->async_error = tl_error;
       }
     }
+    if (prof) G->prof_acc[4] += now_ns() - now;
     if (G->core.idle()) G->cv_idle.notify_all();
   }
 }
@@ -448,6 +472,8 @@ daris_status daris_shutdown(void) {
     for (PartRt& P : G->parts)
       for (auto& S : P.streams) {
         if (S->done) (void)hipEventDestroy(S->done);
+        if (S->begin) (void)hipEventDestroy(S->begin);
+        if (S->end) (void)hipEventDestroy(S->end);
         if (S->s) (void)hipStreamDestroy(S->s);
       }
   }
@@ -626,6 +652,8 @@ static daris_status make_streams(void) {
         StreamRt& S = *P.streams.back();
         HIP_TRY(hipExtStreamCreateWithCUMask(&S.s, 8, P.mask));
         HIP_TRY(hipEventCreateWithFlags(&S.done, hipEventDisableTiming));
+        HIP_TRY(hipEventCreate(&S.begin));
+        HIP_TRY(hipEventCreate(&S.end));
       }
     }
   }
@@ -1000,6 +1028,19 @@ int32_t daris_kernel_timing_read(int32_t cap, int64_t* launches, double* total_m
   G->tm_used = 0;
   if (empty_pair_ms) *empty_pair_ms = G->tm_overhead_ms;
   return K_COUNT;
+}
+
+daris_status daris_driver_profile(int enable, int64_t* out) {
+  if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
+  if (G->vt) return fail(DARIS_ESTATE, "the driver profile belongs to real-time mode");
+  daris_status st = daris_run_until_idle();
+  if (st != DARIS_OK) return st;
+  std::lock_guard<std::mutex> lk(G->mu);
+  if (out)
+    for (int i = 0; i < 8; ++i) out[i] = G->prof_acc[i];
+  for (int i = 0; i < 8; ++i) G->prof_acc[i] = 0;
+  G->prof = enable != 0;
+  return DARIS_OK;
 }
 
 daris_status daris_probe_cus(daris_part p, int n_groups, int spin, uint32_t* out) {

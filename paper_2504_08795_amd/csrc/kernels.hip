@@ -688,7 +688,11 @@ static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16) {
   const int ks = bf16 ? 16 : 8;  // k per step: two 16-byte vectors
   const int S = Kpad / ks;
   const int nb = cdiv(N, 32);
-  const int tn = (nb % 2 == 0) ? 2 : 1;
+  // A wave tile two channel blocks wide halves the reads of the pixel operand, but also halves the number of tiles:
+  // below about 3/4 of the partition's CUs it is better to keep 32-channel tiles and split K less (or not at all,
+  // which saves the reduction launch).
+  int tn = (nb % 2 == 0 && cdiv(M, 32) * (nb / 2) >= 96) ? 2 : 1;
+  if (const char* e = getenv("DARIS_W_TN")) tn = (atoi(e) == 2 && nb % 2 == 0) ? 2 : 1;
   const int tiles = cdiv(M, 32) * (nb / tn);
   const int nominal_cus = kNominalWaveSlots / 4;
   int nw = 8;
@@ -698,7 +702,10 @@ static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16) {
   const int max_by_k = S / (nw * 6) > 0 ? S / (nw * 6) : 1;
   if (z > max_by_k) z = max_by_k;
   if (z > 16) z = 16;
-  if (const char* e = getenv("DARIS_W_NW")) nw = atoi(e);
+  if (const char* e = getenv("DARIS_W_NW")) {
+    const int v = atoi(e);
+    if (v == 2 || v == 4 || v == 8) nw = v;
+  }
   if (const char* e = getenv("DARIS_W_Z")) z = atoi(e) < S ? atoi(e) : S;
   const int sz = cdiv(S, z);
   z = cdiv(S, sz);

@@ -112,12 +112,21 @@ def run_periodic(g: GpuTaskSet, n_jobs, migrate_every=0, seed=1):
     return summarise(ts, before, g.stats(), wall)
 
 
-def run_saturated(g: GpuTaskSet, total_jobs):
+def run_saturated(g: GpuTaskSet, total_jobs, driver_profile=False):
     before = g.stats()
+    if driver_profile:
+        D.daris_driver_profile(True)
     t0 = time.perf_counter()
     D.daris_run_closed_loop([total_jobs] * g.n_tasks, total_jobs)
     wall = time.perf_counter() - t0
-    return summarise(g.ts, before, g.stats(), wall)
+    res = summarise(g.ts, before, g.stats(), wall)
+    if driver_profile:
+        pr = D.daris_driver_profile(False)
+        n = max(pr["stages"], 1)
+        res["driver_profile_us_per_stage"] = {k[:-3]: round(v / n / 1e3, 2) for k, v in pr.items() if k != "stages"}
+        res["driver_profile_us_per_stage"]["stages"] = pr["stages"]
+        res["driver_profile_us_per_stage"]["wall_us"] = round(wall * 1e6, 1)
+    return res
 
 
 def main():
@@ -132,6 +141,7 @@ def main():
     ap.add_argument("--flags", default="", help="comma list of no_last,no_prior,no_fixed,hp_admission")
     ap.add_argument("--migrate-every", type=int, default=0)
     ap.add_argument("--saturated", action="store_true")
+    ap.add_argument("--driver-profile", action="store_true", help="--saturated: where a stage's wall time goes")
     ap.add_argument("--loaded-afet", action="store_true", help="AFET measured while the other streams run other tasks (Sec. IV-A1)")
     ap.add_argument("--paper-set", default="", help="Table-II-shaped set of this DNN type instead of --config (e.g. resnet18)")
     ap.add_argument("--n-high", type=int, default=17)
@@ -157,7 +167,7 @@ def main():
     try:
         g.calibrate(loaded=a.loaded_afet)
         D.daris_commit()
-        res = run_saturated(g, a.jobs * g.n_tasks) if a.saturated else run_periodic(g, a.jobs, a.migrate_every)
+        res = run_saturated(g, a.jobs * g.n_tasks, a.driver_profile) if a.saturated else run_periodic(g, a.jobs, a.migrate_every)
         res["config"] = dict(name=ts.name, partitions=ts.partitions, streams=a.streams, tasks=g.n_tasks, rate=a.rate, oversub=a.oversub,
                              stages=[t.n_stages for t in ts.tasks], flags=a.flags)
         print(json.dumps(res))
