@@ -77,7 +77,8 @@ struct TimingPair {  // one sampled kernel launch: events recorded around it on 
 
 struct StreamRt {  // one CU-masked stream and, in real-time mode, the worker thread that feeds and watches it
   hipStream_t s = nullptr;
-  hipEvent_t done = nullptr;
+  hipEvent_t done = nullptr;      // boundary of a job's last stage: the logits become visible to the host
+  hipEvent_t done_mid = nullptr;  // boundary inside a job: completion only, no system-scope fence
   hipEvent_t begin = nullptr, end = nullptr;  // driver profile only: timed markers around a stage
   std::thread thr;
   std::condition_variable cv;
@@ -330,10 +331,13 @@ void worker_loop(StreamRt* S) {
     if (prof) e = hipEventRecord(S->begin, S->s);
     if (e == hipSuccess) e = launch_stage(T, l.stage, io, S->s, sample);
     if (e == hipSuccess && prof) e = hipEventRecord(S->end, S->s);
-    if (e == hipSuccess) e = hipEventRecord(S->done, S->s);
+    // Inside a job the next stage runs on this device whichever stream it gets, so the boundary needs no cache
+    // write-back towards the host; only the last stage's event carries the system-scope fence.
+    hipEvent_t done = (l.stage + 1 < (int)T.net.stage_first.size()) ? S->done_mid : S->done;
+    if (e == hipSuccess) e = hipEventRecord(done, S->s);
     const int64_t t1 = prof ? now_ns() : 0;
     if (e == hipSuccess) {
-      while ((e = hipEventQuery(S->done)) == hipErrorNotReady) {
+      while ((e = hipEventQuery(done)) == hipErrorNotReady) {
         for (int i = 0; i < 16; ++i) __builtin_ia32_pause();
       }
     }
@@ -472,6 +476,7 @@ daris_status daris_shutdown(void) {
     for (PartRt& P : G->parts)
       for (auto& S : P.streams) {
         if (S->done) (void)hipEventDestroy(S->done);
+        if (S->done_mid) (void)hipEventDestroy(S->done_mid);
         if (S->begin) (void)hipEventDestroy(S->begin);
         if (S->end) (void)hipEventDestroy(S->end);
         if (S->s) (void)hipStreamDestroy(S->s);
@@ -652,8 +657,9 @@ static daris_status make_streams(void) {
         StreamRt& S = *P.streams.back();
         HIP_TRY(hipExtStreamCreateWithCUMask(&S.s, 8, P.mask));
         HIP_TRY(hipEventCreateWithFlags(&S.done, hipEventDisableTiming));
-        HIP_TRY(hipEventCreate(&S.begin));
-        HIP_TRY(hipEventCreate(&S.end));
+        HIP_TRY(hipEventCreateWithFlags(&S.done_mid, hipEventDisableTiming | hipEventDisableSystemFence));
+        HIP_TRY(hipEventCreateWithFlags(&S.begin, hipEventDisableSystemFence));
+        HIP_TRY(hipEventCreateWithFlags(&S.end, hipEventDisableSystemFence));
       }
     }
   }
@@ -974,8 +980,8 @@ daris_status daris_kernel_timing_start(int every, int max_samples) {
   if (!G->core.idle()) return fail(DARIS_ESTATE, "jobs are active");
   while ((int)G->tm_pairs.size() < max_samples) {
     TimingPair tp;
-    HIP_TRY(hipEventCreate(&tp.e0));
-    HIP_TRY(hipEventCreate(&tp.e1));
+    HIP_TRY(hipEventCreateWithFlags(&tp.e0, hipEventDisableSystemFence));  // timed, without cache write-back
+    HIP_TRY(hipEventCreateWithFlags(&tp.e1, hipEventDisableSystemFence));
     G->tm_pairs.push_back(tp);
   }
   G->tm_used = 0;

@@ -140,6 +140,32 @@ def test_closed_loop_with_forced_migrations():
         g.close()
 
 
+def test_driver_profile_accounts_for_the_stages_it_saw():
+    """The stage-boundary accounting covers every stage of the run and its parts are consistent with each other."""
+    ts = wl.make_taskset(2, n_jobs=12)
+    g = GpuTaskSet(ts)
+    try:
+        for i in range(len(ts.tasks)):
+            D.daris_calibrate_afet(i, 0, 2)
+        D.daris_commit()
+        D.daris_driver_profile(True)
+        D.daris_run_closed_loop([12] * 4)
+        pr = D.daris_driver_profile(False)
+        assert pr["stages"] == 4 * 12 * 3
+        # the kernels of a stage run inside the interval in which the host enqueues and waits for them
+        assert 0 < pr["gpu_ns"] <= pr["enqueue_ns"] + pr["wait_ns"]
+        assert all(pr[k] >= 0 for k in pr)
+        D.daris_run_closed_loop([2] * 4)
+        assert D.daris_driver_profile(False)["stages"] == 0       # switched off: nothing gathered
+        outs = [l.cpu().numpy() for l in g.logits]
+        want = g.oracle_logits()
+        for task in range(4):
+            for job in range(2, 12):
+                assert rel_err(outs[task][job], want[task][job % ts.n_inputs])[0] <= TOL["fp32"]
+    finally:
+        g.close()
+
+
 def test_cu_masks_are_honoured():
     """Workgroups launched on a partition's stream run only on as many distinct CUs as the partition owns."""
     D.daris_init(0, 0, 0)
