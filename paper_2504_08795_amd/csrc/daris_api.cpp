@@ -144,6 +144,22 @@ int64_t now_ns() {
 
 // ---- stage execution ----------------------------------------------------------------------------------------------
 
+ConvArgs conv_args(TaskRt& T, int l, void* y) {
+  NetPlan& net = T.net;
+  LayerPlan& L = net.layers[l];
+  const TensorInfo& in = net.tensor(L.in_t);
+  ConvArgs a;
+  a.x = T.slots[in.slot]; a.w = L.w_dev; a.bias = L.b_dev; a.y = y; a.ws = T.ws; a.counters = T.counters;
+  a.res = L.res_t >= 0 ? T.slots[net.tensor(L.res_t).slot] : nullptr;
+  a.H = in.H; a.W = in.W; a.Cin = in.Cs; a.Ho = L.out.H; a.Wo = L.out.W; a.Cout = L.out.Cs;
+  a.kh = a.kw = L.d.k; a.stride = L.d.stride; a.pad = L.d.pad;
+  a.K = L.K; a.Kpad = L.Kpad; a.M = L.out.H * L.out.W; a.act = L.d.act;
+  a.splitk = L.cp.splitk; a.kchunk = L.cp.kchunk; a.S = L.cp.S; a.sz = L.cp.sz; a.sw = L.cp.sw;
+  a.MT = L.cp.MT; a.NTn = L.cp.NTn; a.G = L.cp.G; a.xmode = L.cp.xmode;
+  a.mg_wo = div_magic((uint32_t)a.Wo); a.mg_cin = div_magic((uint32_t)a.Cin); a.mg_kw = div_magic((uint32_t)a.kw);
+  return a;
+}
+
 hipError_t launch_layer(TaskRt& T, int l, void* d_logits, hipStream_t s, bool sample = false) {
   NetPlan& net = T.net;
   LayerPlan& L = net.layers[l];
@@ -160,23 +176,26 @@ hipError_t launch_layer(TaskRt& T, int l, void* d_logits, hipStream_t s, bool sa
         a.k = L.d.k; a.stride = L.d.stride; a.pad = L.d.pad; a.act = L.d.act;
         return launch_dwconv(a, net.bf16, s);
       } else {
-        ConvArgs a;
-        a.x = x; a.w = L.w_dev; a.bias = L.b_dev; a.y = y; a.ws = T.ws; a.counters = T.counters;
-        a.res = L.res_t >= 0 ? T.slots[net.tensor(L.res_t).slot] : nullptr;
-        a.H = in.H; a.W = in.W; a.Cin = in.Cs; a.Ho = L.out.H; a.Wo = L.out.W; a.Cout = L.out.Cs;
-        a.kh = a.kw = L.d.k; a.stride = L.d.stride; a.pad = L.d.pad;
-        a.K = L.K; a.Kpad = L.Kpad; a.M = L.out.H * L.out.W; a.act = L.d.act;
-        a.splitk = L.cp.splitk; a.kchunk = L.cp.kchunk; a.S = L.cp.S; a.sz = L.cp.sz; a.sw = L.cp.sw;
-        a.MT = L.cp.MT; a.NTn = L.cp.NTn; a.G = L.cp.G; a.xmode = L.cp.xmode;
-        a.mg_wo = div_magic((uint32_t)a.Wo); a.mg_cin = div_magic((uint32_t)a.Cin); a.mg_kw = div_magic((uint32_t)a.kw);
+        if (L.pair_with >= 0 && !L.pair_lead) return hipSuccess;  // issued together with the next layer
+        const ConvArgs a = conv_args(T, l, y);
+        hipEvent_t t0 = nullptr, t1 = nullptr;
+        double flops = 2.0 * (double)L.macs;
+        if (L.pair_with >= 0) flops += 2.0 * (double)net.layers[L.pair_with].macs;
         const size_t slot = sample ? G->tm_used.fetch_add(1) : (size_t)-1;
         if (sample && slot < G->tm_pairs.size()) {
           TimingPair& tp = G->tm_pairs[slot];
           tp.kernel = L.kernel_id;
-          tp.flops = 2.0 * (double)L.macs;
-          return launch_conv(L.cp, a, net.bf16, s, tp.e0, tp.e1);
+          tp.flops = flops;
+          t0 = tp.e0;
+          t1 = tp.e1;
         }
-        return launch_conv(L.cp, a, net.bf16, s);
+        if (L.pair_with >= 0) {
+          LayerPlan& O = net.layers[L.pair_with];
+          const ConvArgs b = conv_args(T, L.pair_with, T.slots[O.out.slot]);
+          const bool l_heavy = L.macs >= O.macs;  // the heavier convolution is the first problem (its plan was kept)
+          return l_heavy ? launch_conv_pair(L.cp, a, O.cp, b, net.bf16, s, t0, t1) : launch_conv_pair(O.cp, b, L.cp, a, net.bf16, s, t0, t1);
+        }
+        return launch_conv(L.cp, a, net.bf16, s, t0, t1);
       }
     case DARIS_OP_MAXPOOL:
     case DARIS_OP_GAVGPOOL: {

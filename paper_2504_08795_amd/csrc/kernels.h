@@ -80,6 +80,13 @@ ConvPlan plan_conv(int M, int N, int Kpad, int bf16);
 
 // If t0/t1 are given they are recorded on `s` immediately before and after the main kernel (not the split-K reduce).
 hipError_t launch_conv(const ConvPlan& pl, const ConvArgs& a, int bf16, hipStream_t s, hipEvent_t t0 = nullptr, hipEvent_t t1 = nullptr);
+// Plan for a second convolution that is to share a launch with `first` (launch_conv_pair): the same wave-tile kernel
+// variant, K not split across workgroups.  Returns a plan with kernel == K_NONE when that is not possible.
+ConvPlan plan_conv_like(const ConvPlan& first, int M, int N, int Kpad, int bf16);
+// One launch for two independent convolutions: pl0/a0 as planned by plan_conv (wave-tile family), pl1/a1 by
+// plan_conv_like(pl0, ...).  The event pair brackets the joint kernel.
+hipError_t launch_conv_pair(const ConvPlan& pl0, const ConvArgs& a0, const ConvPlan& pl1, const ConvArgs& a1, int bf16, hipStream_t s,
+                            hipEvent_t t0 = nullptr, hipEvent_t t1 = nullptr);
 // Multiplier for fast_div: floor(2^32 / d) + 1, or 0 for d == 1.  Exact for every n >= 0 with n * d < 2^32.
 inline uint32_t div_magic(uint32_t d) { return d <= 1 ? 0u : (uint32_t)((1ull << 32) / d) + 1u; }
 

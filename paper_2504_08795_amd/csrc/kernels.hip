@@ -300,7 +300,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 // which splitk_reduce_kernel adds in z order (a device-wide fence per workgroup for an in-kernel reduction was
 // measured to cost several times the extra launch).
 template <bool BF16, int TN, int NW, bool ALIGNED>
-__global__ __launch_bounds__(NW * 64) void conv_wave_kernel(const ConvArgs p) {
+__device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L) {
   constexpr int ES = BF16 ? 2 : 4;
   constexpr int VEC = 16 / ES;
   constexpr int KS = 2 * VEC;
@@ -321,10 +321,11 @@ __global__ __launch_bounds__(NW * 64) void conv_wave_kernel(const ConvArgs p) {
   // byte is fetched from memory once per XCD that needs it instead of once per pixel tile.
   int mt, g;
   {
-    const int L = blockIdx.x, x = L & 7, q = L >> 3;
+    const int x = L & 7, q = L >> 3;
     if (p.xmode == 1) {
       g = (q / p.MT) * 8 + x;
       mt = q % p.MT;
+      if (g >= p.G) return;  // padding workgroups of a two-problem launch
     } else if (p.xmode == 2) {
       const int r = 8 / p.G;
       g = x / r;
@@ -333,6 +334,7 @@ __global__ __launch_bounds__(NW * 64) void conv_wave_kernel(const ConvArgs p) {
     } else {
       g = L / p.MT;
       mt = L % p.MT;
+      if (g >= p.G) return;
     }
   }
   const int zi = g / p.NTn;
@@ -483,6 +485,21 @@ __global__ __launch_bounds__(NW * 64) void conv_wave_kernel(const ConvArgs p) {
       }
     }
   }
+}
+
+template <bool BF16, int TN, int NW, bool ALIGNED>
+__global__ __launch_bounds__(NW * 64) void conv_wave_kernel(const ConvArgs p) {
+  conv_wave_body<BF16, TN, NW, ALIGNED>(p, (int)blockIdx.x);
+}
+
+// Two independent convolutions of the same kernel variant in one launch (a residual block's first convolution and
+// the 1x1 convolution of its shortcut read the same tensor): workgroups [0, n0) work on p0, the rest on p1.  n0 is
+// a multiple of 8, so the workgroup -> XCD relation of each problem is the one its plan assumed.
+template <bool BF16, int TN, int NW, bool ALIGNED>
+__global__ __launch_bounds__(NW * 64) void conv_wave_pair_kernel(const ConvArgs p0, const ConvArgs p1, const int n0) {
+  const int L = (int)blockIdx.x;
+  if (L < n0) conv_wave_body<BF16, TN, NW, ALIGNED>(p0, L);
+  else conv_wave_body<BF16, TN, NW, ALIGNED>(p1, L - n0);
 }
 
 // ---- depthwise convolution: memory bound, one thread per (output pixel, 16-byte channel vector) -----------------------
@@ -679,7 +696,7 @@ static ConvPlan plan_conv_tile(int M, int N, int Kpad, int bf16) {
   return pl;
 }
 
-static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16) {
+static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16, int force_tn = 0, int force_nw = 0) {
   // Measured on a 128-CU partition (fp32, ResNet-18 shapes): the K loop itself runs near the MFMA rate; what a
   // launch pays for is its fixed cost and idle CUs.  Best found: 8 waves per workgroup splitting K, and enough
   // grid.z slices that tiles * z is about the number of CUs, while a wave keeps at least ~6 steps.
@@ -693,6 +710,7 @@ static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16) {
   // which saves the reduction launch).
   int tn = (nb % 2 == 0 && cdiv(M, 32) * (nb / 2) >= 96) ? 2 : 1;
   if (const char* e = getenv("DARIS_W_TN")) tn = (atoi(e) == 2 && nb % 2 == 0) ? 2 : 1;
+  if (force_tn) tn = force_tn;
   const int tiles = cdiv(M, 32) * (nb / tn);
   const int nominal_cus = kNominalWaveSlots / 4;
   int nw = 8;
@@ -707,6 +725,10 @@ static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16) {
     if (v == 2 || v == 4 || v == 8) nw = v;
   }
   if (const char* e = getenv("DARIS_W_Z")) z = atoi(e) < S ? atoi(e) : S;
+  if (force_nw) {  // second problem of a two-problem launch: the first one's kernel variant, no split across workgroups
+    nw = force_nw;
+    z = 1;
+  }
   const int sz = cdiv(S, z);
   z = cdiv(S, sz);
   pl.tn = tn;
@@ -751,6 +773,12 @@ ConvPlan plan_conv(int M, int N, int Kpad, int bf16) {
   return plan_conv_wave(M, N, Kpad, bf16);
 }
 
+ConvPlan plan_conv_like(const ConvPlan& first, int M, int N, int Kpad, int bf16) {
+  ConvPlan none = ConvPlan();
+  if (!first.wave || cdiv(N, 32) % first.tn != 0) return none;
+  return plan_conv_wave(M, N, Kpad, bf16, first.tn, first.nw);
+}
+
 template <bool BF16>
 static hipError_t launch_conv_t(const ConvPlan& pl, const ConvArgs& a, hipStream_t s, hipEvent_t t0, hipEvent_t t1) {
   if (t0) (void)hipEventRecord(t0, s);
@@ -793,6 +821,49 @@ static hipError_t launch_conv_t(const ConvPlan& pl, const ConvArgs& a, hipStream
     e = hipGetLastError();
   }
   return e;
+}
+
+template <bool BF16>
+static hipError_t launch_conv_pair_t(const ConvPlan& pl0, const ConvArgs& a0, const ConvPlan& pl1, const ConvArgs& a1, hipStream_t s,
+                                     hipEvent_t t0, hipEvent_t t1) {
+  const int ks = BF16 ? 16 : 8;
+  const bool aligned = a0.Cin % ks == 0;
+  if (!pl0.wave || !pl1.wave || pl0.kernel != pl1.kernel || aligned != (a1.Cin % ks == 0) || pl1.splitk != 1)
+    return hipErrorInvalidValue;
+  const int n0 = (int)(pl0.grid.x + 7) / 8 * 8;
+  const dim3 grid(n0 + pl1.grid.x, 1, 1);
+  const int variant = pl0.kernel - (BF16 ? K_CONVW_BF16_T1W2 : K_CONVW_F32_T1W2);
+  if (t0) (void)hipEventRecord(t0, s);
+#define DARIS_PAIR_CASE(idx, TN_, NW_)                                                                                     \
+  case idx:                                                                                                                \
+    if (aligned) hipLaunchKernelGGL((conv_wave_pair_kernel<BF16, TN_, NW_, true>), grid, dim3(NW_ * 64), 0, s, a0, a1, n0); \
+    else hipLaunchKernelGGL((conv_wave_pair_kernel<BF16, TN_, NW_, false>), grid, dim3(NW_ * 64), 0, s, a0, a1, n0);        \
+    break;
+  switch (variant) {
+    DARIS_PAIR_CASE(0, 1, 2)
+    DARIS_PAIR_CASE(1, 1, 4)
+    DARIS_PAIR_CASE(2, 1, 8)
+    DARIS_PAIR_CASE(3, 2, 2)
+    DARIS_PAIR_CASE(4, 2, 4)
+    DARIS_PAIR_CASE(5, 2, 8)
+    default: return hipErrorInvalidValue;
+  }
+#undef DARIS_PAIR_CASE
+  hipError_t e = hipGetLastError();
+  if (t1) (void)hipEventRecord(t1, s);
+  if (e != hipSuccess) return e;
+  if (pl0.splitk > 1) {
+    const size_t total4 = (size_t)a0.M * a0.Cout / 4;
+    hipLaunchKernelGGL((splitk_reduce_kernel<BF16>), dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, s, a0.ws, a0.bias,
+                       a0.res, a0.y, a0.M, a0.Cout, pl0.splitk, a0.act);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+hipError_t launch_conv_pair(const ConvPlan& pl0, const ConvArgs& a0, const ConvPlan& pl1, const ConvArgs& a1, int bf16, hipStream_t s,
+                            hipEvent_t t0, hipEvent_t t1) {
+  return bf16 ? launch_conv_pair_t<true>(pl0, a0, pl1, a1, s, t0, t1) : launch_conv_pair_t<false>(pl0, a0, pl1, a1, s, t0, t1);
 }
 
 hipError_t launch_conv(const ConvPlan& pl, const ConvArgs& a, int bf16, hipStream_t s, hipEvent_t t0, hipEvent_t t1) {

@@ -1,6 +1,7 @@
 #include "net_plan.h"
 
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 #include <limits>
 
@@ -110,6 +111,23 @@ std::string build_plan(const daris_dnn& dnn, bool keep_activations, NetPlan* out
       if (r.C != o.C || r.H != o.H || r.W != o.W) return "layer " + std::to_string(l) + ": residual shape mismatch";
     }
     o.bytes = (size_t)o.H * o.W * o.Cs * es;
+  }
+  // launch pairs (a residual block's first convolution and its shortcut convolution)
+  for (int l = 0; l + 1 < n && !getenv("DARIS_NO_PAIR"); ++l) {
+    LayerPlan& A = net.layers[l];
+    LayerPlan& B = net.layers[l + 1];
+    if (A.d.op != DARIS_OP_CONV || B.d.op != DARIS_OP_CONV || A.depthwise || B.depthwise) continue;
+    if (A.in_t != B.in_t || B.res_t == l + 1 || !A.cp.wave || !B.cp.wave) continue;
+    LayerPlan& heavy = A.macs > B.macs ? A : B;
+    LayerPlan& light = A.macs > B.macs ? B : A;
+    const ConvPlan like = plan_conv_like(heavy.cp, light.out.H * light.out.W, light.out.Cs, light.Kpad, net.bf16);
+    if (like.kernel == K_NONE) continue;
+    light.cp = like;
+    light.kernel_id = like.kernel;
+    A.pair_with = l + 1;
+    B.pair_with = l;
+    B.pair_lead = true;
+    ++l;
   }
   const TensorInfo& fin = net.layers[n - 1].out;
   net.n_out = fin.C * fin.H * fin.W;

@@ -24,6 +24,10 @@ struct LayerPlan {
   bool depthwise = false;
   int K = 0, Kpad = 0;       // GEMM K (conv: kh*kw*Cs_in, fc: H*W*Cs_in) and its zero-padded length
   ConvPlan cp;
+  // Two dense convolutions that read the same tensor and do not depend on each other share one launch: it is issued
+  // at the later layer (pair_lead), the earlier one issues nothing; the lighter of the two is planned like the heavier.
+  int pair_with = -1;
+  bool pair_lead = false;
   int32_t kernel_id = K_NONE;
   void* w_dev = nullptr;
   float* b_dev = nullptr;
