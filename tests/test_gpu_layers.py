@@ -88,6 +88,25 @@ def test_conv_residual_block(cin, hw, cout, s, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("cin,h,w,mid,cout,s,ds_first", [
+    (64, 28, 28, 32, 128, 2, True),     # ResNet-50 shape of block: shortcut 1x1 s2 and 1x1 s1 read the same tensor, different output sizes
+    (64, 28, 28, 32, 128, 2, False),    # the same with the shortcut listed after the first convolution
+    (40, 13, 11, 24, 72, 1, True),      # ragged sizes: padding workgroups between the two problems of the launch
+    (256, 14, 14, 64, 512, 2, True),    # heavier problem split over K (its reduction follows the joint launch)
+    (32, 9, 9, 96, 96, 1, False),       # channel block counts 3 and 3: the wide-tile variant does not apply to either
+])
+def test_conv_pair_in_bottleneck_block(cin, h, w, mid, cout, s, ds_first, dtype):
+    """Two convolutions reading one tensor (issued as one launch) inside a bottleneck block with a strided middle layer."""
+    ds = N.Layer(op=N.OP_CONV, c_in=cin, c_out=cout, k=1, stride=s, pad=0, act=0, in_from=-1)
+    c1 = N.Layer(op=N.OP_CONV, c_in=cin, c_out=mid, k=1, stride=1, pad=0, act=1, in_from=-1)
+    layers = [ds, c1] if ds_first else [c1, ds]
+    i_ds, i_c1 = (0, 1) if ds_first else (1, 0)
+    layers.append(N.Layer(op=N.OP_CONV, c_in=mid, c_out=mid, k=3, stride=s, pad=1, act=1, in_from=i_c1))
+    layers.append(N.Layer(op=N.OP_CONV, c_in=mid, c_out=cout, k=1, stride=1, pad=0, act=1, in_from=2, res_from=i_ds))
+    run_case(layers, (cin, h, w), dtype, tol={"fp32": 5e-5, "bf16": 1.5e-2}[dtype])
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
 @pytest.mark.parametrize("c,h,w,s", [(32, 112, 112, 1), (96, 57, 55, 2), (144, 28, 28, 1), (960, 7, 7, 1), (24, 9, 9, 2)])
 def test_depthwise(c, h, w, s, dtype):
     layers = [N.Layer(op=N.OP_CONV, c_in=c, c_out=c, k=3, stride=s, pad=1, groups=c, act=2, in_from=-1)]
