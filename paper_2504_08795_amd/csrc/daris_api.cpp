@@ -55,7 +55,7 @@ struct TaskRt {
   NetPlan net;
   std::vector<void*> slots;
   float* ws = nullptr;
-  int* counters = nullptr;
+  int prio = 0;  // DARIS_HP / DARIS_LP
   std::vector<void*> owned;  // every device allocation of the task
   // I/O
   const void* pool_in = nullptr;
@@ -149,7 +149,7 @@ ConvArgs conv_args(TaskRt& T, int l, void* y) {
   LayerPlan& L = net.layers[l];
   const TensorInfo& in = net.tensor(L.in_t);
   ConvArgs a;
-  a.x = T.slots[in.slot]; a.w = L.w_dev; a.bias = L.b_dev; a.y = y; a.ws = T.ws; a.counters = T.counters;
+  a.x = T.slots[in.slot]; a.w = L.w_dev; a.bias = L.b_dev; a.y = y; a.ws = T.ws; a.wave_prio = (T.prio == DARIS_HP && (G->flags & DARIS_WAVE_PRIORITY)) ? 1 : 0;
   a.res = L.res_t >= 0 ? T.slots[net.tensor(L.res_t).slot] : nullptr;
   a.H = in.H; a.W = in.W; a.Cin = in.Cs; a.Ho = L.out.H; a.Wo = L.out.W; a.Cout = L.out.Cs;
   a.kh = a.kw = L.d.k; a.stride = L.d.stride; a.pad = L.d.pad;
@@ -595,20 +595,13 @@ daris_task daris_register_task(const daris_dnn* dnn, int64_t period_ns, int64_t 
         return fail(DARIS_ENOMEM, "split-K workspace: %s", hipGetErrorString(e));
       }
     }
-    if (net.n_counters) {
-      hipError_t e = dev_alloc((size_t)net.n_counters * sizeof(int), (void**)&T->counters);
-      if (e == hipSuccess) e = hipMemset(T->counters, 0, (size_t)net.n_counters * sizeof(int));
-      if (e != hipSuccess) {
-        free_task(*T);
-        return fail(DARIS_ENOMEM, "tile counters: %s", hipGetErrorString(e));
-      }
-    }
     hipError_t e = hipEventCreateWithFlags(&T->chain, hipEventDisableTiming);
     if (e != hipSuccess) {
       free_task(*T);
       return fail(DARIS_EHIP, "hipEventCreate: %s", hipGetErrorString(e));
     }
   }
+  T->prio = priority;
   G->tasks.push_back(std::move(T));
   return G->core.add_task(period_ns, deadline_ns, priority, 1);
 }

@@ -29,7 +29,6 @@ struct ConvArgs {
   const void* res;    // [Ho*Wo][Cout] or nullptr
   void* y;            // [Ho*Wo][Cout]
   float* ws;          // split-K partial sums (splitk > 1)
-  int* counters;      // wave-tile family: one arrival counter per output tile, all zero between launches
   int H, W, Cin, Ho, Wo, Cout;
   int kh, kw, stride, pad;
   int K, Kpad, M;
@@ -39,6 +38,7 @@ struct ConvArgs {
   int S, sz, sw;  // wave-tile family: K steps in total, per K slice of a workgroup, per wave
   uint32_t mg_wo, mg_cin, mg_kw;  // wave-tile family: multipliers for division by Wo, Cin, kw (see div_magic)
   int MT, NTn, G, xmode;  // wave-tile family: pixel tiles, channel tiles, weight groups (= NTn * splitk), XCD mapping mode
+  int wave_prio;          // 1: the waves raise their issue priority (stages of high-priority tasks on shared CUs)
 };
 
 struct DwArgs {

@@ -312,6 +312,7 @@ __device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L) {
 
   __shared__ float red[NW * TILE];
 
+  if (p.wave_prio) __builtin_amdgcn_s_setprio(3);
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the K loop's control flow scalar
   const int li = lane & 31, lh = lane >> 5;

@@ -40,7 +40,6 @@ struct NetPlan {
   std::vector<LayerPlan> layers;
   std::vector<size_t> slot_bytes; // activation slots after liveness-based reuse
   size_t ws_bytes = 0;            // split-K workspace
-  int n_counters = 0;             // tile arrival counters of the wave-tile kernels (split-K across workgroups)
   std::vector<int> legal_cuts;    // l such that a cut after layer l is legal
   std::vector<int> stage_first;   // first layer of each stage (size = number of stages)
   int n_out = 0;                  // elements of the final output (C*H*W)

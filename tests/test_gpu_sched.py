@@ -204,10 +204,12 @@ def test_stress_set_with_forced_migrations_between_chunks():
         g.close()
 
 
-@pytest.mark.parametrize("streams,lib_flags,des_flags", [(2, 0, 0), (1, D.NO_FIXED, des.F_NO_FIXED), (2, D.NO_LAST | D.NO_PRIOR, des.F_NO_LAST | des.F_NO_PRIOR)])
+@pytest.mark.parametrize("streams,lib_flags,des_flags", [(2, 0, 0), (1, D.NO_FIXED, des.F_NO_FIXED), (2, D.NO_LAST | D.NO_PRIOR, des.F_NO_LAST | des.F_NO_PRIOR),
+                                                         (1, D.WAVE_PRIORITY, 0)])
 def test_saturated_run_with_streams_and_ablation_flags(streams, lib_flags, des_flags):
-    """Two streams per partition (the paper's MPS+STR shape) and the ablation switches, saturated so that stages really
-    compete: the recorded trace replays through the oracle with the same switches, logits match."""
+    """Two streams per partition (the paper's MPS+STR shape), the ablation switches and the wave-priority option (which
+    changes kernel timing only), saturated so that stages really compete: the recorded trace replays through the oracle
+    with the same switches, logits match."""
     ts = wl.make_taskset(2, n_jobs=30)
     g = GpuTaskSet(ts, flags=lib_flags, streams=streams)
     try:
