@@ -352,21 +352,30 @@ __device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L) {
   const int oy = fast_div(m, p.mg_wo), ox = m - oy * p.Wo;
   const int iy0 = oy * p.stride - p.pad, ix0 = ox * p.stride - p.pad;
   // Walk over k = (tap, ci).  ALIGNED (Cin a multiple of KS): both lane halves are always in the same tap, so the
-  // walk state (ky, kx, ci) is wave-uniform and lives in scalars; a lane adds its half's offset lh*VEC.  Otherwise
-  // (the padded network input, Cin < KS) every lane walks on its own.  Inside a tap a step only advances the
-  // pointer; a new tap recomputes pointer and validity.
-  const int k0 = sbeg * KS + (ALIGNED ? 0 : lh * VEC);
-  int tap = fast_div(k0, p.mg_cin);
-  int ci = k0 - tap * p.Cin;
+  // walk state (ky, kx, ci) is wave-uniform and lives in scalars; a lane adds its half's offset lh*VEC, a step
+  // inside a tap only advances the pointer and a new tap recomputes pointer and validity.  Otherwise (the padded
+  // network input, Cin < KS, or Cin not a multiple of KS) each lane derives tap and channel of its vector from the
+  // step number in closed form: no lane-dependent branch, so the loads stay unconditional and pipelined.
+  int kcur = sbeg * KS;  // k of the next step to load (scalar)
+  int tap = fast_div(kcur, p.mg_cin);
+  int ci = kcur - tap * p.Cin;
   int ky = fast_div(tap, p.mg_kw), kx = tap - ky * p.kw;
   bool a_valid;
   const unsigned char* ap;
   auto enter_tap = [&]() {
     const int iy = iy0 + ky, ix = ix0 + kx;
     a_valid = a_ok && ky < p.kh && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
-    ap = xb + ((size_t)(a_valid ? iy * p.W + ix : 0) * p.Cin + ci + (ALIGNED ? lh * VEC : 0)) * ES;  // always a valid address
+    ap = xb + ((size_t)(a_valid ? iy * p.W + ix : 0) * p.Cin + ci + lh * VEC) * ES;  // always a valid address
   };
-  enter_tap();
+  auto locate = [&]() {  // !ALIGNED: this lane's vector of step kcur
+    const int k = kcur + lh * VEC;
+    const int t = fast_div(k, p.mg_cin), c = k - t * p.Cin;
+    const int y = fast_div(t, p.mg_kw), x = t - y * p.kw;
+    const int iy = iy0 + y, ix = ix0 + x;
+    a_valid = a_ok && y < p.kh && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
+    ap = xb + ((size_t)(a_valid ? iy * p.W + ix : 0) * p.Cin + c) * ES;
+  };
+  if (ALIGNED) enter_tap();
   const unsigned char* wptr[TN];
 #pragma unroll
   for (int j = 0; j < TN; ++j)
@@ -376,6 +385,7 @@ __device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L) {
   bool av[D];  // validity of slot d's A vector; the blanking is applied when the slot is consumed, so that a load's
                // result is not touched (and not waited for) until D-1 later steps have been issued
   auto load = [&](int d) {
+    if (!ALIGNED) locate();
     ar[d] = *(const uint4*)ap;
     av[d] = a_valid;
 #pragma unroll
@@ -383,15 +393,17 @@ __device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L) {
       br[d][j] = *(const uint4*)wptr[j];
       wptr[j] += 1024;
     }
-    ci += KS;
-    if (ci >= p.Cin) {  // uniform branch when ALIGNED
-      do {
+    if (ALIGNED) {
+      ci += KS;
+      if (ci >= p.Cin) {  // wave-uniform
         ci -= p.Cin;
         if (++kx == p.kw) { kx = 0; ++ky; }
-      } while (!ALIGNED && ci >= p.Cin);
-      enter_tap();
+        enter_tap();
+      } else {
+        ap += KS * ES;
+      }
     } else {
-      ap += KS * ES;
+      kcur += KS;
     }
   };
 
