@@ -161,6 +161,13 @@ ConvArgs conv_args(TaskRt& T, int l, void* y) {
 }
 
 hipError_t launch_layer(TaskRt& T, int l, void* d_logits, hipStream_t s, bool sample = false) {
+  // Diagnostic: DARIS_HOST_LAUNCH_DELAY_US=n makes the host spin n microseconds before every launch, which
+  // reproduces the regime a tracing profiler puts the run in (host-bound launches, kernels starting on an idle GPU).
+  static const int delay_us = getenv("DARIS_HOST_LAUNCH_DELAY_US") ? atoi(getenv("DARIS_HOST_LAUNCH_DELAY_US")) : 0;
+  if (delay_us > 0) {
+    const auto until = std::chrono::steady_clock::now() + std::chrono::microseconds(delay_us);
+    while (std::chrono::steady_clock::now() < until) {}
+  }
   NetPlan& net = T.net;
   LayerPlan& L = net.layers[l];
   const TensorInfo& in = net.tensor(L.in_t);
