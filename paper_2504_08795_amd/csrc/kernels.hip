@@ -306,11 +306,11 @@ __device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L) {
   constexpr int KS = 2 * VEC;
   constexpr int NT = NW * 64;
   constexpr int TILE = TN * 1024;
-  constexpr int PER = TILE / NT;
   constexpr int D = 4;
-  static_assert(TILE % NT == 0, "tile / thread mismatch");
+  static_assert(TN == 1 || TN == 2, "the epilogue selects between at most two channel blocks");
+  static_assert((TILE / 4) % NT == 0 || NT % (TILE / 4) == 0, "tile / thread mismatch");
 
-  __shared__ float red[NW * TILE];
+  __shared__ __align__(16) float red[NW * TILE];
 
   if (p.wave_prio) __builtin_amdgcn_s_setprio(3);
   const int tid = threadIdx.x, lane = tid & 63;
@@ -407,12 +407,16 @@ __device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L) {
     }
   };
 
-  // bias of this thread's epilogue columns, fetched before the K loop so that its latency is hidden
-  float bias_j[TN];
+  // The epilogue works on quads of consecutive channels: quad q of the tile = elements 4q..4q+3 = lanes l..l+3 of one
+  // accumulator row (j, v), i.e. one pixel and channels 32*(nb0+j) + l%32 .. +3.  A thread's quads q = tid + r*NT all
+  // have the same l, so it needs the bias of one channel quad per channel block; fetched here, before the K loop,
+  // so that the latency is hidden.
+  const int ql = (4 * tid) & 63;  // first lane of this thread's quads
+  float4 bias_j[TN];
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
-    const int n = (nb0 + j) * 32 + li;
-    bias_j[j] = (n < p.Cout) ? p.bias[n] : 0.f;
+    const int n = (nb0 + j) * 32 + (ql & 31);
+    bias_j[j] = (n < p.Cout) ? *(const float4*)(p.bias + n) : make_float4(0.f, 0.f, 0.f, 0.f);
   }
 
   f32x16 acc[TN];
@@ -470,31 +474,54 @@ __device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) red[wave * TILE + (j * 16 + v) * 64 + lane] = acc[j][v];
   __syncthreads();
-  float vals[PER];
+  // --- epilogue per channel quad: pixel m0 + 8*(v/4) + 4*(lane/32) + v%4, channels 32*(nb0+j) + lane%32 .. +3 ---------
+  constexpr int QUADS = TILE / 4;
 #pragma unroll
-  for (int r = 0; r < PER; ++r) {
-    const int e = tid + r * NT;
-    float s = red[e];
+  for (int r = 0; r < (QUADS + NT - 1) / NT; ++r) {
+    const int q = tid + r * NT;
+    if (QUADS % NT != 0 && q >= QUADS) break;
+    const int e = 4 * q;
+    float4 sum = *(const float4*)&red[e];
 #pragma unroll
-    for (int w = 1; w < NW; ++w) s += red[w * TILE + e];
-    vals[r] = s;
-  }
-
-  // --- epilogue: element e of the tile is pixel m0 + 8*(v/4) + 4*(lane/32) + v%4, channel 32*(nb0+j) + lane%32 ------
-#pragma unroll
-  for (int r = 0; r < PER; ++r) {
-    const int e = tid + r * NT;
+    for (int w = 1; w < NW; ++w) {
+      const float4 t = *(const float4*)&red[w * TILE + e];
+      sum.x += t.x; sum.y += t.y; sum.z += t.z; sum.w += t.w;
+    }
     const int j = e >> 10, v = (e >> 6) & 15, l = e & 63;
     const int mm = m0 + (v >> 2) * 8 + (l >> 5) * 4 + (v & 3);
     const int n = (nb0 + j) * 32 + (l & 31);
     if (mm < p.M && n < p.Cout) {
       const size_t o = (size_t)mm * p.Cout + n;
       if (p.splitk > 1) {  // partial sums of this K slice; splitk_reduce_kernel finishes the layer
-        p.ws[(size_t)zi * p.M * p.Cout + o] = vals[r];
+        *(float4*)(p.ws + (size_t)zi * p.M * p.Cout + o) = sum;
       } else {
-        float val = vals[r] + bias_j[j];
-        if (p.res) val += load_elem<BF16>(p.res, o);
-        store_elem<BF16>(p.y, o, apply_act(val, p.act));
+        float4 b = bias_j[0];  // component-wise select: indexing the array with a run-time j would move it out of registers
+        if (TN == 2) {
+          const bool hi = j != 0;
+          b.x = hi ? bias_j[TN - 1].x : b.x; b.y = hi ? bias_j[TN - 1].y : b.y;
+          b.z = hi ? bias_j[TN - 1].z : b.z; b.w = hi ? bias_j[TN - 1].w : b.w;
+        }
+        float val[4] = {sum.x + b.x, sum.y + b.y, sum.z + b.z, sum.w + b.w};
+        if (p.res) {
+          if (BF16) {
+            const uint2 rv = *(const uint2*)((const uint16_t*)p.res + o);
+            val[0] += __uint_as_float(rv.x << 16); val[1] += __uint_as_float(rv.x & 0xffff0000u);
+            val[2] += __uint_as_float(rv.y << 16); val[3] += __uint_as_float(rv.y & 0xffff0000u);
+          } else {
+            const float4 rv = *(const float4*)((const float*)p.res + o);
+            val[0] += rv.x; val[1] += rv.y; val[2] += rv.z; val[3] += rv.w;
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) val[i] = apply_act(val[i], p.act);
+        if (BF16) {
+          uint2 out;
+          out.x = f32_to_bf16_bits(val[0]) | (f32_to_bf16_bits(val[1]) << 16);
+          out.y = f32_to_bf16_bits(val[2]) | (f32_to_bf16_bits(val[3]) << 16);
+          *(uint2*)((uint16_t*)p.y + o) = out;
+        } else {
+          *(float4*)((float*)p.y + o) = make_float4(val[0], val[1], val[2], val[3]);
+        }
       }
     }
   }
