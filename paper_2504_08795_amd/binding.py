@@ -81,6 +81,7 @@ _SIGS = {
     "daris_calibrate_afet_loaded": (C.c_int32, [C.c_int32, C.c_int32, C.c_int]),
     "daris_kernel_timing_start": (C.c_int32, [C.c_int, C.c_int]),
     "daris_driver_profile": (C.c_int32, [C.c_int, C.POINTER(C.c_int64)]),
+    "daris_get_launch_plan": (C.c_int32, [C.c_int32, C.c_int, C.POINTER(C.c_int64), C.c_int32]),
     "daris_kernel_timing_read": (C.c_int32, [C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "daris_probe_cus": (C.c_int32, [C.c_int32, C.c_int, C.c_int, C.POINTER(C.c_uint32)]),
 }
@@ -179,6 +180,16 @@ def daris_get_stage_cuts(t):
     buf = (C.c_int32 * 256)()
     n = _chk(lib().daris_get_stage_cuts(t, buf, 256))
     return list(buf[:n])
+
+
+PLAN_FIELDS = ("kernel_id", "dense_conv", "wave", "M", "N", "K", "Kpad", "tn", "nw", "S", "sz", "sw", "splitk", "MT", "NTn", "G", "xmode",
+               "grid_x", "grid_y", "grid_z", "threads", "ws_bytes", "pair_with", "pair_lead")
+
+
+def daris_get_launch_plan(t, layer):
+    buf = (C.c_int64 * 24)()
+    _chk(lib().daris_get_launch_plan(t, layer, buf, 24))
+    return dict(zip(PLAN_FIELDS, (int(v) for v in buf)))
 
 
 def daris_set_afet(t, stage, ns):

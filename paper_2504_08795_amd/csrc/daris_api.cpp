@@ -634,6 +634,22 @@ int32_t daris_get_stage_cuts(daris_task t, int32_t* first_layer, int32_t cap) {
   return (int32_t)f.size();
 }
 
+int32_t daris_get_launch_plan(daris_task t, int layer, int64_t* out, int32_t cap) {
+  daris_status st = check_task(t);
+  if (st != DARIS_OK) return st;
+  const NetPlan& net = G->tasks[t]->net;
+  if (layer < 0 || layer >= (int)net.layers.size()) return fail(DARIS_ERANGE, "layer %d out of range", layer);
+  if (!out || cap < 24) return fail(DARIS_EINVAL, "out must hold 24 entries");
+  const LayerPlan& L = net.layers[layer];
+  const ConvPlan& c = L.cp;
+  const bool conv = L.d.op == DARIS_OP_CONV && !L.depthwise;
+  const int64_t v[24] = {L.kernel_id, conv ? 1 : 0, conv ? c.wave : 0, (int64_t)L.out.H * L.out.W, L.out.Cs, L.K, L.Kpad,
+                         c.tn, c.nw, c.S, c.sz, c.sw, c.splitk, c.MT, c.NTn, c.G, c.xmode, c.grid.x, c.grid.y, c.grid.z,
+                         c.threads, (int64_t)c.ws_bytes, L.pair_with, L.pair_lead ? 1 : 0};
+  for (int i = 0; i < 24; ++i) out[i] = v[i];
+  return 24;
+}
+
 daris_status daris_set_afet(daris_task t, int stage, int64_t ns) {
   daris_status st = check_task(t);
   if (st != DARIS_OK) return st;

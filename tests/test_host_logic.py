@@ -137,6 +137,79 @@ def test_stage_split_matches_oracle(net, ks):
             D.daris_split_stages(t, len(legal) + 2)
 
 
+def _check_plan(pl, name):
+    """What the kernels and their grids assume about a dense convolution's launch plan."""
+    M, N, S = pl["M"], pl["N"], pl["S"]
+    z = pl["splitk"]
+    assert pl["grid_z"] == (1 if pl["wave"] else z) and pl["grid_x"] >= 1, name
+    if z > 1:
+        assert pl["ws_bytes"] >= z * M * N * 4, name                       # one fp32 partial tile set per K slice
+    if not pl["wave"]:
+        return
+    tn, nw = pl["tn"], pl["nw"]
+    assert tn in (1, 2) and nw in (2, 4, 8) and pl["threads"] == 64 * nw, name
+    assert D.daris_kernel_name(pl["kernel_id"]).endswith(f"t{tn}w{nw}"), name
+    nb = (N + 31) // 32
+    assert nb % tn == 0 and pl["NTn"] * tn == nb and pl["MT"] == (M + 31) // 32, name
+    assert S * (8 if "f32" in D.daris_kernel_name(pl["kernel_id"]) else 16) == pl["Kpad"], name
+    # the z slices cover all K steps and none is empty; the nw waves cover their slice
+    assert z >= 1 and pl["sz"] * z >= S and pl["sz"] * (z - 1) < S, name
+    assert pl["sw"] * nw >= pl["sz"] and pl["sw"] >= 1, name
+    assert pl["G"] == pl["NTn"] * z, name
+    # workgroup order: every (pixel tile, weight group) is reached, groups with equal id mod 8 stay together
+    if pl["xmode"] == 1:
+        assert pl["G"] % 8 == 0 and pl["grid_x"] == pl["G"] * pl["MT"], name
+    elif pl["xmode"] == 2:
+        r = 8 // pl["G"]
+        assert 8 % pl["G"] == 0 and pl["grid_x"] == 8 * ((pl["MT"] + r - 1) // r), name
+    else:
+        assert pl["xmode"] == 0 and pl["grid_x"] == pl["G"] * pl["MT"], name
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("net", ["tiny", "resnet18", "resnet50", "vgg16", "mobilenet_v2"])
+def test_launch_plans_satisfy_kernel_assumptions(net, dtype):
+    layers, shp = wl.build_net(net)
+    with Session(HOST):
+        D.daris_create_partition(64)
+        dnn, keep = D.make_dnn(layers, None, shp, dtype)
+        t = D.daris_register_task(dnn, 10**7, 10**7, D.LP)
+        plans = [D.daris_get_launch_plan(t, l) for l in range(len(layers))]
+    n_pairs = 0
+    for l, (L, pl) in enumerate(zip(layers, plans)):
+        if not pl["dense_conv"]:
+            assert pl["pair_with"] == -1
+            continue
+        _check_plan(pl, f"{net} {dtype} layer {l} {L.name}")
+        if pl["pair_with"] >= 0:
+            o = plans[pl["pair_with"]]
+            assert abs(pl["pair_with"] - l) == 1 and o["pair_with"] == l and pl["pair_lead"] != o["pair_lead"]
+            assert pl["pair_lead"] == (pl["pair_with"] < l)                    # issued at the later layer
+            assert layers[l].in_from == layers[pl["pair_with"]].in_from       # both read the same tensor
+            assert o["kernel_id"] == pl["kernel_id"] and o["wave"] and pl["wave"]
+            light = pl if wl.net_macs(layers, shp)[l] < wl.net_macs(layers, shp)[pl["pair_with"]] else o
+            assert light["splitk"] == 1                                        # the second problem never splits K across workgroups
+            n_pairs += 1
+    assert n_pairs // 2 == {"tiny": 0, "resnet18": 3, "resnet50": 4, "vgg16": 0, "mobilenet_v2": 0}[net]
+
+
+def test_launch_plans_of_odd_shapes():
+    rng = np.random.default_rng(5)
+    N = wl.nets
+    with Session(HOST):
+        D.daris_create_partition(64)
+        for i in range(150):
+            cin, cout = int(rng.integers(1, 700)), int(rng.integers(1, 700))
+            k = int(rng.choice([1, 3, 5, 7]))
+            h, w = int(rng.integers(k, 70)), int(rng.integers(k, 70))
+            s = int(rng.choice([1, 2]))
+            layers = [N.Layer(op=N.OP_CONV, c_in=cin, c_out=cout, k=k, stride=s, pad=k // 2, act=1, in_from=-1)]
+            for dtype in ("fp32", "bf16"):
+                dnn, keep = D.make_dnn(layers, None, (cin, h, w), dtype)
+                t = D.daris_register_task(dnn, 10**7, 10**7, D.LP)
+                _check_plan(D.daris_get_launch_plan(t, 0), f"{cin}x{h}x{w}->{cout} k{k} s{s} {dtype}")
+
+
 def test_stage_split_known_results():
     """Per-stage MAC totals at the benchmark configurations (integers from the layer tables)."""
     def stage_macs(net, k):
