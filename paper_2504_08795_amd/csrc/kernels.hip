@@ -753,7 +753,7 @@ static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16, int force_tn = 
   if (force_tn) tn = force_tn;
   const int tiles = cdiv(M, 32) * (nb / tn);
   const int nominal_cus = kNominalWaveSlots / 4;
-  int nw = 8;
+  int nw = bf16 ? 4 : 8;  // bf16 steps are short: fewer waves to sum through LDS beat a finer K split (measured 0.4-0.8 us per layer)
   while (nw > 2 && (S / nw < 4 || tiles * nw > 8 * kNominalWaveSlots)) nw /= 2;  // >= 4 steps per wave, <= 8 waves per SIMD
   int z = nominal_cus / tiles;
   if (z < 1) z = 1;
