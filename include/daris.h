@@ -161,7 +161,7 @@ daris_status daris_split_stages(daris_task t, int k);
 int32_t daris_get_stage_cuts(daris_task t, int32_t* first_layer, int32_t cap);
 /* Launch plan of one layer, for inspection and for host-side checks of what the kernels assume (no device needed).
  * Writes 24 values into out (host int64[cap >= 24]) and returns 24: [0] kernel id (daris_kernel_name), [1] 1 = dense
- * convolution (the rest is meaningful only then), [2] 1 = wave-tile family / 0 = LDS-tiled family, [3] M = output
+ * convolution (the rest is meaningful only then), [2] 1 (one kernel family), [3] M = output
  * pixels, [4] N = output channels incl. padding, [5] K, [6] K padded, [7] channel blocks of 32 per wave tile, [8] waves
  * per workgroup, [9] K steps in total, [10] per workgroup slice, [11] per wave, [12] split-K factor, [13] pixel tiles,
  * [14] channel tiles, [15] weight groups, [16] workgroup order mode, [17..19] grid x y z, [20] threads per workgroup,

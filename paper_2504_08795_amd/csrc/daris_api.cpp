@@ -154,7 +154,7 @@ ConvArgs conv_args(TaskRt& T, int l, void* y) {
   a.H = in.H; a.W = in.W; a.Cin = in.Cs; a.Ho = L.out.H; a.Wo = L.out.W; a.Cout = L.out.Cs;
   a.kh = a.kw = L.d.k; a.stride = L.d.stride; a.pad = L.d.pad;
   a.K = L.K; a.Kpad = L.Kpad; a.M = L.out.H * L.out.W; a.act = L.d.act;
-  a.splitk = L.cp.splitk; a.kchunk = L.cp.kchunk; a.S = L.cp.S; a.sz = L.cp.sz; a.sw = L.cp.sw;
+  a.splitk = L.cp.splitk; a.S = L.cp.S; a.sz = L.cp.sz; a.sw = L.cp.sw;
   a.MT = L.cp.MT; a.NTn = L.cp.NTn; a.G = L.cp.G; a.xmode = L.cp.xmode;
   a.mg_wo = div_magic((uint32_t)a.Wo); a.mg_cin = div_magic((uint32_t)a.Cin); a.mg_kw = div_magic((uint32_t)a.kw);
   return a;
@@ -643,7 +643,7 @@ int32_t daris_get_launch_plan(daris_task t, int layer, int64_t* out, int32_t cap
   const LayerPlan& L = net.layers[layer];
   const ConvPlan& c = L.cp;
   const bool conv = L.d.op == DARIS_OP_CONV && !L.depthwise;
-  const int64_t v[24] = {L.kernel_id, conv ? 1 : 0, conv ? c.wave : 0, (int64_t)L.out.H * L.out.W, L.out.Cs, L.K, L.Kpad,
+  const int64_t v[24] = {L.kernel_id, conv ? 1 : 0, conv ? 1 : 0, (int64_t)L.out.H * L.out.W, L.out.Cs, L.K, L.Kpad,
                          c.tn, c.nw, c.S, c.sz, c.sw, c.splitk, c.MT, c.NTn, c.G, c.xmode, c.grid.x, c.grid.y, c.grid.z,
                          c.threads, (int64_t)c.ws_bytes, L.pair_with, L.pair_lead ? 1 : 0};
   for (int i = 0; i < 24; ++i) out[i] = v[i];

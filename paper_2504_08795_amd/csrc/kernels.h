@@ -11,9 +11,6 @@ namespace daris {
 
 enum KernelId : int32_t {
   K_NONE = 0,
-  // LDS-tiled implicit GEMM, BMxBN workgroup tiles
-  K_CONV_F32_128x64, K_CONV_F32_64x64, K_CONV_F32_64x32, K_CONV_F32_32x64, K_CONV_F32_32x32,
-  K_CONV_BF16_128x64, K_CONV_BF16_64x64, K_CONV_BF16_64x32, K_CONV_BF16_32x64, K_CONV_BF16_32x32,
   // wave-tile implicit GEMM: TN 32-channel blocks per wave, NW waves splitting K inside the workgroup
   K_CONVW_F32_T1W2, K_CONVW_F32_T1W4, K_CONVW_F32_T1W8, K_CONVW_F32_T2W2, K_CONVW_F32_T2W4, K_CONVW_F32_T2W8,
   K_CONVW_BF16_T1W2, K_CONVW_BF16_T1W4, K_CONVW_BF16_T1W8, K_CONVW_BF16_T2W2, K_CONVW_BF16_T2W4, K_CONVW_BF16_T2W8,
@@ -24,7 +21,7 @@ const char* kernel_name(int32_t id);
 
 struct ConvArgs {
   const void* x;      // [H][W][Cin]
-  const void* w;      // packed weights, layout per kernel family (see pack_conv)
+  const void* w;      // packed weights in MFMA fragment order (see pack_conv)
   const float* bias;  // [Cout]
   const void* res;    // [Ho*Wo][Cout] or nullptr
   void* y;            // [Ho*Wo][Cout]
@@ -34,10 +31,9 @@ struct ConvArgs {
   int K, Kpad, M;
   int act;
   int splitk;  // grid.z
-  int kchunk;  // LDS-tiled family: k range per split, multiple of the kernel's BK
-  int S, sz, sw;  // wave-tile family: K steps in total, per K slice of a workgroup, per wave
-  uint32_t mg_wo, mg_cin, mg_kw;  // wave-tile family: multipliers for division by Wo, Cin, kw (see div_magic)
-  int MT, NTn, G, xmode;  // wave-tile family: pixel tiles, channel tiles, weight groups (= NTn * splitk), XCD mapping mode
+  int S, sz, sw;  // K steps in total, per K slice of a workgroup, per wave
+  uint32_t mg_wo, mg_cin, mg_kw;  // multipliers for division by Wo, Cin, kw (see div_magic)
+  int MT, NTn, G, xmode;  // pixel tiles, channel tiles, weight groups (= NTn * splitk), XCD mapping mode
   int wave_prio;          // 1: the waves raise their issue priority (stages of high-priority tasks on shared CUs)
 };
 
@@ -66,16 +62,15 @@ struct FcArgs {
 // Kernel and tile configuration chosen on the host for one dense convolution.
 struct ConvPlan {
   int32_t kernel;  // KernelId
-  int wave;        // 1 = wave-tile family, 0 = LDS-tiled family
-  int bm, bn, bk, splitk, kchunk;  // LDS-tiled family
-  int tn, nw, S, sz, sw, MT, NTn, G, xmode;  // wave-tile family
+  int splitk;      // K slices across workgroups (1 = none); > 1 needs the workspace and the reduction launch
+  int tn, nw, S, sz, sw, MT, NTn, G, xmode;
   int tiles;                       // output tiles per grid.z slice
   size_t ws_bytes;                 // split-K workspace this launch needs
   dim3 grid;
   int threads;
 };
-// bf16 = 0/1.  Chooses family, tile shape and split-K from (M, N, Kpad) only, so results do not depend on the
-// partition a stage runs in.  Environment variable DARIS_CONV_KERNEL = tile | wave forces one family.
+// bf16 = 0/1.  Chooses tile shape, waves per workgroup and split-K from (M, N, Kpad) only, so results do not depend on the
+// partition a stage runs in.
 ConvPlan plan_conv(int M, int N, int Kpad, int bf16);
 
 // If t0/t1 are given they are recorded on `s` immediately before and after the main kernel (not the split-K reduce).
@@ -83,7 +78,7 @@ hipError_t launch_conv(const ConvPlan& pl, const ConvArgs& a, int bf16, hipStrea
 // Plan for a second convolution that is to share a launch with `first` (launch_conv_pair): the same wave-tile kernel
 // variant, K not split across workgroups.  Returns a plan with kernel == K_NONE when that is not possible.
 ConvPlan plan_conv_like(const ConvPlan& first, int M, int N, int Kpad, int bf16);
-// One launch for two independent convolutions: pl0/a0 as planned by plan_conv (wave-tile family), pl1/a1 by
+// One launch for two independent convolutions: pl0/a0 as planned by plan_conv, pl1/a1 by
 // plan_conv_like(pl0, ...).  The event pair brackets the joint kernel.
 hipError_t launch_conv_pair(const ConvPlan& pl0, const ConvArgs& a0, const ConvPlan& pl1, const ConvArgs& a1, int bf16, hipStream_t s,
                             hipEvent_t t0 = nullptr, hipEvent_t t1 = nullptr);

@@ -83,178 +83,6 @@ __device__ __forceinline__ uint4 pack(const float* o) {
   return v;
 }
 
-// ---- implicit-GEMM convolution ----------------------------------------------------------------------------------
-//
-// GEMM view (batch 1): Y[M = Ho*Wo][N = Cout] = A[M][K] * W^T, K = kh*kw*Cin with k = (ky*kw + kx)*Cin + ci.
-// A is never materialised: each 16-byte vector of a tile row is gathered from the NHWC input (Cin is a multiple
-// of the vector width, so a vector never straddles two filter taps).  Both tiles are staged in LDS with the K
-// dimension contiguous ("row = pixel or output channel, KV vectors of 16 bytes per row", row stride (KV+1)*16
-// bytes so that eight lanes reading 16 bytes each hit 32 distinct banks), double buffered, one barrier per
-// K step.  A wave owns a WM x WN block built from 32x32 MFMA tiles: rows of the MFMA A operand are pixels,
-// columns of the B operand are output channels, so that one accumulator register of all 32 lanes of a
-// half-wave is a contiguous 128-byte run of one output pixel.
-//   fp32 : v_mfma_f32_32x32x2_f32, four per 16-byte vector pair (lane half h, element s  <->  k = 4*(2q+h)+s);
-//   bf16 : v_mfma_f32_32x32x16_bf16, one per vector pair (lane half h, element e  <->  k = 8*(2q+h)+e).
-// The same k <-> (lane, element) map is used for both operands, which is all a dot product needs.
-template <bool BF16, int BM, int BN, int WM, int WN, int KV>
-__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void conv_igemm_kernel(const ConvArgs p) {
-  constexpr int ES = BF16 ? 2 : 4;
-  constexpr int VEC = 16 / ES;
-  constexpr int BK = KV * VEC;
-  constexpr int WAVES_N = BN / WN;
-  constexpr int NT = (BM / WM) * WAVES_N * 64;
-  constexpr int ROWB = (KV + 1) * 16;
-  constexpr int A_LD = BM * KV / NT, B_LD = BN * KV / NT;
-  constexpr int TM = WM / 32, TN = WN / 32;
-  static_assert(BM * KV % NT == 0 && BN * KV % NT == 0 && NT % KV == 0 && KV % 2 == 0, "tile / thread mismatch");
-
-  __shared__ __attribute__((aligned(16))) unsigned char lds[2][(BM + BN) * ROWB];
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
-  const int kbeg = blockIdx.z * p.kchunk;
-  const int kend = min(kbeg + p.kchunk, p.Kpad);
-  const int nit = (kend - kbeg) / BK;
-
-  const unsigned char* xb = (const unsigned char*)p.x;
-  const unsigned char* wb = (const unsigned char*)p.w;
-
-  // --- per-thread gather state: all vectors of a thread share the k slot kv, rows differ -------------------------
-  const int kv = tid % KV;
-  int a_iy0[A_LD], a_ix0[A_LD];
-  bool a_ok[A_LD];
-#pragma unroll
-  for (int r = 0; r < A_LD; ++r) {
-    const int row = (tid + r * NT) / KV;
-    const int m = m0 + row;
-    a_ok[r] = m < p.M;
-    const int oy = m / p.Wo, ox = m - oy * p.Wo;
-    a_iy0[r] = oy * p.stride - p.pad;
-    a_ix0[r] = ox * p.stride - p.pad;
-  }
-  size_t b_off[B_LD];
-  bool b_ok[B_LD];
-#pragma unroll
-  for (int r = 0; r < B_LD; ++r) {
-    const int n = n0 + (tid + r * NT) / KV;
-    b_ok[r] = n < p.Cout;
-    b_off[r] = ((size_t)n * p.Kpad + kbeg + kv * VEC) * ES;
-  }
-  int kcur = kbeg + kv * VEC;
-  int tap = kcur / p.Cin;
-  int ci = kcur - tap * p.Cin;
-  int ky = tap / p.kw, kx = tap - ky * p.kw;
-
-  uint4 areg[A_LD], breg[B_LD];
-  bool aval[A_LD];
-
-  auto gload = [&]() {
-#pragma unroll
-    for (int r = 0; r < A_LD; ++r) {
-      const int iy = a_iy0[r] + ky, ix = a_ix0[r] + kx;
-      const bool ok = a_ok[r] && ky < p.kh && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
-      // always load from a valid address and blank the value afterwards: keeps the access a plain global load
-      const size_t off = ok ? ((size_t)(iy * p.W + ix) * p.Cin + ci) * ES : 0;
-      areg[r] = *(const uint4*)(xb + off);
-      aval[r] = ok;
-    }
-#pragma unroll
-    for (int r = 0; r < B_LD; ++r) {
-      breg[r] = *(const uint4*)(wb + (b_ok[r] ? b_off[r] : (size_t)0));
-      b_off[r] += (size_t)BK * ES;
-    }
-    ci += BK;
-    while (ci >= p.Cin) {
-      ci -= p.Cin;
-      if (++kx == p.kw) { kx = 0; ++ky; }
-    }
-  };
-  auto lstore = [&](int buf) {
-#pragma unroll
-    for (int r = 0; r < A_LD; ++r) {
-      const int row = (tid + r * NT) / KV;
-      *(uint4*)(&lds[buf][row * ROWB + kv * 16]) = keep_if(aval[r], areg[r]);  // blanked here, not at the load
-    }
-#pragma unroll
-    for (int r = 0; r < B_LD; ++r) {
-      const int row = (tid + r * NT) / KV;
-      *(uint4*)(&lds[buf][(BM + row) * ROWB + kv * 16]) = keep_if(b_ok[r], breg[r]);
-    }
-  };
-
-  const int wm = wave / WAVES_N, wn = wave - wm * WAVES_N;
-  const int li = lane & 31, lh = lane >> 5;
-
-  f32x16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-  if (nit > 0) {
-    gload();
-    lstore(0);
-  }
-  __syncthreads();
-
-  for (int it = 0; it < nit; ++it) {
-    const int buf = it & 1;
-    if (it + 1 < nit) gload();
-    const unsigned char* As = &lds[buf][(wm * WM + li) * ROWB + lh * 16];
-    const unsigned char* Bs = &lds[buf][(BM + wn * WN + li) * ROWB + lh * 16];
-#pragma unroll
-    for (int q = 0; q < KV / 2; ++q) {
-      uint4 av[TM], bv[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i) av[i] = *(const uint4*)(As + i * 32 * ROWB + q * 32);
-#pragma unroll
-      for (int j = 0; j < TN; ++j) bv[j] = *(const uint4*)(Bs + j * 32 * ROWB + q * 32);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          if (BF16) {
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av[i]),
-                                                                __builtin_bit_cast(bf16x8, bv[j]), acc[i][j], 0, 0, 0);
-          } else {
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av[i].x), __uint_as_float(bv[j].x), acc[i][j], 0, 0, 0);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av[i].y), __uint_as_float(bv[j].y), acc[i][j], 0, 0, 0);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av[i].z), __uint_as_float(bv[j].z), acc[i][j], 0, 0, 0);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av[i].w), __uint_as_float(bv[j].w), acc[i][j], 0, 0, 0);
-          }
-        }
-    }
-    if (it + 1 < nit) lstore(buf ^ 1);
-    __syncthreads();
-  }
-
-  // --- epilogue: accumulator register v of lane (li, lh) is row 8*(v/4) + 4*lh + (v%4), column li of a 32x32 tile -
-#pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int n = n0 + wn * WN + j * 32 + li;
-    if (n >= p.Cout) continue;
-    const float bias = (p.splitk == 1) ? p.bias[n] : 0.f;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int m = m0 + wm * WM + i * 32 + (v >> 2) * 8 + lh * 4 + (v & 3);
-        if (m >= p.M) continue;
-        const size_t o = (size_t)m * p.Cout + n;
-        if (p.splitk == 1) {
-          float val = acc[i][j][v] + bias;
-          if (p.res) val += load_elem<BF16>(p.res, o);
-          store_elem<BF16>(p.y, o, apply_act(val, p.act));
-        } else {
-          p.ws[(size_t)blockIdx.z * p.M * p.Cout + o] = acc[i][j][v];
-        }
-      }
-    }
-  }
-}
-
 // Sums the split-K partials in split order and applies the fused epilogue.  One thread per 4 output channels.
 template <bool BF16>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ ws, const float* __restrict__ bias,
@@ -691,8 +519,6 @@ __global__ __launch_bounds__(64) void cu_probe_kernel(uint32_t* out, int spin) {
 
 static const char* const kNames[K_COUNT] = {
     "none",
-    "conv_igemm_f32_128x64", "conv_igemm_f32_64x64", "conv_igemm_f32_64x32", "conv_igemm_f32_32x64", "conv_igemm_f32_32x32",
-    "conv_igemm_bf16_128x64", "conv_igemm_bf16_64x64", "conv_igemm_bf16_64x32", "conv_igemm_bf16_32x64", "conv_igemm_bf16_32x32",
     "conv_wave_f32_t1w2", "conv_wave_f32_t1w4", "conv_wave_f32_t1w8", "conv_wave_f32_t2w2", "conv_wave_f32_t2w4", "conv_wave_f32_t2w8",
     "conv_wave_bf16_t1w2", "conv_wave_bf16_t1w4", "conv_wave_bf16_t1w8", "conv_wave_bf16_t2w2", "conv_wave_bf16_t2w4", "conv_wave_bf16_t2w8",
     "splitk_reduce", "dwconv", "maxpool", "gavgpool", "fc", "ingest", "egress"};
@@ -703,45 +529,11 @@ static inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
 static const int kNominalWaveSlots = 512;  // 128 CUs x 4 SIMDs: the partition size the plans are tuned for
 
-static ConvPlan plan_conv_tile(int M, int N, int Kpad, int bf16) {
-  ConvPlan pl = ConvPlan();
-  const int bk = bf16 ? 32 : 16;  // KV = 4 vectors of 16 bytes per tile row
-  pl.bk = bk;
-  const int blocks32 = cdiv(M, 32) * cdiv(N, 32);  // 32x32 MFMA tiles in the output
-  int variant;                                     // 0: 128x64, 1: 64x64, 2: 64x32, 3: 32x64, 4: 32x32
-  if (blocks32 >= 4 * kNominalWaveSlots && N >= 64) variant = 0;
-  else if (N <= 32) variant = (M > 32) ? 2 : 4;
-  else if (M <= 32) variant = 3;
-  else variant = 1;
-  static const int bm_[5] = {128, 64, 64, 32, 32}, bn_[5] = {64, 64, 32, 64, 32}, thr_[5] = {256, 256, 128, 128, 64};
-  pl.bm = bm_[variant];
-  pl.bn = bn_[variant];
-  pl.threads = thr_[variant];
-  pl.kernel = (bf16 ? K_CONV_BF16_128x64 : K_CONV_F32_128x64) + variant;
-  // split-K until the launch has about one wave per SIMD of the nominal partition
-  int splitk = 1;
-  if (variant != 0 && blocks32 < kNominalWaveSlots) {
-    splitk = cdiv(kNominalWaveSlots, blocks32);
-    const int max_by_k = Kpad / (4 * bk) > 0 ? Kpad / (4 * bk) : 1;  // at least four K steps per split
-    if (splitk > max_by_k) splitk = max_by_k;
-    if (splitk > 16) splitk = 16;
-  }
-  int kchunk = cdiv(cdiv(Kpad, splitk), bk) * bk;
-  splitk = cdiv(Kpad, kchunk);
-  pl.splitk = splitk;
-  pl.kchunk = kchunk;
-  pl.grid = dim3(cdiv(M, pl.bm), cdiv(N, pl.bn), splitk);
-  pl.tiles = pl.grid.x * pl.grid.y;
-  pl.ws_bytes = splitk > 1 ? (size_t)splitk * M * N * sizeof(float) : 0;
-  return pl;
-}
-
 static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16, int force_tn = 0, int force_nw = 0) {
   // Measured on a 128-CU partition (fp32, ResNet-18 shapes): the K loop itself runs near the MFMA rate; what a
   // launch pays for is its fixed cost and idle CUs.  Best found: 8 waves per workgroup splitting K, and enough
   // grid.z slices that tiles * z is about the number of CUs, while a wave keeps at least ~6 steps.
   ConvPlan pl = ConvPlan();
-  pl.wave = 1;
   const int ks = bf16 ? 16 : 8;  // k per step: two 16-byte vectors
   const int S = Kpad / ks;
   const int nb = cdiv(N, 32);
@@ -802,27 +594,18 @@ static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16, int force_tn = 
   return pl;
 }
 
-ConvPlan plan_conv(int M, int N, int Kpad, int bf16) {
-  const char* force = getenv("DARIS_CONV_KERNEL");
-  if (force && !strcmp(force, "tile")) return plan_conv_tile(M, N, Kpad, bf16);
-  if (force && !strcmp(force, "wave")) return plan_conv_wave(M, N, Kpad, bf16);
-  // Large outputs fill the partition with LDS-shared 128x64 tiles and read each operand far fewer times;
-  // everything smaller is latency bound and goes to the wave-tile family.
-  const int blocks32 = cdiv(M, 32) * cdiv(N, 32);
-  if (blocks32 >= 4 * kNominalWaveSlots && N >= 64) return plan_conv_tile(M, N, Kpad, bf16);
-  return plan_conv_wave(M, N, Kpad, bf16);
-}
+ConvPlan plan_conv(int M, int N, int Kpad, int bf16) { return plan_conv_wave(M, N, Kpad, bf16); }
 
 ConvPlan plan_conv_like(const ConvPlan& first, int M, int N, int Kpad, int bf16) {
   ConvPlan none = ConvPlan();
-  if (!first.wave || cdiv(N, 32) % first.tn != 0) return none;
+  if (cdiv(N, 32) % first.tn != 0) return none;
   return plan_conv_wave(M, N, Kpad, bf16, first.tn, first.nw);
 }
 
 template <bool BF16>
 static hipError_t launch_conv_t(const ConvPlan& pl, const ConvArgs& a, hipStream_t s, hipEvent_t t0, hipEvent_t t1) {
   if (t0) (void)hipEventRecord(t0, s);
-  if (pl.wave) {
+  {
     const int variant = pl.kernel - (BF16 ? K_CONVW_BF16_T1W2 : K_CONVW_F32_T1W2);
     const bool aligned = a.Cin % (BF16 ? 16 : 8) == 0;  // a K step never straddles a filter tap
 #define DARIS_WAVE_CASE(idx, TN_, NW_)                                                                            \
@@ -840,16 +623,6 @@ static hipError_t launch_conv_t(const ConvPlan& pl, const ConvArgs& a, hipStream
       default: return hipErrorInvalidValue;
     }
 #undef DARIS_WAVE_CASE
-  } else {
-  const int variant = pl.kernel - (BF16 ? K_CONV_BF16_128x64 : K_CONV_F32_128x64);
-  switch (variant) {
-    case 0: hipLaunchKernelGGL((conv_igemm_kernel<BF16, 128, 64, 64, 32, 4>), pl.grid, dim3(256), 0, s, a); break;
-    case 1: hipLaunchKernelGGL((conv_igemm_kernel<BF16, 64, 64, 32, 32, 4>), pl.grid, dim3(256), 0, s, a); break;
-    case 2: hipLaunchKernelGGL((conv_igemm_kernel<BF16, 64, 32, 32, 32, 4>), pl.grid, dim3(128), 0, s, a); break;
-    case 3: hipLaunchKernelGGL((conv_igemm_kernel<BF16, 32, 64, 32, 32, 4>), pl.grid, dim3(128), 0, s, a); break;
-    case 4: hipLaunchKernelGGL((conv_igemm_kernel<BF16, 32, 32, 32, 32, 4>), pl.grid, dim3(64), 0, s, a); break;
-    default: return hipErrorInvalidValue;
-  }
   }
   hipError_t e = hipGetLastError();
   if (t1) (void)hipEventRecord(t1, s);
@@ -868,7 +641,7 @@ static hipError_t launch_conv_pair_t(const ConvPlan& pl0, const ConvArgs& a0, co
                                      hipEvent_t t0, hipEvent_t t1) {
   const int ks = BF16 ? 16 : 8;
   const bool aligned = a0.Cin % ks == 0;
-  if (!pl0.wave || !pl1.wave || pl0.kernel != pl1.kernel || aligned != (a1.Cin % ks == 0) || pl1.splitk != 1)
+  if (pl0.kernel != pl1.kernel || aligned != (a1.Cin % ks == 0) || pl1.splitk != 1)
     return hipErrorInvalidValue;
   const int n0 = (int)(pl0.grid.x + 7) / 8 * 8;
   const dim3 grid(n0 + pl1.grid.x, 1, 1);

@@ -117,7 +117,7 @@ std::string build_plan(const daris_dnn& dnn, bool keep_activations, NetPlan* out
     LayerPlan& A = net.layers[l];
     LayerPlan& B = net.layers[l + 1];
     if (A.d.op != DARIS_OP_CONV || B.d.op != DARIS_OP_CONV || A.depthwise || B.depthwise) continue;
-    if (A.in_t != B.in_t || B.res_t == l + 1 || !A.cp.wave || !B.cp.wave) continue;
+    if (A.in_t != B.in_t || B.res_t == l + 1) continue;
     LayerPlan& heavy = A.macs > B.macs ? A : B;
     LayerPlan& light = A.macs > B.macs ? B : A;
     const ConvPlan like = plan_conv_like(heavy.cp, light.out.H * light.out.W, light.out.Cs, light.Kpad, net.bf16);
@@ -235,29 +235,20 @@ void pack_conv(const NetPlan& net, const LayerPlan& L, const float* w, const flo
       for (int t = 0; t < kk; ++t) put<float>(wp, (size_t)t * in.Cs + c, w[(size_t)c * kk + t], bf);
     return;
   }
-  if (L.cp.wave) {
-    // wave-tile family: [channel block of 32][step][lane = i + 32 h][VEC], element e of lane (i, h) at step s is
-    // W[n = 32 nb + i][k = s*KS + h*VEC + e], k = tap * Cs_in + ci; blocks padded to a multiple of TN, zeros elsewhere
-    const int vec = bf ? 8 : 4, ks = 2 * vec, S = L.cp.S;
-    const int nblocks = (L.out.Cs + 31) / 32;
-    const int nb_alloc = (nblocks + L.cp.tn - 1) / L.cp.tn * L.cp.tn;
-    wp->assign((size_t)nb_alloc * S * 64 * 16 + 8 * 1024, 0);  // + slack for the kernel's pipeline refills past the last step
-    for (int o = 0; o < d.c_out; ++o)
-      for (int ci = 0; ci < d.c_in; ++ci)
-        for (int t = 0; t < kk; ++t) {
-          const int k = t * in.Cs + ci;
-          const int st = k / ks, h = (k % ks) / vec, e = k % vec;
-          const size_t lane = (size_t)(o % 32) + 32 * h;
-          put<float>(wp, (((size_t)(o / 32) * S + st) * 64 + lane) * vec + e, w[((size_t)o * d.c_in + ci) * kk + t], bf);
-        }
-    return;
-  }
-  // LDS-tiled family: [Cs_out][Kpad], k = tap * Cs_in + ci
-  wp->assign((size_t)L.out.Cs * L.Kpad * es, 0);
+  // [channel block of 32][step][lane = i + 32 h][VEC], element e of lane (i, h) at step s is
+  // W[n = 32 nb + i][k = s*KS + h*VEC + e], k = tap * Cs_in + ci; blocks padded to a multiple of TN, zeros elsewhere
+  const int vec = bf ? 8 : 4, ks = 2 * vec, S = L.cp.S;
+  const int nblocks = (L.out.Cs + 31) / 32;
+  const int nb_alloc = (nblocks + L.cp.tn - 1) / L.cp.tn * L.cp.tn;
+  wp->assign((size_t)nb_alloc * S * 64 * 16 + 8 * 1024, 0);  // + slack for the kernel's pipeline refills past the last step
   for (int o = 0; o < d.c_out; ++o)
     for (int ci = 0; ci < d.c_in; ++ci)
-      for (int t = 0; t < kk; ++t)
-        put<float>(wp, (size_t)o * L.Kpad + (size_t)t * in.Cs + ci, w[((size_t)o * d.c_in + ci) * kk + t], bf);
+      for (int t = 0; t < kk; ++t) {
+        const int k = t * in.Cs + ci;
+        const int st = k / ks, h = (k % ks) / vec, e = k % vec;
+        const size_t lane = (size_t)(o % 32) + 32 * h;
+        put<float>(wp, (((size_t)(o / 32) * S + st) * 64 + lane) * vec + e, w[((size_t)o * d.c_in + ci) * kk + t], bf);
+      }
 }
 
 void pack_fc(const NetPlan& net, const LayerPlan& L, const float* w, const float* b, std::vector<unsigned char>* wp,

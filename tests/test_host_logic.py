@@ -141,11 +141,9 @@ def _check_plan(pl, name):
     """What the kernels and their grids assume about a dense convolution's launch plan."""
     M, N, S = pl["M"], pl["N"], pl["S"]
     z = pl["splitk"]
-    assert pl["grid_z"] == (1 if pl["wave"] else z) and pl["grid_x"] >= 1, name
+    assert pl["wave"] == 1 and pl["grid_y"] == 1 and pl["grid_z"] == 1 and pl["grid_x"] >= 1, name
     if z > 1:
         assert pl["ws_bytes"] >= z * M * N * 4, name                       # one fp32 partial tile set per K slice
-    if not pl["wave"]:
-        return
     tn, nw = pl["tn"], pl["nw"]
     assert tn in (1, 2) and nw in (2, 4, 8) and pl["threads"] == 64 * nw, name
     assert D.daris_kernel_name(pl["kernel_id"]).endswith(f"t{tn}w{nw}"), name
@@ -186,7 +184,7 @@ def test_launch_plans_satisfy_kernel_assumptions(net, dtype):
             assert abs(pl["pair_with"] - l) == 1 and o["pair_with"] == l and pl["pair_lead"] != o["pair_lead"]
             assert pl["pair_lead"] == (pl["pair_with"] < l)                    # issued at the later layer
             assert layers[l].in_from == layers[pl["pair_with"]].in_from       # both read the same tensor
-            assert o["kernel_id"] == pl["kernel_id"] and o["wave"] and pl["wave"]
+            assert o["kernel_id"] == pl["kernel_id"]
             light = pl if wl.net_macs(layers, shp)[l] < wl.net_macs(layers, shp)[pl["pair_with"]] else o
             assert light["splitk"] == 1                                        # the second problem never splits K across workgroups
             n_pairs += 1
