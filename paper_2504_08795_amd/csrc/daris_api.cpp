@@ -144,7 +144,7 @@ int64_t now_ns() {
 
 // ---- stage execution ----------------------------------------------------------------------------------------------
 
-ConvArgs conv_args(TaskRt& T, int l, void* y) {
+ConvArgs conv_args(TaskRt& T, int l, void* y, const void* net_input = nullptr) {
   NetPlan& net = T.net;
   LayerPlan& L = net.layers[l];
   const TensorInfo& in = net.tensor(L.in_t);
@@ -157,10 +157,15 @@ ConvArgs conv_args(TaskRt& T, int l, void* y) {
   a.splitk = L.cp.splitk; a.S = L.cp.S; a.sz = L.cp.sz; a.sw = L.cp.sw;
   a.MT = L.cp.MT; a.NTn = L.cp.NTn; a.G = L.cp.G; a.xmode = L.cp.xmode;
   a.mg_wo = div_magic((uint32_t)a.Wo); a.mg_cin = div_magic((uint32_t)a.Cin); a.mg_kw = div_magic((uint32_t)a.kw);
+  a.c_real = 0;
+  if (l == 0 && net.fuse_ingest) {  // layer 0 gathers from the caller's fp32 [C][H][W] buffer
+    a.x = net_input;
+    a.c_real = net.in_c;
+  }
   return a;
 }
 
-hipError_t launch_layer(TaskRt& T, int l, void* d_logits, hipStream_t s, bool sample = false) {
+hipError_t launch_layer(TaskRt& T, int l, const void* net_input, void* d_logits, hipStream_t s, bool sample = false) {
   // Diagnostic: DARIS_HOST_LAUNCH_DELAY_US=n makes the host spin n microseconds before every launch, which
   // reproduces the regime a tracing profiler puts the run in (host-bound launches, kernels starting on an idle GPU).
   static const int delay_us = getenv("DARIS_HOST_LAUNCH_DELAY_US") ? atoi(getenv("DARIS_HOST_LAUNCH_DELAY_US")) : 0;
@@ -184,7 +189,8 @@ hipError_t launch_layer(TaskRt& T, int l, void* d_logits, hipStream_t s, bool sa
         return launch_dwconv(a, net.bf16, s);
       } else {
         if (L.pair_with >= 0 && !L.pair_lead) return hipSuccess;  // issued together with the next layer
-        const ConvArgs a = conv_args(T, l, y);
+        if (l == 0 && net.fuse_ingest && !net_input) return hipErrorInvalidValue;
+        const ConvArgs a = conv_args(T, l, y, net_input);
         hipEvent_t t0 = nullptr, t1 = nullptr;
         double flops = 2.0 * (double)L.macs;
         if (L.pair_with >= 0) flops += 2.0 * (double)net.layers[L.pair_with].macs;
@@ -228,13 +234,13 @@ hipError_t launch_stage(TaskRt& T, int stage, const JobIo& io, hipStream_t s, bo
   const int first = net.stage_first[stage];
   const int end = stage + 1 < (int)net.stage_first.size() ? net.stage_first[stage + 1] : n;
   hipError_t e;
-  if (stage == 0) {
+  if (stage == 0 && !net.fuse_ingest) {
     e = launch_ingest((const float*)io.in, T.slots[net.ingest.slot], net.ingest.C, net.ingest.Cs, net.ingest.H, net.ingest.W,
                       net.bf16, s);
     if (e != hipSuccess) return e;
   }
   for (int l = first; l < end; ++l) {
-    e = launch_layer(T, l, io.out, s, sample);
+    e = launch_layer(T, l, io.in, io.out, s, sample);
     if (e != hipSuccess) return e;
   }
   if (end == n && !net.final_direct) {
@@ -982,14 +988,23 @@ daris_status daris_profile_layers(daris_task t, daris_part p, int reps, float* m
   const int n = (int)T.net.layers.size();
   float* scratch_out = nullptr;
   HIP_TRY(hipMalloc((void**)&scratch_out, (size_t)std::max(T.net.n_out, 4) * sizeof(float)));
+  float* scratch_in = nullptr;  // stands in for the caller's input where layer 0 reads it directly
+  const size_t in_bytes = (size_t)T.net.in_c * T.net.in_h * T.net.in_w * sizeof(float);
+  hipError_t ea = hipMalloc((void**)&scratch_in, in_bytes);
+  if (ea == hipSuccess) ea = hipMemset(scratch_in, 0, in_bytes);
+  if (ea != hipSuccess) {
+    (void)hipFree(scratch_out);
+    if (scratch_in) (void)hipFree(scratch_in);
+    return fail(DARIS_ENOMEM, "profile buffers: %s", hipGetErrorString(ea));
+  }
   hipEvent_t e0, e1;
   HIP_TRY(hipEventCreate(&e0));
   HIP_TRY(hipEventCreate(&e1));
   daris_status result = DARIS_OK;
   for (int l = 0; l < n && result == DARIS_OK; ++l) {
-    hipError_t e = launch_layer(T, l, scratch_out, s);  // warm-up
+    hipError_t e = launch_layer(T, l, scratch_in, scratch_out, s);  // warm-up
     if (e == hipSuccess) e = hipEventRecord(e0, s);
-    for (int r = 0; r < reps && e == hipSuccess; ++r) e = launch_layer(T, l, scratch_out, s);
+    for (int r = 0; r < reps && e == hipSuccess; ++r) e = launch_layer(T, l, scratch_in, scratch_out, s);
     if (e == hipSuccess) e = hipEventRecord(e1, s);
     if (e == hipSuccess) e = hipEventSynchronize(e1);
     float ms = 0.f;
@@ -1002,6 +1017,7 @@ daris_status daris_profile_layers(daris_task t, daris_part p, int reps, float* m
   (void)hipEventDestroy(e0);
   (void)hipEventDestroy(e1);
   (void)hipFree(scratch_out);
+  (void)hipFree(scratch_in);
   return result;
 }
 

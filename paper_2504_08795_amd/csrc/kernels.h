@@ -20,7 +20,7 @@ enum KernelId : int32_t {
 const char* kernel_name(int32_t id);
 
 struct ConvArgs {
-  const void* x;      // [H][W][Cin]
+  const void* x;      // [H][W][Cin]; with c_real > 0: the network input as the caller gives it, float [c_real][H][W]
   const void* w;      // packed weights in MFMA fragment order (see pack_conv)
   const float* bias;  // [Cout]
   const void* res;    // [Ho*Wo][Cout] or nullptr
@@ -34,6 +34,7 @@ struct ConvArgs {
   int S, sz, sw;  // K steps in total, per K slice of a workgroup, per wave
   uint32_t mg_wo, mg_cin, mg_kw;  // multipliers for division by Wo, Cin, kw (see div_magic)
   int MT, NTn, G, xmode;  // pixel tiles, channel tiles, weight groups (= NTn * splitk), XCD mapping mode
+  int c_real;             // > 0: layer 0 reads the fp32 [C][H][W] network input directly (Cin == one 16-byte vector, c_real <= 4)
   int wave_prio;          // 1: the waves raise their issue priority (stages of high-priority tasks on shared CUs)
 };
 

@@ -127,8 +127,9 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 // wave order.  With grid.z > 1 the workgroups of one tile also split K and write partial sums to the workspace,
 // which splitk_reduce_kernel adds in z order (a device-wide fence per workgroup for an in-kernel reduction was
 // measured to cost several times the extra launch).
-template <bool BF16, int TN, int NW, bool ALIGNED>
+template <bool BF16, int TN, int NW, int MODE>
 __device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L) {
+  constexpr bool ALIGNED = MODE == 0;   // 0: Cin a multiple of KS; 1: any Cin; 2: the network input itself, fp32 [C][H][W]
   constexpr int ES = BF16 ? 2 : 4;
   constexpr int VEC = 16 / ES;
   constexpr int KS = 2 * VEC;
@@ -195,13 +196,20 @@ __device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L) {
     a_valid = a_ok && ky < p.kh && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
     ap = xb + ((size_t)(a_valid ? iy * p.W + ix : 0) * p.Cin + ci + lh * VEC) * ES;  // always a valid address
   };
+  // MODE 2 reads the caller's fp32 [C][H][W] input directly (no separate layout conversion launch): the padded channel
+  // count equals VEC, so a lane's vector is one filter tap, gathered as four scalar loads from the channel planes.
+  // Planes beyond the real channel count repeat the last real one; their weights are zero.
+  const size_t plane = (size_t)p.H * p.W;
+  const size_t po1 = (size_t)min(1, p.c_real - 1) * plane, po2 = (size_t)min(2, p.c_real - 1) * plane,
+               po3 = (size_t)min(3, p.c_real - 1) * plane;
   auto locate = [&]() {  // !ALIGNED: this lane's vector of step kcur
     const int k = kcur + lh * VEC;
-    const int t = fast_div(k, p.mg_cin), c = k - t * p.Cin;
+    const int t = MODE == 2 ? k / VEC : fast_div(k, p.mg_cin), c = k - t * p.Cin;
     const int y = fast_div(t, p.mg_kw), x = t - y * p.kw;
     const int iy = iy0 + y, ix = ix0 + x;
     a_valid = a_ok && y < p.kh && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
-    ap = xb + ((size_t)(a_valid ? iy * p.W + ix : 0) * p.Cin + c) * ES;
+    if (MODE == 2) ap = xb + (size_t)(a_valid ? iy * p.W + ix : 0) * 4;
+    else ap = xb + ((size_t)(a_valid ? iy * p.W + ix : 0) * p.Cin + c) * ES;
   };
   if (ALIGNED) enter_tap();
   const unsigned char* wptr[TN];
@@ -214,7 +222,15 @@ __device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L) {
                // result is not touched (and not waited for) until D-1 later steps have been issued
   auto load = [&](int d) {
     if (!ALIGNED) locate();
-    ar[d] = *(const uint4*)ap;
+    if (MODE == 2) {
+      const float* q = (const float*)ap;
+      ar[d].x = __float_as_uint(q[0]);
+      ar[d].y = __float_as_uint(q[po1]);
+      ar[d].z = __float_as_uint(q[po2]);
+      ar[d].w = __float_as_uint(q[po3]);
+    } else {
+      ar[d] = *(const uint4*)ap;
+    }
     av[d] = a_valid;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
@@ -254,7 +270,13 @@ __device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L) {
     for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
 
   auto compute = [&](int d) {
-    const uint4 a4 = keep_if(av[d], ar[d]);
+    uint4 a4 = keep_if(av[d], ar[d]);
+    if (MODE == 2 && BF16) {  // four fp32 channels -> the 8-channel bf16 vector of the tap (same rounding as the conversion kernel)
+      a4.x = f32_to_bf16_bits(__uint_as_float(a4.x)) | (f32_to_bf16_bits(__uint_as_float(a4.y)) << 16);
+      a4.y = f32_to_bf16_bits(__uint_as_float(a4.z)) | (f32_to_bf16_bits(__uint_as_float(a4.w)) << 16);
+      a4.z = 0u;
+      a4.w = 0u;
+    }
     if (BF16) {
 #pragma unroll
       for (int j = 0; j < TN; ++j)
@@ -355,19 +377,19 @@ __device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L) {
   }
 }
 
-template <bool BF16, int TN, int NW, bool ALIGNED>
+template <bool BF16, int TN, int NW, int MODE>
 __global__ __launch_bounds__(NW * 64) void conv_wave_kernel(const ConvArgs p) {
-  conv_wave_body<BF16, TN, NW, ALIGNED>(p, (int)blockIdx.x);
+  conv_wave_body<BF16, TN, NW, MODE>(p, (int)blockIdx.x);
 }
 
 // Two independent convolutions of the same kernel variant in one launch (a residual block's first convolution and
 // the 1x1 convolution of its shortcut read the same tensor): workgroups [0, n0) work on p0, the rest on p1.  n0 is
 // a multiple of 8, so the workgroup -> XCD relation of each problem is the one its plan assumed.
-template <bool BF16, int TN, int NW, bool ALIGNED>
+template <bool BF16, int TN, int NW, int MODE>
 __global__ __launch_bounds__(NW * 64) void conv_wave_pair_kernel(const ConvArgs p0, const ConvArgs p1, const int n0) {
   const int L = (int)blockIdx.x;
-  if (L < n0) conv_wave_body<BF16, TN, NW, ALIGNED>(p0, L);
-  else conv_wave_body<BF16, TN, NW, ALIGNED>(p1, L - n0);
+  if (L < n0) conv_wave_body<BF16, TN, NW, MODE>(p0, L);
+  else conv_wave_body<BF16, TN, NW, MODE>(p1, L - n0);
 }
 
 // ---- depthwise convolution: memory bound, one thread per (output pixel, 16-byte channel vector) -----------------------
@@ -607,11 +629,14 @@ static hipError_t launch_conv_t(const ConvPlan& pl, const ConvArgs& a, hipStream
   if (t0) (void)hipEventRecord(t0, s);
   {
     const int variant = pl.kernel - (BF16 ? K_CONVW_BF16_T1W2 : K_CONVW_F32_T1W2);
-    const bool aligned = a.Cin % (BF16 ? 16 : 8) == 0;  // a K step never straddles a filter tap
+    // 0: a K step never straddles a filter tap; 1: general walk; 2: layer 0 reading the caller's fp32 [C][H][W] input
+    const int mode = a.c_real > 0 ? 2 : (a.Cin % (BF16 ? 16 : 8) == 0 ? 0 : 1);
+    if (mode == 2 && (a.Cin != (BF16 ? 8 : 4) || a.c_real > 4)) return hipErrorInvalidValue;
 #define DARIS_WAVE_CASE(idx, TN_, NW_)                                                                            \
   case idx:                                                                                                       \
-    if (aligned) hipLaunchKernelGGL((conv_wave_kernel<BF16, TN_, NW_, true>), pl.grid, dim3(NW_ * 64), 0, s, a);    \
-    else hipLaunchKernelGGL((conv_wave_kernel<BF16, TN_, NW_, false>), pl.grid, dim3(NW_ * 64), 0, s, a);           \
+    if (mode == 0) hipLaunchKernelGGL((conv_wave_kernel<BF16, TN_, NW_, 0>), pl.grid, dim3(NW_ * 64), 0, s, a);     \
+    else if (mode == 1) hipLaunchKernelGGL((conv_wave_kernel<BF16, TN_, NW_, 1>), pl.grid, dim3(NW_ * 64), 0, s, a); \
+    else hipLaunchKernelGGL((conv_wave_kernel<BF16, TN_, NW_, 2>), pl.grid, dim3(NW_ * 64), 0, s, a);               \
     break;
     switch (variant) {
       DARIS_WAVE_CASE(0, 1, 2)
@@ -641,7 +666,7 @@ static hipError_t launch_conv_pair_t(const ConvPlan& pl0, const ConvArgs& a0, co
                                      hipEvent_t t0, hipEvent_t t1) {
   const int ks = BF16 ? 16 : 8;
   const bool aligned = a0.Cin % ks == 0;
-  if (pl0.kernel != pl1.kernel || aligned != (a1.Cin % ks == 0) || pl1.splitk != 1)
+  if (pl0.kernel != pl1.kernel || aligned != (a1.Cin % ks == 0) || pl1.splitk != 1 || a0.c_real > 0 || a1.c_real > 0)
     return hipErrorInvalidValue;
   const int n0 = (int)(pl0.grid.x + 7) / 8 * 8;
   const dim3 grid(n0 + pl1.grid.x, 1, 1);
@@ -649,8 +674,8 @@ static hipError_t launch_conv_pair_t(const ConvPlan& pl0, const ConvArgs& a0, co
   if (t0) (void)hipEventRecord(t0, s);
 #define DARIS_PAIR_CASE(idx, TN_, NW_)                                                                                     \
   case idx:                                                                                                                \
-    if (aligned) hipLaunchKernelGGL((conv_wave_pair_kernel<BF16, TN_, NW_, true>), grid, dim3(NW_ * 64), 0, s, a0, a1, n0); \
-    else hipLaunchKernelGGL((conv_wave_pair_kernel<BF16, TN_, NW_, false>), grid, dim3(NW_ * 64), 0, s, a0, a1, n0);        \
+    if (aligned) hipLaunchKernelGGL((conv_wave_pair_kernel<BF16, TN_, NW_, 0>), grid, dim3(NW_ * 64), 0, s, a0, a1, n0); \
+    else hipLaunchKernelGGL((conv_wave_pair_kernel<BF16, TN_, NW_, 1>), grid, dim3(NW_ * 64), 0, s, a0, a1, n0);        \
     break;
   switch (variant) {
     DARIS_PAIR_CASE(0, 1, 2)

@@ -129,6 +129,16 @@ std::string build_plan(const daris_dnn& dnn, bool keep_activations, NetPlan* out
     B.pair_lead = true;
     ++l;
   }
+  // Layer 0 can gather straight from the caller's input when that is its only reader and one filter tap is exactly
+  // one 16-byte vector of the padded layout (1..4 real channels).
+  {
+    const LayerPlan& L0 = net.layers[0];
+    bool only_reader = true;
+    for (int l = 1; l < n; ++l)
+      if (net.layers[l].in_t == 0 || net.layers[l].res_t == 0) only_reader = false;
+    net.fuse_ingest = !keep_activations && !getenv("DARIS_NO_FUSED_INGEST") && L0.d.op == DARIS_OP_CONV && !L0.depthwise &&
+                      L0.in_t == 0 && L0.res_t < 0 && L0.pair_with < 0 && only_reader && net.ingest.Cs == vec && dnn.in_c <= 4;
+  }
   const TensorInfo& fin = net.layers[n - 1].out;
   net.n_out = fin.C * fin.H * fin.W;
   net.final_direct = net.layers[n - 1].d.op == DARIS_OP_FC;

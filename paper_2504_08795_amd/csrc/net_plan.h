@@ -44,6 +44,7 @@ struct NetPlan {
   std::vector<int> stage_first;   // first layer of each stage (size = number of stages)
   int n_out = 0;                  // elements of the final output (C*H*W)
   bool final_direct = false;      // last layer is an FC writing fp32 logits itself
+  bool fuse_ingest = false;       // layer 0 reads the caller's fp32 [C][H][W] input itself: no layout conversion launch
 
   const TensorInfo& tensor(int t) const { return t == 0 ? ingest : layers[t - 1].out; }
 };
