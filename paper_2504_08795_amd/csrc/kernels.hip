@@ -1,8 +1,10 @@
-// HIP kernels of the DNN stages for gfx950 (CDNA4): implicit-GEMM convolution on MFMA with LDS-staged tiles
+// HIP kernels of the DNN stages for gfx950 (CDNA4): implicit-GEMM convolution on MFMA with register-fed wave tiles
 // and a fused bias / residual / activation epilogue, split-K reduction, depthwise convolution, pooling, FC
 // (batch-1 GEMV), and the NCHW<->NHWC boundary conversions.  A DNN is, for the scheduler of the paper
 // (Sec. I, Sec. III-B1), a sequence of such kernels cut into stages.
 #include "kernels.h"
+
+#include <type_traits>
 
 #include <cstdlib>
 #include <cstring>
@@ -263,6 +265,24 @@ __device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L) {
     bias_j[j] = (n < p.Cout) ? *(const float4*)(p.bias + n) : make_float4(0.f, 0.f, 0.f, 0.f);
   }
 
+  // The residual operand of this thread's quads is fetched here as well (when this launch applies the epilogue itself).
+  constexpr int QUADS = TILE / 4;
+  constexpr int RQ = (QUADS + NT - 1) / NT;  // quads per thread
+  using ResVec = typename std::conditional<BF16, uint2, uint4>::type;
+  ResVec res_pre[RQ];
+  const bool own_epilogue = p.splitk == 1;
+  const bool use_res = own_epilogue && p.res != nullptr;
+#pragma unroll
+  for (int r = 0; r < RQ; ++r) {
+    res_pre[r] = ResVec();
+    const int e = 4 * (tid + r * NT);
+    const int j = e >> 10, v = (e >> 6) & 15, l = e & 63;
+    const int mm = m0 + (v >> 2) * 8 + (l >> 5) * 4 + (v & 3);
+    const int n = (nb0 + j) * 32 + (l & 31);
+    if (use_res && (QUADS % NT == 0 || e < TILE) && mm < p.M && n < p.Cout)
+      res_pre[r] = *(const ResVec*)((const unsigned char*)p.res + ((size_t)mm * p.Cout + n) * ES);
+  }
+
   f32x16 acc[TN];
 #pragma unroll
   for (int j = 0; j < TN; ++j)
@@ -325,9 +345,8 @@ __device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L) {
     for (int v = 0; v < 16; ++v) red[wave * TILE + (j * 16 + v) * 64 + lane] = acc[j][v];
   __syncthreads();
   // --- epilogue per channel quad: pixel m0 + 8*(v/4) + 4*(lane/32) + v%4, channels 32*(nb0+j) + lane%32 .. +3 ---------
-  constexpr int QUADS = TILE / 4;
 #pragma unroll
-  for (int r = 0; r < (QUADS + NT - 1) / NT; ++r) {
+  for (int r = 0; r < RQ; ++r) {
     const int q = tid + r * NT;
     if (QUADS % NT != 0 && q >= QUADS) break;
     const int e = 4 * q;
@@ -342,7 +361,7 @@ __device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L) {
     const int n = (nb0 + j) * 32 + (l & 31);
     if (mm < p.M && n < p.Cout) {
       const size_t o = (size_t)mm * p.Cout + n;
-      if (p.splitk > 1) {  // partial sums of this K slice; splitk_reduce_kernel finishes the layer
+      if (!own_epilogue) {  // partial sums of this K slice; splitk_reduce_kernel finishes the layer
         *(float4*)(p.ws + (size_t)zi * p.M * p.Cout + o) = sum;
       } else {
         float4 b = bias_j[0];  // component-wise select: indexing the array with a run-time j would move it out of registers
@@ -352,14 +371,14 @@ __device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L) {
           b.z = hi ? bias_j[TN - 1].z : b.z; b.w = hi ? bias_j[TN - 1].w : b.w;
         }
         float val[4] = {sum.x + b.x, sum.y + b.y, sum.z + b.z, sum.w + b.w};
-        if (p.res) {
-          if (BF16) {
-            const uint2 rv = *(const uint2*)((const uint16_t*)p.res + o);
+        if (use_res) {
+          const ResVec rv = res_pre[r];
+          if constexpr (BF16) {
             val[0] += __uint_as_float(rv.x << 16); val[1] += __uint_as_float(rv.x & 0xffff0000u);
             val[2] += __uint_as_float(rv.y << 16); val[3] += __uint_as_float(rv.y & 0xffff0000u);
           } else {
-            const float4 rv = *(const float4*)((const float*)p.res + o);
-            val[0] += rv.x; val[1] += rv.y; val[2] += rv.z; val[3] += rv.w;
+            val[0] += __uint_as_float(rv.x); val[1] += __uint_as_float(rv.y);
+            val[2] += __uint_as_float(rv.z); val[3] += __uint_as_float(rv.w);
           }
         }
 #pragma unroll
