@@ -129,6 +129,57 @@ def run_saturated(g: GpuTaskSet, total_jobs, driver_profile=False):
     return res
 
 
+PEAK_TFLOPS = {"fp32": 157.3, "bf16": 2500.0}   # MI355X dense MFMA peaks
+PEAK_HBM_GBS = 8000.0
+
+
+def layer_profile(net, dtype, n_cu, reps=50):
+    """Every layer of one DNN alone on an n_cu partition: kernel, time, and its roofline.  Algorithmic bytes of a layer =
+    its weights and biases once + its input tensor(s) read once + its output written once (element size of the
+    task); algorithmic FLOPs = 2 x MACs.  t_roof = max(FLOPs / MFMA peak of the dtype, bytes / HBM peak), whole chip."""
+    import torch
+    import workloads as wl
+    layers, shp = wl.build_net(net)
+    weights = wl.make_weights(layers, 1)
+    es = 4 if dtype == "fp32" else 2
+    D.daris_init(0, 0, 0)
+    try:
+        p = D.daris_create_partition(n_cu)
+        dnn, keep = D.make_dnn(layers, weights, shp, dtype)
+        t = D.daris_register_task(dnn, 10**7, 10**7, 0)
+        x = torch.from_numpy(wl.make_inputs(shp, 1, 1, "normal")[0]).cuda()
+        y = torch.zeros(layers[-1].c_out, device="cuda")
+        D.daris_forward(t, x, y, p)
+        ms, kid, fl = D.daris_profile_layers(t, p, reps, len(layers))
+        plans = [D.daris_get_launch_plan(t, l) for l in range(len(layers))]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(200):
+            D.daris_forward(t, x, y, p)
+        latency_us = (time.perf_counter() - t0) / 200 * 1e6
+    finally:
+        D.daris_shutdown()
+    shapes = wl.layer_shapes(layers, shp)
+    rows = []
+    for l, L in enumerate(layers):
+        c, h, w = shapes[l]
+        ci, hi, wi = shp if L.in_from < 0 else shapes[L.in_from]
+        w_elems = 0 if weights[l][0] is None else weights[l][0].size
+        by = w_elems * es + (0 if weights[l][1] is None else weights[l][1].size * 4) + ci * hi * wi * es + c * h * w * es
+        if L.res_from >= 0:
+            by += c * h * w * es
+        us = float(ms[l]) * 1e3
+        t_roof = max(fl[l] / (PEAK_TFLOPS[dtype] * 1e12), by / (PEAK_HBM_GBS * 1e9)) * 1e6
+        rows.append(dict(layer=l, name=L.name, kernel=D.daris_kernel_name(kid[l]), M=h * w, N=c, us=round(us, 2),
+                         gflop=round(fl[l] / 1e9, 4), mbytes=round(by / 1e6, 3),
+                         tflops=round(fl[l] / us / 1e6, 2) if us > 0.2 else None, gbs=round(by / us / 1e3, 1) if us > 0.2 else None,
+                         bound="mfma" if fl[l] / (PEAK_TFLOPS[dtype] * 1e12) > by / (PEAK_HBM_GBS * 1e9) else "hbm",
+                         t_roof_us=round(t_roof, 3), frac=round(t_roof / us, 4) if us > 0.2 else None,
+                         joint_launch_with=plans[l]["pair_with"] if plans[l]["pair_with"] >= 0 else None))
+    return dict(net=net, dtype=dtype, n_cu=n_cu, kernel_time_us=round(float(sum(r["us"] for r in rows)), 1), forward_latency_us=round(latency_us, 1),
+                t_roof_us=round(sum(r["t_roof_us"] for r in rows), 2), layers=rows)
+
+
 def main():
     import workloads as wl
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
@@ -149,7 +200,24 @@ def main():
     ap.add_argument("--task-jps", type=float, default=30.0, help="jobs per second released by every task of a --paper-set")
     ap.add_argument("--nc", type=int, default=6, help="--paper-set: number of partitions N_c")
     ap.add_argument("--os", default="2", help="--paper-set: oversubscription OS as a fraction, e.g. 3/2 (1 <= OS <= N_c)")
+    ap.add_argument("--layer-profile", default="", help="instead of a run: per-layer kernel times and rooflines of this DNN alone (e.g. resnet18)")
+    ap.add_argument("--dtype", default="fp32", help="--layer-profile: fp32 | bf16")
+    ap.add_argument("--ncu", type=int, default=128, help="--layer-profile: partition size")
+    ap.add_argument("--table", action="store_true", help="--layer-profile: markdown table instead of JSON")
     a = ap.parse_args()
+    if a.layer_profile:
+        r = layer_profile(a.layer_profile, a.dtype, a.ncu)
+        if not a.table:
+            print(json.dumps(r))
+            return
+        print(f"{r['net']} {r['dtype']} alone on {r['n_cu']} CUs: kernels {r['kernel_time_us']} us, forward latency {r['forward_latency_us']} us, "
+              f"sum of layer rooflines {r['t_roof_us']} us\n")
+        print("| # | layer | kernel | M | N | us | GFLOP | MB | TFLOP/s | GB/s | bound | t_roof us | frac |\n|---|---|---|---|---|---|---|---|---|---|---|---|---|")
+        for x in r["layers"]:
+            note = f" (launched with layer {x['joint_launch_with']})" if x["joint_launch_with"] is not None else ""
+            print(f"| {x['layer']} | {x['name']}{note} | {x['kernel']} | {x['M']} | {x['N']} | {x['us']} | {x['gflop']} | {x['mbytes']} | {x['tflops']} | {x['gbs']} | "
+                  f"{x['bound']} | {x['t_roof_us']} | {x['frac']} |")
+        return
     if a.paper_set:
         # Table II shape: N_c equal partitions of ceil_even(OS * 256 / N_c) CUs (Sec. III-C2), OS given as a fraction
         num, den = (int(v) for v in (a.os.split("/") + ["1"])[:2])
