@@ -85,6 +85,24 @@ def summarise(ts, before, after, wall_s):
     return out
 
 
+def response_percentiles(trace, priorities):
+    """Per-priority response times (ms) of the jobs that completed inside `trace` (list of record tuples): a job's
+    response = its JOB_DONE time - its nominal release (RELEASE time - the lateness stored in aux)."""
+    RELEASE, JOB_DONE = 1, 7
+    rel, resp = {}, {0: [], 1: []}
+    for seq, t, typ, level, stage, part, task, stream, job, aux in trace:
+        if typ == RELEASE:
+            rel[(task, job)] = t - aux
+        elif typ == JOB_DONE and (task, job) in rel:
+            resp[priorities[task]].append((t - rel.pop((task, job))) / 1e6)
+    out = {}
+    for name, prio in (("hp", 1), ("lp", 0)):
+        v = np.sort(np.asarray(resp[prio]))
+        out[name] = None if len(v) == 0 else dict(jobs=int(len(v)), min_ms=round(float(v[0]), 4), p50_ms=round(float(np.percentile(v, 50)), 4),
+                                                  p99_ms=round(float(np.percentile(v, 99)), 4), max_ms=round(float(v[-1]), 4))
+    return out
+
+
 def run_periodic(g: GpuTaskSet, n_jobs, migrate_every=0, seed=1):
     """Periodic releases at the nominal periods.  With migrate_every > 0 the run is cut into chunks and a seeded LP
     task is forced to a seeded other partition between chunks (one migration per `migrate_every` completed jobs)."""
@@ -236,6 +254,7 @@ def main():
         g.calibrate(loaded=a.loaded_afet)
         D.daris_commit()
         res = run_saturated(g, a.jobs * g.n_tasks, a.driver_profile) if a.saturated else run_periodic(g, a.jobs, a.migrate_every)
+        res["response_ms"] = response_percentiles(D.trace_read_all(), [t.priority for t in ts.tasks])
         res["config"] = dict(name=ts.name, partitions=ts.partitions, streams=a.streams, tasks=g.n_tasks, rate=a.rate, oversub=a.oversub,
                              stages=[t.n_stages for t in ts.tasks], flags=a.flags)
         print(json.dumps(res))

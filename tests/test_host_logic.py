@@ -258,6 +258,23 @@ def _oracle_and_library(ts, et, afet, flags=0, n_streams=None, migrations=()):
     return m, want, got, stats, dec
 
 
+def test_response_percentiles_agree_with_the_library_statistics():
+    """The harness derives per-job response times from the trace; their extremes and mean must be the library's."""
+    from paper_2504_08795_amd import harness
+    ts = wl.make_taskset(2, n_jobs=25)
+    et = wl.virtual_et_table(ts, load_scale=25.0)
+    afet = [[int(np.mean(et[i][j][0][:8])) for j in range(t.n_stages)] for i, t in enumerate(ts.tasks)]
+    m, want, got, stats, dec = _oracle_and_library(ts, et, afet)
+    prios = [t.priority for t in ts.tasks]
+    pct = harness.response_percentiles(got, prios)
+    for name, prio in (("hp", wl.HP), ("lp", wl.LP)):
+        sel = [s for s, p in zip(stats, prios) if p == prio and s["completed"] > 0]
+        assert pct[name]["jobs"] == sum(s["completed"] for s in sel)
+        assert pct[name]["min_ms"] == round(min(s["resp_min_ns"] for s in sel) / 1e6, 4)
+        assert pct[name]["max_ms"] == round(max(s["resp_max_ns"] for s in sel) / 1e6, 4)
+        assert pct[name]["min_ms"] <= pct[name]["p50_ms"] <= pct[name]["p99_ms"] <= pct[name]["max_ms"]
+
+
 @pytest.mark.parametrize("config,load,flags,ns", [
     (1, 300.0, 0, 1), (2, 25.0, 0, 1), (3, 18.0, 0, 1), (4, 22.0, 0, 1), (2, 30.0, 0, 2), (3, 14.0, D.NO_LAST, 1), (2, 25.0, D.NO_PRIOR, 1),
     (4, 22.0, D.NO_FIXED, 1), (2, 45.0, D.HP_ADMISSION, 1), (5, 12.0, 0, 1)])
