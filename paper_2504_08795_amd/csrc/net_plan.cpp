@@ -63,7 +63,7 @@ std::string build_plan(const daris_dnn& dnn, bool keep_activations, NetPlan* out
         L.macs = (int64_t)o.H * o.W * d.c_out * (d.c_in / d.groups) * d.k * d.k;
         if (!L.depthwise) {
           L.K = d.k * d.k * in.Cs;
-          L.Kpad = round_up(L.K, 32);
+          L.Kpad = round_up(L.K, 2 * vec);  // whole K steps of the convolution kernel (two 16-byte vectors per pixel)
           // the kernels divide pixel and k indices by Wo, Cin and kw with 32-bit multipliers: operands must stay small
           if ((uint64_t)(o.H * (uint64_t)o.W + 64) * (uint64_t)o.W >= (1ull << 32) || (uint64_t)(L.Kpad + 64) * (uint64_t)in.Cs >= (1ull << 32))
             return "layer " + std::to_string(l) + ": tensor too large for the kernels' index arithmetic";
