@@ -126,7 +126,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 // at registration in exactly this order ([channel block][step][lane][16 B]: one fully coalesced 1 KiB read per
 // step, consecutive steps consecutive in memory).  No barrier and no LDS in the K loop; D steps are in flight.
 // The NW waves of a workgroup split the K slice of the workgroup; their partial tiles are summed through LDS in
-// wave order.  With grid.z > 1 the workgroups of one tile also split K and write partial sums to the workspace,
+// wave order.  With splitk > 1 several workgroups share one tile, split K as well and write partial sums to the workspace,
 // which splitk_reduce_kernel adds in z order (a device-wide fence per workgroup for an in-kernel reduction was
 // measured to cost several times the extra launch).
 template <bool BF16, int TN, int NW, int MODE>
