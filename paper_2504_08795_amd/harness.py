@@ -219,7 +219,7 @@ def main():
     ap.add_argument("--nc", type=int, default=6, help="--paper-set: number of partitions N_c")
     ap.add_argument("--os", default="2", help="--paper-set: oversubscription OS as a fraction, e.g. 3/2 (1 <= OS <= N_c)")
     ap.add_argument("--layer-profile", default="", help="instead of a run: per-layer kernel times and rooflines of this DNN alone (e.g. resnet18)")
-    ap.add_argument("--dtype", default="fp32", help="--layer-profile: fp32 | bf16")
+    ap.add_argument("--dtype", default="fp32", help="--layer-profile and --paper-set: fp32 | bf16")
     ap.add_argument("--ncu", type=int, default=128, help="--layer-profile: partition size")
     ap.add_argument("--table", action="store_true", help="--layer-profile: markdown table instead of JSON")
     a = ap.parse_args()
@@ -240,7 +240,8 @@ def main():
         # Table II shape: N_c equal partitions of ceil_even(OS * 256 / N_c) CUs (Sec. III-C2), OS given as a fraction
         num, den = (int(v) for v in (a.os.split("/") + ["1"])[:2])
         n_cu = min(256, D.daris_cu_per_partition(num, den, 256, a.nc))
-        ts = wl.make_paper_taskset(a.paper_set, a.n_high, a.n_low, a.task_jps, [n_cu] * a.nc, n_jobs=a.jobs, n_stages=a.stages or 4)
+        ts = wl.make_paper_taskset(a.paper_set, a.n_high, a.n_low, a.task_jps, [n_cu] * a.nc, n_jobs=a.jobs, n_stages=a.stages or 4,
+                                   dtype=a.dtype)
     else:
         ts = wl.make_taskset(a.config, n_jobs=a.jobs, rate_scale=a.rate, oversub=a.oversub)
     if a.stages:
