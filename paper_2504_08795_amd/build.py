@@ -1,4 +1,5 @@
-"""Builds libdaris.so (HIP kernels + host runtime + C ABI) for gfx950 with hipcc, in-tree."""
+"""Builds libdaris.so for gfx950 with hipcc, in-tree: the device code object (every kernel of csrc/kernels.hip), linked
+into the library as data, and the host runtime that dispatches it (HSA queues) behind the C ABI."""
 import os
 import subprocess
 import sys
@@ -6,25 +7,46 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdaris.so")
-SOURCES = ["kernels.hip", "sched_core.cpp", "net_plan.cpp", "daris_api.cpp"]
-FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wall", "-Wno-unused-function",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+CODE_OBJECT = os.path.join(CSRC, "daris_kernels.co")
+HOST_SOURCES = ["aql.cpp", "launch.cpp", "sched_core.cpp", "net_plan.cpp", "daris_api.cpp"]
+COMMON = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-Wall", "-Wno-unused-function"]
+# no packed fp32 arithmetic in device code (some forms have given wrong results on this hardware)
+DEVICE_FLAGS = COMMON + ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "--cuda-device-only", "--no-gpu-bundle-output"]
+HOST_FLAGS = COMMON + ["-fPIC"]
+
+BLOB_ASM = """
+    .section .rodata
+    .global daris_kernels_co
+    .global daris_kernels_co_end
+    .balign 4096
+daris_kernels_co:
+    .incbin "{path}"
+daris_kernels_co_end:
+    .byte 0
+    .section .note.GNU-stack,"",@progbits
+"""
+
+
+def _run(cmd, verbose):
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
 
 
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    objs = []
-    for src in SOURCES:
+    _run([hipcc] + DEVICE_FLAGS + ["-c", os.path.join(CSRC, "kernels.hip"), "-o", CODE_OBJECT], verbose)
+    blob_s = os.path.join(CSRC, "kernels_blob.S.tmp.s")
+    with open(blob_s, "w") as f:
+        f.write(BLOB_ASM.format(path=CODE_OBJECT))
+    objs = [os.path.join(CSRC, "kernels_blob.o")]
+    _run(["gcc", "-c", blob_s, "-o", objs[0]], verbose)
+    os.remove(blob_s)
+    for src in HOST_SOURCES:
         obj = os.path.join(CSRC, src + ".o")
-        cmd = [hipcc] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
-        if verbose:
-            print(" ".join(cmd), flush=True)
-        subprocess.check_call(cmd)
+        _run([hipcc] + HOST_FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj], verbose)
         objs.append(obj)
-    cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs + ["-lpthread"]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
+    _run([hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs + ["-L/opt/rocm/lib", "-lhsa-runtime64", "-lpthread", "-ldl"], verbose)
     return LIB
 
 

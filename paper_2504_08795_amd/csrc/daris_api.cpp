@@ -1,6 +1,10 @@
-// C ABI of the library: global state, partitions as CU-masked HIP streams, task registration, and the two
+// C ABI of the library: global state, partitions as CU-masked hardware queues, task registration, and the two
 // drivers around the decision core -- a virtual-time event loop and the real-time driver (API thread + one worker
-// thread per stream) in which a stage boundary is a completion event observed by the host (Sec. III-B1).
+// thread per stream) in which a stage boundary is a completion signal observed by the host (Sec. III-B1).
+//
+// HIP serves for device memory and copies only.  Kernels are dispatched as AQL packets on the library's own queues
+// (aql.h); every layer's argument block is encoded when the task is registered and lives in device memory.
+#include <dlfcn.h>
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -20,11 +24,16 @@
 #include <vector>
 
 #include "../../include/daris.h"
+#include "aql.h"
 #include "kernels.h"
 #include "net_plan.h"
 #include "sched_core.h"
 
 using namespace daris;
+
+// the device code object (every kernel, built from kernels.hip), linked into the library as data
+extern "C" const char daris_kernels_co[];
+extern "C" const char daris_kernels_co_end[];
 
 namespace {
 
@@ -49,6 +58,22 @@ daris_status fail(daris_status code, const char* fmt, ...) {
 struct JobIo {
   const void* in = nullptr;
   void* out = nullptr;
+  // device-resident argument blocks of the two launches that touch these buffers, prepared ahead (I/O pools); nullptr:
+  // the block is patched at launch time and travels through the queue's host-coherent ring
+  const void* in_args = nullptr;
+  const void* out_args = nullptr;
+};
+
+struct LaunchRt {
+  KernelLaunch kl;
+  const void* dev = nullptr;  // the launch's argument block inside the task's device buffer
+  double flops = 0;           // arithmetic of the layer(s) a dense-convolution launch computes, else 0
+};
+
+// Argument blocks of the input-reading and the logits-writing launch, one per buffer of a set of I/O buffers.
+struct IoVariants {
+  char* dev = nullptr;
+  std::vector<const void*> in, out;
 };
 
 struct TaskRt {
@@ -62,24 +87,28 @@ struct TaskRt {
   void* pool_out = nullptr;
   int32_t n_inputs = 0, n_slots = 0;
   std::unordered_map<uint32_t, JobIo> io;  // per released job
-  hipEvent_t chain = nullptr;              // virtual-time mode: orders a task's stages across streams
+  // the whole network as launches in execution order, encoded at registration; layer l issues launches
+  // [layer_lo[l], layer_lo[l + 1]) (none for the earlier member of a launch pair)
+  std::vector<LaunchRt> launches;
+  std::vector<int> layer_lo;
+  int in_launch = -1, out_launch = -1;  // the launches that read the job's input / write its logits
+  uint32_t in_off = 0, out_off = 0;     // byte offset of that pointer inside the argument block
+  IoVariants pool;                      // argument blocks for the buffers of daris_task_set_io
   // virtual execution times: (stage, partition) -> (job_lo, values)
   std::map<std::pair<int, int>, std::pair<int64_t, std::vector<int64_t>>> vt;
   // library-driven runs
   int32_t closed_left = 0;
 };
 
-struct TimingPair {  // one sampled kernel launch: events recorded around it on its own stream
-  hipEvent_t e0 = nullptr, e1 = nullptr;
-  int32_t kernel = 0;
-  double flops = 0;
-};
-
-struct StreamRt {  // one CU-masked stream and, in real-time mode, the worker thread that feeds and watches it
-  hipStream_t s = nullptr;
-  hipEvent_t done = nullptr;      // boundary of a job's last stage: the logits become visible to the host
-  hipEvent_t done_mid = nullptr;  // boundary inside a job: completion only, no system-scope fence
-  hipEvent_t begin = nullptr, end = nullptr;  // driver profile only: timed markers around a stage
+struct StreamRt {  // one CU-masked queue and, in real-time mode, the worker thread that feeds and watches it
+  AqlQueue q;
+  std::mutex qmu;                  // one producer at a time (the worker; direct calls of the API thread)
+  hsa_signal_t done{0};            // completion of the last launch of a stage
+  hsa_signal_t begin{0};           // driver profile: completion of a stage's first launch (its start time stamp)
+  std::vector<hsa_signal_t> tsig;  // kernel timing: one signal per launch of a sampled stage
+  // what enqueue_stage left for finish_stage
+  int pend_lo = 0, pend_hi = 0;
+  bool pend_sample = false, pend_prof = false;
   std::thread thr;
   std::condition_variable cv;
   std::atomic<bool> has_work{false};  // a stage handed over by a dispatch pass, not yet picked up by the worker
@@ -129,9 +158,10 @@ struct Global {
   std::chrono::steady_clock::time_point epoch;
   std::string async_error;
   int tm_every = 0;                 // kernel timing: sample every n-th job of a task, 0 = off
-  std::vector<TimingPair> tm_pairs;
-  std::atomic<size_t> tm_used{0};
-  double tm_overhead_ms = 0;        // what an empty event pair reports on a partition stream
+  int64_t tm_left = 0;              // samples still to take
+  int64_t tm_launches[K_COUNT] = {0};
+  double tm_ms[K_COUNT] = {0}, tm_flops[K_COUNT] = {0};
+  hsa_signal_t util_sig{0};         // completion signal of the API thread's direct launches (under mu)
   int64_t closed_total_left = -1;  // closed-loop runs: releases left over all tasks, -1 = no common budget
   bool prof = false;                // driver profile: where a stage's wall time goes (host clock and GPU markers)
   int64_t prof_acc[8] = {0};
@@ -145,7 +175,12 @@ int64_t now_ns() {
 
 // ---- stage execution ----------------------------------------------------------------------------------------------
 
-ConvArgs conv_args(TaskRt& T, int l, void* y, const void* net_input = nullptr) {
+// The loaded code object and its kernels: set up by the first daris_init with a device and kept until the process ends.
+AqlRuntime g_rt;
+KernelTable g_kt;
+int g_rt_device = -1;
+
+ConvArgs conv_args(TaskRt& T, int l, void* y) {
   NetPlan& net = T.net;
   LayerPlan& L = net.layers[l];
   const TensorInfo& in = net.tensor(L.in_t);
@@ -159,101 +194,328 @@ ConvArgs conv_args(TaskRt& T, int l, void* y, const void* net_input = nullptr) {
   a.MT = L.cp.MT; a.NTn = L.cp.NTn; a.G = L.cp.G; a.xmode = L.cp.xmode;
   a.mg_wo = div_magic((uint32_t)a.Wo); a.mg_cin = div_magic((uint32_t)a.Cin); a.mg_kw = div_magic((uint32_t)a.kw);
   a.c_real = 0;
-  if (l == 0 && net.fuse_ingest) {  // layer 0 gathers from the caller's fp32 [C][H][W] buffer
-    a.x = net_input;
+  if (l == 0 && net.fuse_ingest) {  // layer 0 gathers from the job's fp32 [C][H][W] input: the pointer is filled in per job
+    a.x = nullptr;
     a.c_real = net.in_c;
   }
   return a;
 }
 
-hipError_t launch_layer(TaskRt& T, int l, const void* net_input, void* d_logits, hipStream_t s, bool sample = false) {
-  // Diagnostic: DARIS_HOST_LAUNCH_DELAY_US=n makes the host spin n microseconds before every launch, which
-  // reproduces the regime a tracing profiler puts the run in (host-bound launches, kernels starting on an idle GPU).
-  static const int delay_us = getenv("DARIS_HOST_LAUNCH_DELAY_US") ? atoi(getenv("DARIS_HOST_LAUNCH_DELAY_US")) : 0;
-  if (delay_us > 0) {
-    const auto until = std::chrono::steady_clock::now() + std::chrono::microseconds(delay_us);
-    while (std::chrono::steady_clock::now() < until) {}
-  }
-  NetPlan& net = T.net;
-  LayerPlan& L = net.layers[l];
-  const TensorInfo& in = net.tensor(L.in_t);
-  const void* x = T.slots[in.slot];
-  const bool last = l == (int)net.layers.size() - 1;
-  void* y = (last && net.final_direct) ? d_logits : T.slots[L.out.slot];
-  switch (L.d.op) {
-    case DARIS_OP_CONV:
-      if (L.depthwise) {
-        DwArgs a;
-        a.x = x; a.w = L.w_dev; a.bias = L.b_dev; a.y = y;
-        a.H = in.H; a.W = in.W; a.C = in.Cs; a.Ho = L.out.H; a.Wo = L.out.W;
-        a.k = L.d.k; a.stride = L.d.stride; a.pad = L.d.pad; a.act = L.d.act;
-        return launch_dwconv(a, net.bf16, s);
-      } else {
-        if (L.pair_with >= 0 && !L.pair_lead) return hipSuccess;  // issued together with the next layer
-        if (l == 0 && net.fuse_ingest && !net_input) return hipErrorInvalidValue;
-        const ConvArgs a = conv_args(T, l, y, net_input);
-        hipEvent_t t0 = nullptr, t1 = nullptr;
-        double flops = 2.0 * (double)L.macs;
-        if (L.pair_with >= 0) flops += 2.0 * (double)net.layers[L.pair_with].macs;
-        const size_t slot = sample ? G->tm_used.fetch_add(1) : (size_t)-1;
-        if (sample && slot < G->tm_pairs.size()) {
-          TimingPair& tp = G->tm_pairs[slot];
-          tp.kernel = L.kernel_id;
-          tp.flops = flops;
-          t0 = tp.e0;
-          t1 = tp.e1;
-        }
-        if (L.pair_with >= 0) {
-          LayerPlan& O = net.layers[L.pair_with];
-          const ConvArgs b = conv_args(T, L.pair_with, T.slots[O.out.slot]);
-          const bool l_heavy = L.macs >= O.macs;  // the heavier convolution is the first problem (its plan was kept)
-          return l_heavy ? launch_conv_pair(L.cp, a, O.cp, b, net.bf16, s, t0, t1) : launch_conv_pair(O.cp, b, L.cp, a, net.bf16, s, t0, t1);
-        }
-        return launch_conv(L.cp, a, net.bf16, s, t0, t1);
-      }
-    case DARIS_OP_MAXPOOL:
-    case DARIS_OP_GAVGPOOL: {
-      PoolArgs a;
-      a.x = x; a.y = y; a.H = in.H; a.W = in.W; a.C = in.Cs; a.Ho = L.out.H; a.Wo = L.out.W;
-      a.k = L.d.k; a.stride = L.d.stride; a.pad = L.d.pad;
-      return L.d.op == DARIS_OP_MAXPOOL ? launch_maxpool(a, net.bf16, s) : launch_gavgpool(a, net.bf16, s);
-    }
-    case DARIS_OP_FC: {
-      FcArgs a;
-      a.x = x; a.w = L.w_dev; a.bias = L.b_dev; a.y = y;
-      a.K = L.K; a.N = L.d.c_out; a.Ns = (last && net.final_direct) ? L.d.c_out : L.out.Cs;
-      a.act = L.d.act; a.out_f32 = (last && net.final_direct) ? 1 : 0;
-      return launch_fc(a, net.bf16, s);
-    }
-  }
-  return hipErrorInvalidValue;
-}
-
-hipError_t launch_stage(TaskRt& T, int stage, const JobIo& io, hipStream_t s, bool sample = false) {
+// Encodes the whole network of T as launches (weights, activation buffers and workspace must exist) and uploads their
+// argument blocks.  The two pointers that change from job to job (the input of the first launch, the logits of the last)
+// stay null in these blocks; a job brings its own copies of the two blocks (JobIo).  Returns "" or an error text.
+std::string build_launches(TaskRt& T) {
   NetPlan& net = T.net;
   const int n = (int)net.layers.size();
-  const int first = net.stage_first[stage];
-  const int end = stage + 1 < (int)net.stage_first.size() ? net.stage_first[stage + 1] : n;
-  hipError_t e;
-  if (stage == 0 && !net.fuse_ingest) {
-    e = launch_ingest((const float*)io.in, T.slots[net.ingest.slot], net.ingest.C, net.ingest.Cs, net.ingest.H, net.ingest.W,
-                      net.bf16, s);
-    if (e != hipSuccess) return e;
+  const int bf16 = net.bf16;
+  std::vector<KernelLaunch> ks;
+  T.launches.clear();
+  T.layer_lo.assign(n + 1, 0);
+  T.in_launch = T.out_launch = -1;
+  auto take = [&](double flops) {
+    for (size_t i = 0; i < ks.size(); ++i) {
+      LaunchRt r;
+      r.kl = ks[i];
+      r.flops = i == 0 ? flops : 0;
+      T.launches.push_back(r);
+    }
+    ks.clear();
+  };
+  if (!net.fuse_ingest) {
+    if (!encode_ingest(g_kt, nullptr, T.slots[net.ingest.slot], net.ingest.C, net.ingest.Cs, net.ingest.H, net.ingest.W, bf16, &ks))
+      return "input conversion launch";
+    T.in_launch = 0;
+    T.in_off = kIngestInputOffset;
+    take(0);
   }
-  for (int l = first; l < end; ++l) {
-    e = launch_layer(T, l, io.in, io.out, s, sample);
-    if (e != hipSuccess) return e;
+  for (int l = 0; l < n; ++l) {
+    T.layer_lo[l] = (int)T.launches.size();
+    LayerPlan& L = net.layers[l];
+    const TensorInfo& in = net.tensor(L.in_t);
+    const void* x = T.slots[in.slot];
+    const bool direct = l == n - 1 && net.final_direct;  // writes the job's logits
+    void* y = direct ? nullptr : T.slots[L.out.slot];
+    bool ok = false;
+    double flops = 0;
+    switch (L.d.op) {
+      case DARIS_OP_CONV:
+        if (L.depthwise) {
+          DwArgs a;
+          a.x = x; a.w = L.w_dev; a.bias = L.b_dev; a.y = y;
+          a.H = in.H; a.W = in.W; a.C = in.Cs; a.Ho = L.out.H; a.Wo = L.out.W;
+          a.k = L.d.k; a.stride = L.d.stride; a.pad = L.d.pad; a.act = L.d.act;
+          ok = encode_dwconv(g_kt, a, bf16, &ks);
+        } else if (L.pair_with >= 0 && !L.pair_lead) {
+          ok = true;  // issued together with the next layer
+        } else {
+          const ConvArgs a = conv_args(T, l, y);
+          flops = 2.0 * (double)L.macs;
+          if (L.pair_with >= 0) {
+            LayerPlan& O = net.layers[L.pair_with];
+            const ConvArgs b = conv_args(T, L.pair_with, T.slots[O.out.slot]);
+            flops += 2.0 * (double)O.macs;
+            // the heavier convolution is the first problem (its plan was kept)
+            ok = L.macs >= O.macs ? encode_conv_pair(g_kt, L.cp, a, O.cp, b, bf16, &ks) : encode_conv_pair(g_kt, O.cp, b, L.cp, a, bf16, &ks);
+          } else {
+            if (l == 0 && net.fuse_ingest) {
+              T.in_launch = (int)T.launches.size();
+              T.in_off = kConvInputOffset;
+            }
+            ok = encode_conv(g_kt, L.cp, a, bf16, &ks);
+          }
+        }
+        break;
+      case DARIS_OP_MAXPOOL:
+      case DARIS_OP_GAVGPOOL: {
+        PoolArgs a;
+        a.x = x; a.y = y; a.H = in.H; a.W = in.W; a.C = in.Cs; a.Ho = L.out.H; a.Wo = L.out.W;
+        a.k = L.d.k; a.stride = L.d.stride; a.pad = L.d.pad;
+        ok = L.d.op == DARIS_OP_MAXPOOL ? encode_maxpool(g_kt, a, bf16, &ks) : encode_gavgpool(g_kt, a, bf16, &ks);
+        break;
+      }
+      case DARIS_OP_FC: {
+        FcArgs a;
+        a.x = x; a.w = L.w_dev; a.bias = L.b_dev; a.y = y;
+        a.K = L.K; a.N = L.d.c_out; a.Ns = direct ? L.d.c_out : L.out.Cs;
+        a.act = L.d.act; a.out_f32 = direct ? 1 : 0;
+        if (direct) {
+          T.out_launch = (int)T.launches.size();
+          T.out_off = kFcOutputOffset;
+        }
+        ok = encode_fc(g_kt, a, bf16, &ks);
+        break;
+      }
+    }
+    if (!ok) return "launch of layer " + std::to_string(l) + " (" + kernel_name(L.kernel_id) + ")";
+    take(flops);
   }
-  if (end == n && !net.final_direct) {
+  T.layer_lo[n] = (int)T.launches.size();
+  if (!net.final_direct) {
     const TensorInfo& o = net.layers[n - 1].out;
-    e = launch_egress(T.slots[o.slot], (float*)io.out, o.C, o.Cs, o.H, o.W, net.bf16, s);
-    if (e != hipSuccess) return e;
+    if (!encode_egress(g_kt, T.slots[o.slot], nullptr, o.C, o.Cs, o.H, o.W, bf16, &ks)) return "output conversion launch";
+    T.out_launch = (int)T.launches.size();
+    T.out_off = kEgressOutputOffset;
+    take(0);
   }
+  // one device buffer for all argument blocks, 64 bytes apart at least
+  std::vector<unsigned char> img;
+  std::vector<size_t> off;
+  for (LaunchRt& r : T.launches) {
+    off.push_back(img.size());
+    img.insert(img.end(), r.kl.args, r.kl.args + r.kl.nbytes);
+    img.resize((img.size() + 63) / 64 * 64, 0);
+  }
+  void* dev = nullptr;
+  hipError_t e = hipMalloc(&dev, img.size());
+  if (e != hipSuccess) return std::string("argument buffer: ") + hipGetErrorString(e);
+  T.owned.push_back(dev);
+  e = hipMemcpy(dev, img.data(), img.size(), hipMemcpyHostToDevice);
+  if (e != hipSuccess) return std::string("argument upload: ") + hipGetErrorString(e);
+  for (size_t i = 0; i < T.launches.size(); ++i) T.launches[i].dev = (const char*)dev + off[i];
+  return "";
+}
+
+void free_variants(IoVariants* v) {
+  if (v->dev) (void)hipFree(v->dev);
+  v->dev = nullptr;
+  v->in.clear();
+  v->out.clear();
+}
+
+// Argument blocks of T's input-reading launch for n_in input buffers (in_stride bytes apart) and of its logits-writing
+// launch for n_out output buffers.  Leaves v empty when one launch does both (then jobs patch at launch time).
+hipError_t build_variants(TaskRt& T, const void* in_base, int n_in, size_t in_stride, void* out_base, int n_out, size_t out_stride,
+                          IoVariants* v) {
+  free_variants(v);
+  if (T.in_launch < 0 || T.out_launch < 0 || T.in_launch == T.out_launch) return hipSuccess;
+  const KernelLaunch& ki = T.launches[T.in_launch].kl;
+  const KernelLaunch& ko = T.launches[T.out_launch].kl;
+  const size_t bi = (ki.nbytes + 63) / 64 * 64, bo = (ko.nbytes + 63) / 64 * 64;
+  std::vector<unsigned char> img((size_t)n_in * bi + (size_t)n_out * bo, 0);
+  for (int i = 0; i < n_in; ++i) {
+    unsigned char* blk = img.data() + (size_t)i * bi;
+    std::memcpy(blk, ki.args, ki.nbytes);
+    const void* ptr = (const char*)in_base + (size_t)i * in_stride;
+    std::memcpy(blk + T.in_off, &ptr, sizeof(ptr));
+  }
+  for (int i = 0; i < n_out; ++i) {
+    unsigned char* blk = img.data() + (size_t)n_in * bi + (size_t)i * bo;
+    std::memcpy(blk, ko.args, ko.nbytes);
+    void* ptr = (char*)out_base + (size_t)i * out_stride;
+    std::memcpy(blk + T.out_off, &ptr, sizeof(ptr));
+  }
+  hipError_t e = hipMalloc((void**)&v->dev, img.size());
+  if (e != hipSuccess) {
+    v->dev = nullptr;
+    return e;
+  }
+  e = hipMemcpy(v->dev, img.data(), img.size(), hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    free_variants(v);
+    return e;
+  }
+  for (int i = 0; i < n_in; ++i) v->in.push_back(v->dev + (size_t)i * bi);
+  for (int i = 0; i < n_out; ++i) v->out.push_back(v->dev + (size_t)n_in * bi + (size_t)i * bo);
   return hipSuccess;
 }
 
+struct EnqueueOpts {
+  hsa_signal_t done{0};   // completes with the last launch
+  hsa_signal_t first{0};  // completes with the first launch (ignored when that launch carries `done`, or when sampling)
+  bool release_system = false;  // the last launch makes its writes visible to the host and to other processes' copies
+  bool acquire_system = false;  // the first launch sees what copies and other queues of the system wrote before
+  bool sample = false;          // every launch completes a signal of S.tsig, so that its time stamps can be read
+};
+
+// Appends launches [lo, hi) of T to S's queue (S.qmu held).  Returns nullptr or an error text.
+const char* enqueue_range(TaskRt& T, int lo, int hi, const JobIo& io, StreamRt& S, const EnqueueOpts& o) {
+  // Diagnostic: DARIS_HOST_LAUNCH_DELAY_US=n makes the host spin n microseconds before every launch, which
+  // reproduces the regime a tracing profiler puts the run in (host-bound launches, kernels starting on an idle GPU).
+  static const int delay_us = getenv("DARIS_HOST_LAUNCH_DELAY_US") ? atoi(getenv("DARIS_HOST_LAUNCH_DELAY_US")) : 0;
+  if (lo < 0 || hi > (int)T.launches.size() || lo >= hi) return "empty launch range";
+  if (o.sample) {
+    while ((int)S.tsig.size() < hi - lo - 1) {
+      hsa_signal_t sg = g_rt.new_signal(1);
+      if (!sg.handle) return "signal creation failed";
+      S.tsig.push_back(sg);
+    }
+  }
+  for (int i = lo; i < hi; ++i) {
+    if (delay_us > 0) {
+      const auto until = std::chrono::steady_clock::now() + std::chrono::microseconds(delay_us);
+      while (std::chrono::steady_clock::now() < until) {}
+    }
+    const LaunchRt& r = T.launches[i];
+    hsa_signal_t sig{0};
+    if (i == hi - 1 && o.done.handle) sig = o.done;
+    else if (o.sample && i < hi - 1) sig = S.tsig[i - lo];
+    else if (i == lo) sig = o.first;
+    const unsigned fl = ((i == hi - 1 && o.release_system) ? AqlQueue::kReleaseSystem : 0u) | ((i == lo && o.acquire_system) ? AqlQueue::kAcquireSystem : 0u);
+    const void* dev = r.dev;
+    const bool is_in = i == T.in_launch, is_out = i == T.out_launch;
+    if (is_in || is_out) {
+      if (is_in && !is_out && io.in_args) dev = io.in_args;
+      else if (is_out && !is_in && io.out_args) dev = io.out_args;
+      else {
+        if ((is_in && !io.in) || (is_out && !io.out)) return "job without I/O buffers";
+        alignas(8) unsigned char blk[sizeof(KernelLaunch::args)];
+        std::memcpy(blk, r.kl.args, r.kl.nbytes);
+        if (is_in) std::memcpy(blk + T.in_off, &io.in, sizeof(void*));
+        if (is_out) std::memcpy(blk + T.out_off, &io.out, sizeof(void*));
+        if (!S.q.dispatch_copy(*r.kl.k, r.kl.groups, r.kl.threads, blk, r.kl.nbytes, sig, fl)) return "packet rejected";
+        continue;
+      }
+    }
+    if (!S.q.dispatch(*r.kl.k, r.kl.groups, r.kl.threads, dev, sig, fl)) return "packet rejected";
+  }
+  return nullptr;
+}
+
+void stage_range(const TaskRt& T, int stage, int* lo, int* hi) {
+  const NetPlan& net = T.net;
+  const int n = (int)net.layers.size();
+  const int first = net.stage_first[stage];
+  const int end = stage + 1 < (int)net.stage_first.size() ? net.stage_first[stage + 1] : n;
+  *lo = stage == 0 ? 0 : T.layer_lo[first];
+  *hi = end == n ? (int)T.launches.size() : T.layer_lo[end];
+}
+
+// Enqueues one stage of a job on S (S.qmu held); S.done completes with it.  Inside a job the next stage runs on this
+// device whichever queue it gets, so its boundary releases at device scope; the last stage's boundary makes the logits
+// visible to the host.
+const char* enqueue_stage(TaskRt& T, int stage, const JobIo& io, StreamRt& S, bool sample, bool prof) {
+  int lo, hi;
+  stage_range(T, stage, &lo, &hi);
+  EnqueueOpts o;
+  o.done = S.done;
+  o.first = prof ? S.begin : hsa_signal_t{0};
+  o.release_system = stage + 1 == (int)T.net.stage_first.size();
+  o.acquire_system = stage == 0;
+  o.sample = sample;
+  S.pend_lo = lo;
+  S.pend_hi = hi;
+  S.pend_sample = sample;
+  S.pend_prof = prof;
+  return enqueue_range(T, lo, hi, io, S, o);
+}
+
+// After S.done was seen complete: reads the time stamps the stage asked for (kernel timing into the global sums; the
+// span from the first kernel's start to the last kernel's end is returned in nanoseconds, 0 if not profiled) and
+// re-arms the signals.  The global sums need G->mu in real-time mode.
+int64_t finish_stage(TaskRt& T, StreamRt& S) {
+  const int lo = S.pend_lo, hi = S.pend_hi;
+  int64_t span_ns = 0;
+  double t_first = 0, t_last_end = 0, a = 0, b = 0;
+  if (S.pend_sample) {
+    for (int i = lo; i < hi; ++i) {
+      const hsa_signal_t sg = i == hi - 1 ? S.done : S.tsig[i - lo];
+      if (!g_rt.dispatch_time_us(sg, &a, &b)) continue;
+      const LaunchRt& r = T.launches[i];
+      const int k = r.kl.kernel_id;
+      if (k > K_NONE && k < K_COUNT) {
+        G->tm_launches[k]++;
+        G->tm_ms[k] += (b - a) * 1e-3;
+        G->tm_flops[k] += r.flops;
+      }
+      if (i == lo) t_first = a;
+      if (i == hi - 1) t_last_end = b;
+      if (i < hi - 1) hsa_signal_store_relaxed(sg, 1);
+    }
+    span_ns = (int64_t)((t_last_end - t_first) * 1e3);
+  } else if (S.pend_prof) {
+    if (g_rt.dispatch_time_us(S.done, &a, &b)) {
+      t_first = a;
+      t_last_end = b;
+      if (hi - lo > 1) {
+        double a0 = 0, b0 = 0;
+        if (g_rt.dispatch_time_us(S.begin, &a0, &b0)) t_first = a0;
+      }
+      span_ns = (int64_t)((t_last_end - t_first) * 1e3);
+    }
+    if (hi - lo > 1) hsa_signal_store_relaxed(S.begin, 1);
+  }
+  hsa_signal_store_relaxed(S.done, 1);
+  return span_ns;
+}
+
+void spin_until_done(hsa_signal_t sg) {
+  while (!aql_done(sg)) {
+    for (int i = 0; i < 8; ++i) __builtin_ia32_pause();
+  }
+}
+
+// API thread, G->mu held: runs launches [lo, hi) of T on S and waits for them.
+daris_status run_direct(TaskRt& T, int lo, int hi, const JobIo& io, StreamRt& S) {
+  EnqueueOpts o;
+  o.done = G->util_sig;
+  o.release_system = o.acquire_system = true;
+  const char* err;
+  {
+    std::lock_guard<std::mutex> ql(S.qmu);
+    err = enqueue_range(T, lo, hi, io, S, o);
+  }
+  if (err) return fail(DARIS_EHIP, "%s", err);
+  aql_wait(G->util_sig);
+  return DARIS_OK;
+}
+
+// API thread, G->mu held: one launch with arguments built just now.
+daris_status run_one(const std::vector<KernelLaunch>& ks, StreamRt& S) {
+  for (size_t i = 0; i < ks.size(); ++i) {
+    bool ok;
+    {
+      std::lock_guard<std::mutex> ql(S.qmu);
+      ok = S.q.dispatch_copy(*ks[i].k, ks[i].groups, ks[i].threads, ks[i].args, ks[i].nbytes, G->util_sig, AqlQueue::kReleaseSystem | AqlQueue::kAcquireSystem);
+    }
+    if (!ok) return fail(DARIS_EHIP, "packet rejected");
+    aql_wait(G->util_sig);
+  }
+  return DARIS_OK;
+}
+
 // Acts on the launches a dispatch pass produced.  Virtual time: schedule the completion from the table and (with a
-// device) enqueue the kernels behind the task's previous stage.  Real time: enqueue and record the boundary event.
+// device) run the kernels now, waiting for them, so that a task's stages execute in order whichever queues they get.
+// Real time: hand the stage to the worker of its stream.
 daris_status issue(const std::vector<Launch>& ls, int64_t t) {
   for (const Launch& l : ls) {
     TaskRt& T = *G->tasks[l.task];
@@ -269,13 +531,23 @@ daris_status issue(const std::vector<Launch>& ls, int64_t t) {
       StreamRt& S = *G->parts[l.part].streams[l.stream];
       auto io = T.io.find(l.job);
       if (io == T.io.end()) return fail(DARIS_ESTATE, "job %u of task %d has no I/O buffers", l.job, l.task);
-      const bool sample = G->tm_every > 0 && l.job % (uint32_t)G->tm_every == 0;
+      bool sample = G->tm_every > 0 && l.job % (uint32_t)G->tm_every == 0 && G->tm_left > 0;
+      if (sample) {
+        int lo, hi;
+        stage_range(T, l.stage, &lo, &hi);
+        G->tm_left -= hi - lo;
+      }
       if (G->vt) {
-        HIP_TRY(hipStreamWaitEvent(S.s, T.chain, 0));
-        HIP_TRY(launch_stage(T, l.stage, io->second, S.s, sample));
-        HIP_TRY(hipEventRecord(T.chain, S.s));
+        const char* err;
+        {
+          std::lock_guard<std::mutex> ql(S.qmu);
+          err = enqueue_stage(T, l.stage, io->second, S, sample, false);
+        }
+        if (err) return fail(DARIS_EHIP, "stage execution: %s", err);
+        spin_until_done(S.done);
+        finish_stage(T, S);
       } else {
-        // real time: the stream's own worker enqueues the kernels and watches the boundary event
+        // real time: the stream's own worker enqueues the kernels and watches the boundary signal
         S.work = l;
         S.work_io = io->second;
         S.work_sample = sample;
@@ -336,17 +608,19 @@ JobIo pool_io(TaskRt& T, uint32_t job) {
   JobIo io;
   const NetPlan& n = T.net;
   const size_t in_elems = (size_t)n.in_c * n.in_h * n.in_w;
-  io.in = (const float*)T.pool_in + (size_t)(job % (uint32_t)T.n_inputs) * in_elems;
-  io.out = (float*)T.pool_out + (size_t)(job % (uint32_t)T.n_slots) * n.n_out;
+  const uint32_t i = job % (uint32_t)T.n_inputs, j = job % (uint32_t)T.n_slots;
+  io.in = (const float*)T.pool_in + (size_t)i * in_elems;
+  io.out = (float*)T.pool_out + (size_t)j * n.n_out;
+  if (i < T.pool.in.size()) io.in_args = T.pool.in[i];
+  if (j < T.pool.out.size()) io.out_args = T.pool.out[j];
   return io;
 }
 
 // Worker of one stream (real-time mode).  It enqueues the kernels of the stage a dispatch pass gave to its stream,
-// records the boundary event, spins on it, and then -- under the scheduler lock -- feeds the completion into the
+// spins on the completion signal of the last one, and then -- under the scheduler lock -- feeds the completion into the
 // decision core and runs the dispatch pass that follows every input event.  The enqueue and the wait happen
 // outside the lock, so the partitions' launch paths do not serialise.
 void worker_loop(StreamRt* S) {
-  (void)hipSetDevice(G->device);
   std::unique_lock<std::mutex> lk(G->mu);
   for (;;) {
     if (!G->stop && !S->has_work) {
@@ -368,32 +642,28 @@ void worker_loop(StreamRt* S) {
     const int64_t t_handed = S->work_t;
     lk.unlock();
     const int64_t t0 = prof ? now_ns() : 0;
-    hipError_t e = hipSuccess;
-    if (prof) e = hipEventRecord(S->begin, S->s);
-    if (e == hipSuccess) e = launch_stage(T, l.stage, io, S->s, sample);
-    if (e == hipSuccess && prof) e = hipEventRecord(S->end, S->s);
-    // Inside a job the next stage runs on this device whichever stream it gets, so the boundary needs no cache
-    // write-back towards the host; only the last stage's event carries the system-scope fence.
-    hipEvent_t done = (l.stage + 1 < (int)T.net.stage_first.size()) ? S->done_mid : S->done;
-    if (e == hipSuccess) e = hipEventRecord(done, S->s);
-    const int64_t t1 = prof ? now_ns() : 0;
-    if (e == hipSuccess) {
-      while ((e = hipEventQuery(done)) == hipErrorNotReady) {
-        for (int i = 0; i < 16; ++i) __builtin_ia32_pause();
-      }
+    const char* err;
+    {
+      std::lock_guard<std::mutex> ql(S->qmu);
+      err = enqueue_stage(T, l.stage, io, *S, sample, prof);
     }
+    const int64_t t1 = prof ? now_ns() : 0;
+    if (!err) spin_until_done(S->done);
     const int64_t t2 = prof ? now_ns() : 0;
-    float gpu_ms = 0.f;
-    if (prof && e == hipSuccess) e = hipEventElapsedTime(&gpu_ms, S->begin, S->end);
     lk.lock();
-    if (e != hipSuccess && G->async_error.empty()) G->async_error = std::string("stage execution: ") + hipGetErrorString(e);
+    int64_t gpu_ns = 0;
+    if (err) {
+      if (G->async_error.empty()) G->async_error = std::string("stage execution: ") + err;
+    } else {
+      gpu_ns = finish_stage(T, *S);
+    }
     const int64_t now = now_ns();
     if (prof) {
       G->prof_acc[0] += 1;
       G->prof_acc[1] += t1 - t0;
       G->prof_acc[2] += t2 - t1;
       G->prof_acc[3] += now - t2;
-      G->prof_acc[5] += (int64_t)(gpu_ms * 1e6);
+      G->prof_acc[5] += gpu_ns;
       G->prof_acc[6] += t0 - t_handed;
     }
     const int task = l.task;
@@ -446,8 +716,7 @@ daris_status wait_idle() {
 void free_task(TaskRt& T) {
   for (void* p : T.owned) (void)hipFree(p);
   T.owned.clear();
-  if (T.chain) (void)hipEventDestroy(T.chain);
-  T.chain = nullptr;
+  free_variants(&T.pool);
 }
 
 }  // namespace
@@ -486,10 +755,31 @@ daris_status daris_init(int device, uint64_t seed, int flags) {
       return fail(DARIS_EHIP, "no usable HIP device %d (%s)", device, e == hipSuccess ? "index out of range" : hipGetErrorString(e));
     }
     e = hipSetDevice(device);
+    if (e == hipSuccess) e = hipFree(nullptr);  // HIP's context (and with it the HSA runtime) exists from here on
     if (e != hipSuccess) {
       delete G;
       G = nullptr;
       return fail(DARIS_EHIP, "hipSetDevice failed: %s", hipGetErrorString(e));
+    }
+    std::string err;
+    if (!g_rt.ready()) {
+      err = g_rt.init(device, daris_kernels_co, (size_t)(daris_kernels_co_end - daris_kernels_co));
+      if (err.empty()) {
+        err = g_kt.resolve(g_rt);
+        if (!err.empty()) err = "kernel " + err;
+      }
+      if (err.empty()) g_rt_device = device;
+    } else if (device != g_rt_device) {
+      err = "the kernels are loaded on device " + std::to_string(g_rt_device) + "; one device per process";
+    }
+    if (err.empty()) {
+      G->util_sig = g_rt.new_signal(1);
+      if (!G->util_sig.handle) err = "signal creation failed";
+    }
+    if (!err.empty()) {
+      delete G;
+      G = nullptr;
+      return fail(DARIS_EHIP, "%s", err.c_str());
     }
   }
   G->inited = true;
@@ -511,18 +801,14 @@ daris_status daris_shutdown(void) {
   if (!G->nodev) {
     (void)hipDeviceSynchronize();
     for (auto& T : G->tasks) free_task(*T);
-    for (TimingPair& tp : G->tm_pairs) {
-      (void)hipEventDestroy(tp.e0);
-      (void)hipEventDestroy(tp.e1);
-    }
     for (PartRt& P : G->parts)
       for (auto& S : P.streams) {
-        if (S->done) (void)hipEventDestroy(S->done);
-        if (S->done_mid) (void)hipEventDestroy(S->done_mid);
-        if (S->begin) (void)hipEventDestroy(S->begin);
-        if (S->end) (void)hipEventDestroy(S->end);
-        if (S->s) (void)hipStreamDestroy(S->s);
+        S->q.destroy();
+        g_rt.free_signal(S->done);
+        g_rt.free_signal(S->begin);
+        for (hsa_signal_t sg : S->tsig) g_rt.free_signal(sg);
       }
+    g_rt.free_signal(G->util_sig);
   }
   delete G;
   G = nullptr;
@@ -618,10 +904,11 @@ daris_task daris_register_task(const daris_dnn* dnn, int64_t period_ns, int64_t 
         return fail(DARIS_ENOMEM, "split-K workspace: %s", hipGetErrorString(e));
       }
     }
-    hipError_t e = hipEventCreateWithFlags(&T->chain, hipEventDisableTiming);
-    if (e != hipSuccess) {
+    T->prio = priority;
+    err = build_launches(*T);
+    if (!err.empty()) {
       free_task(*T);
-      return fail(DARIS_EHIP, "hipEventCreate: %s", hipGetErrorString(e));
+      return fail(DARIS_EHIP, "%s", err.c_str());
     }
   }
   T->prio = priority;
@@ -660,7 +947,7 @@ int32_t daris_get_launch_plan(daris_task t, int layer, int64_t* out, int32_t cap
   const ConvPlan& c = L.cp;
   const bool conv = L.d.op == DARIS_OP_CONV && !L.depthwise;
   const int64_t v[24] = {L.kernel_id, conv ? 1 : 0, conv ? 1 : 0, (int64_t)L.out.H * L.out.W, L.out.Cs, L.K, L.Kpad,
-                         c.tn, c.nw, c.S, c.sz, c.sw, c.splitk, c.MT, c.NTn, c.G, c.xmode, c.grid.x, c.grid.y, c.grid.z,
+                         c.tn, c.nw, c.S, c.sz, c.sw, c.splitk, c.MT, c.NTn, c.G, c.xmode, (int64_t)c.grid_x, 1, 1,
                          c.threads, (int64_t)c.ws_bytes, L.pair_with, L.pair_lead ? 1 : 0};
   for (int i = 0; i < 24; ++i) out[i] = v[i];
   return 24;
@@ -697,7 +984,7 @@ daris_status daris_set_virtual_time(daris_task t, int stage, daris_part p, int64
   return DARIS_OK;
 }
 
-// Creates the CU-masked streams of every partition; after this the partition set is frozen.
+// Creates the CU-masked queues of every partition; after this the partition set is frozen.
 static daris_status make_streams(void) {
   if (G->frozen) return DARIS_OK;
   if (G->parts.empty()) return fail(DARIS_ESTATE, "no partition");
@@ -706,11 +993,14 @@ static daris_status make_streams(void) {
       for (int i = 0; i < P.n_streams; ++i) {
         P.streams.emplace_back(new StreamRt());
         StreamRt& S = *P.streams.back();
-        HIP_TRY(hipExtStreamCreateWithCUMask(&S.s, 8, P.mask));
-        HIP_TRY(hipEventCreateWithFlags(&S.done, hipEventDisableTiming));
-        HIP_TRY(hipEventCreateWithFlags(&S.done_mid, hipEventDisableTiming | hipEventDisableSystemFence));
-        HIP_TRY(hipEventCreateWithFlags(&S.begin, hipEventDisableSystemFence));
-        HIP_TRY(hipEventCreateWithFlags(&S.end, hipEventDisableSystemFence));
+        const std::string err = S.q.create(&g_rt, P.mask);
+        if (!err.empty()) return fail(DARIS_EHIP, "queue of partition with %d CUs: %s", P.n_cu, err.c_str());
+        S.done = g_rt.new_signal(1);
+        S.begin = g_rt.new_signal(1);
+        if (!S.done.handle || !S.begin.handle) return fail(DARIS_EHIP, "signal creation failed");
+        // completion signals receive the start and end time stamps of their dispatch; switched on before the first
+        // packet and left on (a stage carries one signal, so the cost is one record per stage)
+        S.q.set_profiling(true);
       }
     }
   }
@@ -797,8 +1087,7 @@ daris_status daris_run_until_idle(void) {
   if (G->vt) {
     daris_status st = vt_advance(0, true);
     if (st != DARIS_OK) return st;
-    if (!G->nodev) HIP_TRY(hipDeviceSynchronize());
-    return DARIS_OK;
+    return DARIS_OK;  // with a device every stage was waited for when it was issued
   }
   return wait_idle();
 }
@@ -809,10 +1098,22 @@ daris_status daris_task_set_io(daris_task t, const void* d_inputs, int32_t n_inp
   if (!G->nodev && (!d_inputs || !d_logits)) return fail(DARIS_EINVAL, "NULL device buffer");
   if (n_inputs < 1 || n_slots < 1) return fail(DARIS_EINVAL, "pool sizes must be >= 1");
   TaskRt& T = *G->tasks[t];
+  std::lock_guard<std::mutex> lk(G->mu);
+  if (G->core.has_active(t)) return fail(DARIS_ESTATE, "task %d has an active job", t);
   T.pool_in = d_inputs;
   T.pool_out = d_logits;
   T.n_inputs = n_inputs;
   T.n_slots = n_slots;
+  if (!G->nodev) {
+    // argument blocks for every buffer of the two pools, so that a release writes nothing but packets
+    free_variants(&T.pool);
+    if ((int64_t)n_inputs + n_slots <= (1 << 20)) {
+      const NetPlan& n = T.net;
+      hipError_t e = build_variants(T, d_inputs, n_inputs, (size_t)n.in_c * n.in_h * n.in_w * sizeof(float), d_logits, n_slots,
+                                    (size_t)n.n_out * sizeof(float), &T.pool);
+      if (e != hipSuccess) return fail(e == hipErrorOutOfMemory ? DARIS_ENOMEM : DARIS_EHIP, "argument blocks of the I/O pool: %s", hipGetErrorString(e));
+    }
+  }
   return DARIS_OK;
 }
 
@@ -958,13 +1259,10 @@ daris_status daris_forward(daris_task t, const void* d_input, void* d_logits, da
   std::lock_guard<std::mutex> lk(G->mu);
   if (G->core.has_active(t)) return fail(DARIS_ESTATE, "task %d has an active job", t);
   TaskRt& T = *G->tasks[t];
-  hipStream_t s = G->parts[p].streams[0]->s;
   JobIo io;
   io.in = d_input;
   io.out = d_logits;
-  for (int j = 0; j < (int)T.net.stage_first.size(); ++j) HIP_TRY(launch_stage(T, j, io, s));
-  HIP_TRY(hipStreamSynchronize(s));
-  return DARIS_OK;
+  return run_direct(T, 0, (int)T.launches.size(), io, *G->parts[p].streams[0]);
 }
 
 daris_status daris_read_layer(daris_task t, int layer, float* host_out, int64_t cap_elems) {
@@ -978,13 +1276,18 @@ daris_status daris_read_layer(daris_task t, int layer, float* host_out, int64_t 
   if (o.slot < 0) return fail(DARIS_ESTATE, "layer %d writes straight to the caller's logits", layer);
   const int64_t n = (int64_t)o.C * o.H * o.W;
   if (!host_out || cap_elems < n) return fail(DARIS_EINVAL, "host buffer too small (%lld needed)", (long long)n);
+  st = make_streams();
+  if (st != DARIS_OK) return st;
+  std::lock_guard<std::mutex> lk(G->mu);
   float* tmp = nullptr;
   HIP_TRY(hipMalloc((void**)&tmp, (size_t)n * sizeof(float)));
-  hipError_t e = launch_egress(T.slots[o.slot], tmp, o.C, o.Cs, o.H, o.W, T.net.bf16, nullptr);
-  if (e == hipSuccess) e = hipMemcpy(host_out, tmp, (size_t)n * sizeof(float), hipMemcpyDeviceToHost);
+  std::vector<KernelLaunch> ks;
+  st = encode_egress(g_kt, T.slots[o.slot], tmp, o.C, o.Cs, o.H, o.W, T.net.bf16, &ks) ? run_one(ks, *G->parts[0].streams[0])
+                                                                                      : fail(DARIS_EHIP, "read_layer: launch encoding");
+  hipError_t e = st == DARIS_OK ? hipMemcpy(host_out, tmp, (size_t)n * sizeof(float), hipMemcpyDeviceToHost) : hipSuccess;
   (void)hipFree(tmp);
   if (e != hipSuccess) return fail(DARIS_EHIP, "read_layer: %s", hipGetErrorString(e));
-  return DARIS_OK;
+  return st;
 }
 
 daris_status daris_profile_layers(daris_task t, daris_part p, int reps, float* ms_per_layer, int32_t* kernel_id, double* flops) {
@@ -994,38 +1297,63 @@ daris_status daris_profile_layers(daris_task t, daris_part p, int reps, float* m
   std::lock_guard<std::mutex> lk(G->mu);
   if (G->core.has_active(t)) return fail(DARIS_ESTATE, "task %d has an active job", t);
   TaskRt& T = *G->tasks[t];
-  hipStream_t s = G->parts[p].streams[0]->s;
+  StreamRt& S = *G->parts[p].streams[0];
   const int n = (int)T.net.layers.size();
   float* scratch_out = nullptr;
   HIP_TRY(hipMalloc((void**)&scratch_out, (size_t)std::max(T.net.n_out, 4) * sizeof(float)));
   float* scratch_in = nullptr;  // stands in for the caller's input where layer 0 reads it directly
   const size_t in_bytes = (size_t)T.net.in_c * T.net.in_h * T.net.in_w * sizeof(float);
+  IoVariants var;
   hipError_t ea = hipMalloc((void**)&scratch_in, in_bytes);
   if (ea == hipSuccess) ea = hipMemset(scratch_in, 0, in_bytes);
-  if (ea != hipSuccess) {
+  if (ea == hipSuccess) ea = build_variants(T, scratch_in, 1, 0, scratch_out, 1, 0, &var);
+  hsa_signal_t first = g_rt.new_signal(1);
+  if (ea != hipSuccess || !first.handle) {
     (void)hipFree(scratch_out);
     if (scratch_in) (void)hipFree(scratch_in);
+    g_rt.free_signal(first);
     return fail(DARIS_ENOMEM, "profile buffers: %s", hipGetErrorString(ea));
   }
-  hipEvent_t e0, e1;
-  HIP_TRY(hipEventCreate(&e0));
-  HIP_TRY(hipEventCreate(&e1));
+  JobIo io;
+  io.in = scratch_in;
+  io.out = scratch_out;
+  if (!var.in.empty()) io.in_args = var.in[0];
+  if (!var.out.empty()) io.out_args = var.out[0];
   daris_status result = DARIS_OK;
+  std::lock_guard<std::mutex> ql(S.qmu);
   for (int l = 0; l < n && result == DARIS_OK; ++l) {
-    hipError_t e = launch_layer(T, l, scratch_in, scratch_out, s);  // warm-up
-    if (e == hipSuccess) e = hipEventRecord(e0, s);
-    for (int r = 0; r < reps && e == hipSuccess; ++r) e = launch_layer(T, l, scratch_in, scratch_out, s);
-    if (e == hipSuccess) e = hipEventRecord(e1, s);
-    if (e == hipSuccess) e = hipEventSynchronize(e1);
-    float ms = 0.f;
-    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
-    if (e != hipSuccess) result = fail(DARIS_EHIP, "profiling layer %d: %s", l, hipGetErrorString(e));
-    ms_per_layer[l] = ms / reps;
+    const int lo = T.layer_lo[l], hi = T.layer_lo[l + 1];
+    ms_per_layer[l] = 0.f;
     if (kernel_id) kernel_id[l] = T.net.layers[l].kernel_id;
     if (flops) flops[l] = 2.0 * (double)T.net.layers[l].macs;
+    if (lo == hi) continue;  // the earlier member of a launch pair: its work is timed with the later one
+    // one warm-up pass, then `reps` passes back to back: from the start of the first kernel to the end of the last
+    const bool one = reps == 1 && hi - lo == 1;  // then the only launch carries the completion signal
+    const char* err = nullptr;
+    for (int r = -1; r < reps && !err; ++r) {
+      EnqueueOpts o;
+      if (r == 0 && !one) o.first = first;
+      if (r == reps - 1) o.done = G->util_sig;
+      o.acquire_system = r == -1;
+      o.release_system = r == reps - 1;
+      err = enqueue_range(T, lo, hi, io, S, o);
+    }
+    if (err) {
+      result = fail(DARIS_EHIP, "profiling layer %d: %s", l, err);
+      break;  // nothing was given the completion signal: do not wait
+    }
+    spin_until_done(G->util_sig);
+    double a0 = 0, b0 = 0, a1 = 0, b1 = 0;
+    bool ok = g_rt.dispatch_time_us(G->util_sig, &a1, &b1);
+    if (one) a0 = a1;
+    else ok = ok && g_rt.dispatch_time_us(first, &a0, &b0);
+    hsa_signal_store_relaxed(G->util_sig, 1);
+    hsa_signal_store_relaxed(first, 1);
+    if (!ok) result = fail(DARIS_EHIP, "profiling layer %d: no time stamps", l);
+    ms_per_layer[l] = (float)((b1 - a0) * 1e-3 / reps);
   }
-  (void)hipEventDestroy(e0);
-  (void)hipEventDestroy(e1);
+  g_rt.free_signal(first);
+  free_variants(&var);
   (void)hipFree(scratch_out);
   (void)hipFree(scratch_in);
   return result;
@@ -1037,36 +1365,16 @@ daris_status daris_kernel_timing_start(int every, int max_samples) {
   if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
   if (G->nodev) return fail(DARIS_ESTATE, "no device in DARIS_NO_DEVICE mode");
   if (every < 0 || max_samples < 0 || max_samples > 1000000) return fail(DARIS_EINVAL, "bad arguments");
-  std::lock_guard<std::mutex> lk(G->mu);
-  if (!G->core.idle()) return fail(DARIS_ESTATE, "jobs are active");
-  while ((int)G->tm_pairs.size() < max_samples) {
-    TimingPair tp;
-    HIP_TRY(hipEventCreateWithFlags(&tp.e0, hipEventDisableSystemFence));  // timed, without cache write-back
-    HIP_TRY(hipEventCreateWithFlags(&tp.e1, hipEventDisableSystemFence));
-    G->tm_pairs.push_back(tp);
-  }
-  G->tm_used = 0;
-  // What an event pair reports for NO work between its two records, on a partition stream: the command processor's
-  // own marker latency, which every sampled launch carries as well.  Median of 65 empty pairs.
   daris_status st = make_streams();
   if (st != DARIS_OK) return st;
-  G->tm_overhead_ms = 0;
-  if (G->tm_pairs.size() >= 65) {
-    hipStream_t s0 = G->parts[0].streams[0]->s;
-    std::vector<float> v;
-    for (int i = 0; i < 65; ++i) {
-      HIP_TRY(hipEventRecord(G->tm_pairs[i].e0, s0));
-      HIP_TRY(hipEventRecord(G->tm_pairs[i].e1, s0));
-    }
-    HIP_TRY(hipStreamSynchronize(s0));
-    for (int i = 0; i < 65; ++i) {
-      float ms = 0.f;
-      HIP_TRY(hipEventElapsedTime(&ms, G->tm_pairs[i].e0, G->tm_pairs[i].e1));
-      v.push_back(ms);
-    }
-    std::sort(v.begin(), v.end());
-    G->tm_overhead_ms = v[32];
+  std::lock_guard<std::mutex> lk(G->mu);
+  if (!G->core.idle()) return fail(DARIS_ESTATE, "jobs are active");
+  for (int i = 0; i < K_COUNT; ++i) {
+    G->tm_launches[i] = 0;
+    G->tm_ms[i] = 0;
+    G->tm_flops[i] = 0;
   }
+  G->tm_left = max_samples;
   G->tm_every = every;
   return DARIS_OK;
 }
@@ -1079,21 +1387,15 @@ int32_t daris_kernel_timing_read(int32_t cap, int64_t* launches, double* total_m
   std::lock_guard<std::mutex> lk(G->mu);
   G->tm_every = 0;
   for (int i = 0; i < K_COUNT; ++i) {
-    launches[i] = 0;
-    total_ms[i] = 0;
-    total_flops[i] = 0;
+    launches[i] = G->tm_launches[i];
+    total_ms[i] = G->tm_ms[i];
+    total_flops[i] = G->tm_flops[i];
+    G->tm_launches[i] = 0;
+    G->tm_ms[i] = 0;
+    G->tm_flops[i] = 0;
   }
-  for (size_t i = 0; i < G->tm_used; ++i) {
-    TimingPair& tp = G->tm_pairs[i];
-    HIP_TRY(hipEventSynchronize(tp.e1));
-    float ms = 0.f;
-    HIP_TRY(hipEventElapsedTime(&ms, tp.e0, tp.e1));
-    launches[tp.kernel]++;
-    total_ms[tp.kernel] += ms;
-    total_flops[tp.kernel] += tp.flops;
-  }
-  G->tm_used = 0;
-  if (empty_pair_ms) *empty_pair_ms = G->tm_overhead_ms;
+  // the durations are the command processor's own start and end stamps of each dispatch: nothing to subtract
+  if (empty_pair_ms) *empty_pair_ms = 0.0;
   return K_COUNT;
 }
 
@@ -1120,13 +1422,15 @@ daris_status daris_probe_cus(daris_part p, int n_groups, int spin, uint32_t* out
   uint32_t* d = nullptr;
   const size_t bytes = (size_t)n_groups * 2 * sizeof(uint32_t);
   HIP_TRY(hipMalloc((void**)&d, bytes));
-  hipStream_t s = G->parts[p].streams[0]->s;
-  hipError_t e = launch_cu_probe(d, n_groups, spin, s);
-  if (e == hipSuccess) e = hipStreamSynchronize(s);
-  if (e == hipSuccess) e = hipMemcpy(out, d, bytes, hipMemcpyDeviceToHost);
+  std::vector<KernelLaunch> ks;
+  {
+    std::lock_guard<std::mutex> lk(G->mu);
+    st = encode_cu_probe(g_kt, d, n_groups, spin, &ks) ? run_one(ks, *G->parts[p].streams[0]) : fail(DARIS_EHIP, "probe: launch encoding");
+  }
+  hipError_t e = st == DARIS_OK ? hipMemcpy(out, d, bytes, hipMemcpyDeviceToHost) : hipSuccess;
   (void)hipFree(d);
   if (e != hipSuccess) return fail(DARIS_EHIP, "probe: %s", hipGetErrorString(e));
-  return DARIS_OK;
+  return st;
 }
 
 daris_status daris_calibrate_afet(daris_task t, daris_part p, int reps) {
@@ -1136,33 +1440,41 @@ daris_status daris_calibrate_afet(daris_task t, daris_part p, int reps) {
   std::lock_guard<std::mutex> lk(G->mu);
   if (G->core.has_active(t) || G->core.stats(t).released > 0) return fail(DARIS_ESTATE, "calibrate before the first release of task %d", t);
   TaskRt& T = *G->tasks[t];
-  hipStream_t s = G->parts[p].streams[0]->s;
+  StreamRt& S = *G->parts[p].streams[0];
   const int k = (int)T.net.stage_first.size();
   float* in = nullptr;
   float* out = nullptr;
   const size_t in_elems = (size_t)T.net.in_c * T.net.in_h * T.net.in_w;
-  HIP_TRY(hipMalloc((void**)&in, in_elems * sizeof(float)));
-  HIP_TRY(hipMemset(in, 0, in_elems * sizeof(float)));
-  HIP_TRY(hipMalloc((void**)&out, (size_t)std::max(T.net.n_out, 4) * sizeof(float)));
+  IoVariants var;
+  hipError_t ea = hipMalloc((void**)&in, in_elems * sizeof(float));
+  if (ea == hipSuccess) ea = hipMemset(in, 0, in_elems * sizeof(float));
+  if (ea == hipSuccess) ea = hipMalloc((void**)&out, (size_t)std::max(T.net.n_out, 4) * sizeof(float));
+  if (ea == hipSuccess) ea = build_variants(T, in, 1, 0, out, 1, 0, &var);
+  if (ea != hipSuccess) {
+    if (in) (void)hipFree(in);
+    if (out) (void)hipFree(out);
+    return fail(DARIS_ENOMEM, "calibration buffers: %s", hipGetErrorString(ea));
+  }
   JobIo io;
   io.in = in;
   io.out = out;
+  if (!var.in.empty()) io.in_args = var.in[0];
+  if (!var.out.empty()) io.out_args = var.out[0];
   std::vector<int64_t> best(k, 0);
   daris_status result = DARIS_OK;
   for (int r = 0; r <= reps && result == DARIS_OK; ++r) {  // run 0 is a warm-up
     for (int j = 0; j < k; ++j) {
+      int lo, hi;
+      stage_range(T, j, &lo, &hi);
       auto t0 = std::chrono::steady_clock::now();
-      hipError_t e = launch_stage(T, j, io, s);
-      if (e == hipSuccess) e = hipStreamSynchronize(s);
+      result = run_direct(T, lo, hi, io, S);
       auto t1 = std::chrono::steady_clock::now();
-      if (e != hipSuccess) {
-        result = fail(DARIS_EHIP, "calibration: %s", hipGetErrorString(e));
-        break;
-      }
+      if (result != DARIS_OK) break;
       const int64_t ns = std::chrono::duration_cast<std::chrono::nanoseconds>(t1 - t0).count();
       if (r > 0) best[j] = std::max(best[j], ns);
     }
   }
+  free_variants(&var);
   (void)hipFree(in);
   (void)hipFree(out);
   if (result != DARIS_OK) return result;
@@ -1182,9 +1494,11 @@ daris_status daris_calibrate_afet_loaded(daris_task t, daris_part p, int reps) {
   const int nt = (int)G->tasks.size();
   // one zero-filled input and one logits buffer per task
   std::vector<float*> in(nt, nullptr), out(nt, nullptr);
+  IoVariants var;  // the target's two job-dependent argument blocks, in device memory as in production
   auto cleanup = [&]() {
     for (float* q : in) if (q) (void)hipFree(q);
     for (float* q : out) if (q) (void)hipFree(q);
+    free_variants(&var);
   };
   for (int i = 0; i < nt; ++i) {
     const NetPlan& n = G->tasks[i]->net;
@@ -1198,7 +1512,14 @@ daris_status daris_calibrate_afet_loaded(daris_task t, daris_part p, int reps) {
     }
   }
   TaskRt& T = *G->tasks[t];
-  hipStream_t s = G->parts[p].streams[0]->s;
+  StreamRt& S = *G->parts[p].streams[0];
+  {
+    hipError_t e = build_variants(T, in[t], 1, 0, out[t], 1, 0, &var);
+    if (e != hipSuccess) {
+      cleanup();
+      return fail(DARIS_ENOMEM, "calibration buffers: %s", hipGetErrorString(e));
+    }
+  }
   const int k = (int)T.net.stage_first.size();
   std::vector<int64_t> sum(k, 0);
   uint64_t rng = G->seed * 6364136223846793005ull + 1442695040888963407ull + (uint64_t)t;
@@ -1208,6 +1529,7 @@ daris_status daris_calibrate_afet_loaded(daris_task t, daris_part p, int reps) {
     std::vector<int> others;
     for (int i = 0; i < nt; ++i)
       if (i != t) others.push_back(i);
+    std::vector<StreamRt*> loaded;
     for (size_t q = 0; q < G->parts.size() && result == DARIS_OK; ++q)
       for (size_t si = 0; si < G->parts[q].streams.size() && result == DARIS_OK; ++si) {
         if ((int)q == p && si == 0) continue;
@@ -1217,27 +1539,32 @@ daris_status daris_calibrate_afet_loaded(daris_task t, daris_part p, int reps) {
         const int o = others[pick];
         others.erase(others.begin() + pick);
         TaskRt& O = *G->tasks[o];
+        StreamRt& Q = *G->parts[q].streams[si];
         JobIo io;
         io.in = in[o];
         io.out = out[o];
-        for (int j = 0; j < (int)O.net.stage_first.size(); ++j) {
-          hipError_t e = launch_stage(O, j, io, G->parts[q].streams[si]->s);
-          if (e != hipSuccess) result = fail(DARIS_EHIP, "calibration load: %s", hipGetErrorString(e));
-        }
+        EnqueueOpts eo;
+        eo.done = Q.done;  // no job is active, so the stream's worker is not using its signal
+        eo.acquire_system = eo.release_system = true;
+        std::lock_guard<std::mutex> ql(Q.qmu);
+        const char* err = enqueue_range(O, 0, (int)O.launches.size(), io, Q, eo);
+        if (err) result = fail(DARIS_EHIP, "calibration load: %s", err);
+        else loaded.push_back(&Q);
       }
     JobIo io;
     io.in = in[t];
     io.out = out[t];
+    if (!var.in.empty()) io.in_args = var.in[0];
+    if (!var.out.empty()) io.out_args = var.out[0];
     for (int j = 0; j < k && result == DARIS_OK; ++j) {
+      int lo, hi;
+      stage_range(T, j, &lo, &hi);
       auto t0 = std::chrono::steady_clock::now();
-      hipError_t e = launch_stage(T, j, io, s);
-      if (e == hipSuccess) e = hipStreamSynchronize(s);
+      result = run_direct(T, lo, hi, io, S);
       auto t1 = std::chrono::steady_clock::now();
-      if (e != hipSuccess) result = fail(DARIS_EHIP, "calibration: %s", hipGetErrorString(e));
       if (r > 0) sum[j] += std::chrono::duration_cast<std::chrono::nanoseconds>(t1 - t0).count();
     }
-    hipError_t e = hipDeviceSynchronize();
-    if (e != hipSuccess && result == DARIS_OK) result = fail(DARIS_EHIP, "calibration: %s", hipGetErrorString(e));
+    for (StreamRt* Q : loaded) aql_wait(Q->done);
   }
   cleanup();
   if (result != DARIS_OK) return result;

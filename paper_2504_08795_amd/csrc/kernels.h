@@ -1,11 +1,13 @@
-// Launch interface between the host runtime and the HIP kernels (gfx950 only).
+// Interface between the host runtime and the HIP kernels (gfx950 only): argument structures shared by both sides,
+// the host-side launch plans, and the encoders that turn a layer into ready-to-dispatch AQL launches.
 //
 // Device tensor format: NHWC, element type float (fp32 tasks) or bfloat16 stored as uint16 (bf16 tasks),
 // channel stride Cs = channel count rounded up to one 16-byte vector (4 floats / 8 bf16); pad channels hold 0.
 #pragma once
-#include <hip/hip_runtime.h>
-
+#include <cstddef>
 #include <cstdint>
+#include <string>
+#include <vector>
 
 namespace daris {
 
@@ -67,34 +69,64 @@ struct ConvPlan {
   int tn, nw, S, sz, sw, MT, NTn, G, xmode;
   int tiles;                       // output tiles per grid.z slice
   size_t ws_bytes;                 // split-K workspace this launch needs
-  dim3 grid;
+  uint32_t grid_x;                 // workgroups of the launch
   int threads;
 };
 // bf16 = 0/1.  Chooses tile shape, waves per workgroup and split-K from (M, N, Kpad) only, so results do not depend on the
 // partition a stage runs in.
 ConvPlan plan_conv(int M, int N, int Kpad, int bf16);
-
-// If t0/t1 are given they are recorded on `s` immediately before and after the main kernel (not the split-K reduce).
-hipError_t launch_conv(const ConvPlan& pl, const ConvArgs& a, int bf16, hipStream_t s, hipEvent_t t0 = nullptr, hipEvent_t t1 = nullptr);
-// Plan for a second convolution that is to share a launch with `first` (launch_conv_pair): the same wave-tile kernel
-// variant, K not split across workgroups.  Returns a plan with kernel == K_NONE when that is not possible.
+// Plan for a second convolution that is to share a launch with `first`: the same wave-tile kernel variant, K not split
+// across workgroups.  Returns a plan with kernel == K_NONE when that is not possible.
 ConvPlan plan_conv_like(const ConvPlan& first, int M, int N, int Kpad, int bf16);
-// One launch for two independent convolutions: pl0/a0 as planned by plan_conv, pl1/a1 by
-// plan_conv_like(pl0, ...).  The event pair brackets the joint kernel.
-hipError_t launch_conv_pair(const ConvPlan& pl0, const ConvArgs& a0, const ConvPlan& pl1, const ConvArgs& a1, int bf16, hipStream_t s,
-                            hipEvent_t t0 = nullptr, hipEvent_t t1 = nullptr);
 // Multiplier for fast_div: floor(2^32 / d) + 1, or 0 for d == 1.  Exact for every n >= 0 with n * d < 2^32.
 inline uint32_t div_magic(uint32_t d) { return d <= 1 ? 0u : (uint32_t)((1ull << 32) / d) + 1u; }
 
-hipError_t launch_dwconv(const DwArgs& a, int bf16, hipStream_t s);
-hipError_t launch_maxpool(const PoolArgs& a, int bf16, hipStream_t s);
-hipError_t launch_gavgpool(const PoolArgs& a, int bf16, hipStream_t s);
-hipError_t launch_fc(const FcArgs& a, int bf16, hipStream_t s);
+// ---- launches ------------------------------------------------------------------------------------------------------------
+//
+// The kernels are dispatched by AQL packets written by the library itself (aql.h).  An encoder turns the arguments of
+// a layer into one or two Launch records: kernel, geometry and the exact argument bytes the kernel expects.
+
+struct AqlKernel;
+class AqlRuntime;
+
+struct KernelLaunch {
+  const AqlKernel* k = nullptr;
+  uint32_t groups = 0, threads = 0;  // workgroups, threads per workgroup
+  uint32_t nbytes = 0;               // bytes of args in use
+  int32_t kernel_id = K_NONE;
+  alignas(8) unsigned char args[336];
+};
+
+// Every kernel of the code object, looked up once.
+struct KernelTable {
+  const AqlKernel* conv[2][6][3] = {};  // [bf16][(tn - 1) * 3 + log2(nw) - 1][gather mode]
+  const AqlKernel* pair[2][6][2] = {};
+  const AqlKernel *reduce[2] = {}, *dwconv[2] = {}, *maxpool[2] = {}, *gavgpool[2] = {}, *fc[2] = {}, *ingest[2] = {}, *egress[2] = {};
+  const AqlKernel* cu_probe = nullptr;
+  // "" or the name of the first kernel that is missing or whose argument size is not what this header declares
+  std::string resolve(const AqlRuntime& rt);
+};
+
+// Dense convolution: the main kernel, then the split-K reduction if the plan has one.  False on an inconsistent plan.
+bool encode_conv(const KernelTable& kt, const ConvPlan& pl, const ConvArgs& a, int bf16, std::vector<KernelLaunch>* out);
+// Two independent convolutions in one launch: pl0/a0 as planned by plan_conv, pl1/a1 by plan_conv_like(pl0, ...).
+bool encode_conv_pair(const KernelTable& kt, const ConvPlan& pl0, const ConvArgs& a0, const ConvPlan& pl1, const ConvArgs& a1, int bf16,
+                      std::vector<KernelLaunch>* out);
+bool encode_dwconv(const KernelTable& kt, const DwArgs& a, int bf16, std::vector<KernelLaunch>* out);
+bool encode_maxpool(const KernelTable& kt, const PoolArgs& a, int bf16, std::vector<KernelLaunch>* out);
+bool encode_gavgpool(const KernelTable& kt, const PoolArgs& a, int bf16, std::vector<KernelLaunch>* out);
+bool encode_fc(const KernelTable& kt, const FcArgs& a, int bf16, std::vector<KernelLaunch>* out);
 // x: float [C][H][W] -> y: [H][W][Cs]
-hipError_t launch_ingest(const float* x, void* y, int C, int Cs, int H, int W, int bf16, hipStream_t s);
+bool encode_ingest(const KernelTable& kt, const float* x, void* y, int C, int Cs, int H, int W, int bf16, std::vector<KernelLaunch>* out);
 // x: [H][W][Cs] -> y: float [C][H][W]
-hipError_t launch_egress(const void* x, float* y, int C, int Cs, int H, int W, int bf16, hipStream_t s);
+bool encode_egress(const KernelTable& kt, const void* x, float* y, int C, int Cs, int H, int W, int bf16, std::vector<KernelLaunch>* out);
 // Records, per workgroup, the XCC id and the hardware id register of the CU it ran on (mask probing).
-hipError_t launch_cu_probe(uint32_t* out, int n_groups, int spin, hipStream_t s);
+bool encode_cu_probe(const KernelTable& kt, uint32_t* out_dev, int n_groups, int spin, std::vector<KernelLaunch>* out);
+
+// Byte offsets inside a launch's argument block of the pointers that change from job to job.
+constexpr uint32_t kConvInputOffset = 0;     // ConvArgs::x (layer 0 gathering from the job's input)
+constexpr uint32_t kIngestInputOffset = 0;   // ingest: x
+constexpr uint32_t kFcOutputOffset = 24;     // FcArgs::y
+constexpr uint32_t kEgressOutputOffset = 8;  // egress: y
 
 }  // namespace daris

@@ -2,12 +2,11 @@
 // and a fused bias / residual / activation epilogue, split-K reduction, depthwise convolution, pooling, FC
 // (batch-1 GEMV), and the NCHW<->NHWC boundary conversions.  A DNN is, for the scheduler of the paper
 // (Sec. I, Sec. III-B1), a sequence of such kernels cut into stages.
-#include "kernels.h"
+#include <hip/hip_runtime.h>
 
 #include <type_traits>
 
-#include <cstdlib>
-#include <cstring>
+#include "kernels.h"
 
 namespace daris {
 
@@ -556,220 +555,26 @@ __global__ __launch_bounds__(64) void cu_probe_kernel(uint32_t* out, int spin) {
   }
 }
 
-// ---- host side -----------------------------------------------------------------------------------------------------------------
-
-static const char* const kNames[K_COUNT] = {
-    "none",
-    "conv_wave_f32_t1w2", "conv_wave_f32_t1w4", "conv_wave_f32_t1w8", "conv_wave_f32_t2w2", "conv_wave_f32_t2w4", "conv_wave_f32_t2w8",
-    "conv_wave_bf16_t1w2", "conv_wave_bf16_t1w4", "conv_wave_bf16_t1w8", "conv_wave_bf16_t2w2", "conv_wave_bf16_t2w4", "conv_wave_bf16_t2w8",
-    "splitk_reduce", "dwconv", "maxpool", "gavgpool", "fc", "ingest", "egress"};
-
-const char* kernel_name(int32_t id) { return (id >= 0 && id < K_COUNT) ? kNames[id] : "?"; }
-
-static inline int cdiv(int a, int b) { return (a + b - 1) / b; }
-
-static const int kNominalWaveSlots = 512;  // 128 CUs x 4 SIMDs: the partition size the plans are tuned for
-
-static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16, int force_tn = 0, int force_nw = 0) {
-  // Measured on a 128-CU partition (fp32, ResNet-18 shapes): the K loop itself runs near the MFMA rate; what a
-  // launch pays for is its fixed cost and idle CUs.  Best found: 8 waves per workgroup splitting K, and enough
-  // grid.z slices that tiles * z is about the number of CUs, while a wave keeps at least ~6 steps.
-  ConvPlan pl = ConvPlan();
-  const int ks = bf16 ? 16 : 8;  // k per step: two 16-byte vectors
-  const int S = Kpad / ks;
-  const int nb = cdiv(N, 32);
-  // A wave tile two channel blocks wide halves the reads of the pixel operand, but also halves the number of tiles:
-  // below about 3/4 of the partition's CUs it is better to keep 32-channel tiles and split K less (or not at all,
-  // which saves the reduction launch).
-  int tn = (nb % 2 == 0 && cdiv(M, 32) * (nb / 2) >= 96) ? 2 : 1;
-  if (const char* e = getenv("DARIS_W_TN")) tn = (atoi(e) == 2 && nb % 2 == 0) ? 2 : 1;
-  if (force_tn) tn = force_tn;
-  const int tiles = cdiv(M, 32) * (nb / tn);
-  const int nominal_cus = kNominalWaveSlots / 4;
-  int nw = bf16 ? 4 : 8;  // bf16 steps are short: fewer waves to sum through LDS beat a finer K split (measured 0.4-0.8 us per layer)
-  while (nw > 2 && (S / nw < 4 || tiles * nw > 8 * kNominalWaveSlots)) nw /= 2;  // >= 4 steps per wave, <= 8 waves per SIMD
-  int z = nominal_cus / tiles;
-  if (z < 1) z = 1;
-  const int max_by_k = S / (nw * 6) > 0 ? S / (nw * 6) : 1;
-  if (z > max_by_k) z = max_by_k;
-  if (z > 16) z = 16;
-  if (tiles > nominal_cus) {
-    // More tiles than CUs: the launch runs in ceil(tiles * z / CUs) rounds of workgroups whose K loops take
-    // (S / z) * tn * c cycles of MFMA time per SIMD, so a K split can even out the last round (200 tiles: z = 1 and 2
-    // need the time of 2 whole tiles, z = 3 that of 5/3).  Model checked against measured VGG-16 layers (within 3 %):
-    // loop time x 1.3 + a reduction pass of 3 us + its traffic at 1.5 TB/s.
-    const double cyc = bf16 ? tn * 8.0 : tn * 64.0;
-    double best = 1e30;
-    for (int zz = 1; zz <= 6 && S / (nw * zz) >= 6; ++zz) {
-      const double rounds = (double)cdiv(tiles * zz, nominal_cus);
-      double us = 1.3 * rounds * cdiv(S, zz) * cyc / 2400.0;
-      if (zz > 1) us += 3.0 + (double)zz * M * N * 4.0 / 1.5e6;
-      if (us < best) {
-        best = us;
-        z = zz;
-      }
-    }
-  }
-  if (const char* e = getenv("DARIS_W_NW")) {
-    const int v = atoi(e);
-    if (v == 2 || v == 4 || v == 8) nw = v;
-  }
-  if (const char* e = getenv("DARIS_W_Z")) z = atoi(e) < S ? atoi(e) : S;
-  if (force_nw) {  // second problem of a two-problem launch: the first one's kernel variant, no split across workgroups
-    nw = force_nw;
-    z = 1;
-  }
-  const int sz = cdiv(S, z);
-  z = cdiv(S, sz);
-  pl.tn = tn;
-  pl.nw = nw;
-  pl.S = S;
-  pl.sz = sz;
-  pl.sw = cdiv(sz, nw);
-  pl.splitk = z;
-  pl.tiles = tiles;
-  pl.threads = nw * 64;
-  pl.MT = cdiv(M, 32);  // (the division multipliers are filled in by the caller, which knows Wo, Cin and kw)
-  pl.NTn = nb / tn;
-  pl.G = pl.NTn * z;
-  if (pl.G % 8 == 0) {
-    pl.xmode = 1;
-    pl.grid = dim3(pl.G * pl.MT, 1, 1);
-  } else if (8 % pl.G == 0) {
-    pl.xmode = 2;
-    pl.grid = dim3(8 * cdiv(pl.MT, 8 / pl.G), 1, 1);
-  } else {
-    pl.xmode = 0;
-    pl.grid = dim3(pl.G * pl.MT, 1, 1);
-  }
-  if (getenv("DARIS_W_XMODE0")) {
-    pl.xmode = 0;
-    pl.grid = dim3(pl.G * pl.MT, 1, 1);
-  }
-  pl.ws_bytes = z > 1 ? (size_t)z * M * N * sizeof(float) : 0;
-  const int wi = nw == 2 ? 0 : (nw == 4 ? 1 : 2);
-  pl.kernel = (bf16 ? K_CONVW_BF16_T1W2 : K_CONVW_F32_T1W2) + (tn - 1) * 3 + wi;
-  return pl;
-}
-
-ConvPlan plan_conv(int M, int N, int Kpad, int bf16) { return plan_conv_wave(M, N, Kpad, bf16); }
-
-ConvPlan plan_conv_like(const ConvPlan& first, int M, int N, int Kpad, int bf16) {
-  ConvPlan none = ConvPlan();
-  if (cdiv(N, 32) % first.tn != 0) return none;
-  return plan_conv_wave(M, N, Kpad, bf16, first.tn, first.nw);
-}
-
-template <bool BF16>
-static hipError_t launch_conv_t(const ConvPlan& pl, const ConvArgs& a, hipStream_t s, hipEvent_t t0, hipEvent_t t1) {
-  if (t0) (void)hipEventRecord(t0, s);
-  {
-    const int variant = pl.kernel - (BF16 ? K_CONVW_BF16_T1W2 : K_CONVW_F32_T1W2);
-    // 0: a K step never straddles a filter tap; 1: general walk; 2: layer 0 reading the caller's fp32 [C][H][W] input
-    const int mode = a.c_real > 0 ? 2 : (a.Cin % (BF16 ? 16 : 8) == 0 ? 0 : 1);
-    if (mode == 2 && (a.Cin != (BF16 ? 8 : 4) || a.c_real > 4)) return hipErrorInvalidValue;
-#define DARIS_WAVE_CASE(idx, TN_, NW_)                                                                            \
-  case idx:                                                                                                       \
-    if (mode == 0) hipLaunchKernelGGL((conv_wave_kernel<BF16, TN_, NW_, 0>), pl.grid, dim3(NW_ * 64), 0, s, a);     \
-    else if (mode == 1) hipLaunchKernelGGL((conv_wave_kernel<BF16, TN_, NW_, 1>), pl.grid, dim3(NW_ * 64), 0, s, a); \
-    else hipLaunchKernelGGL((conv_wave_kernel<BF16, TN_, NW_, 2>), pl.grid, dim3(NW_ * 64), 0, s, a);               \
-    break;
-    switch (variant) {
-      DARIS_WAVE_CASE(0, 1, 2)
-      DARIS_WAVE_CASE(1, 1, 4)
-      DARIS_WAVE_CASE(2, 1, 8)
-      DARIS_WAVE_CASE(3, 2, 2)
-      DARIS_WAVE_CASE(4, 2, 4)
-      DARIS_WAVE_CASE(5, 2, 8)
-      default: return hipErrorInvalidValue;
-    }
-#undef DARIS_WAVE_CASE
-  }
-  hipError_t e = hipGetLastError();
-  if (t1) (void)hipEventRecord(t1, s);
-  if (e != hipSuccess) return e;
-  if (pl.splitk > 1) {
-    const size_t total4 = (size_t)a.M * a.Cout / 4;
-    hipLaunchKernelGGL((splitk_reduce_kernel<BF16>), dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, s, a.ws, a.bias,
-                       a.res, a.y, a.M, a.Cout, pl.splitk, a.act);
-    e = hipGetLastError();
-  }
-  return e;
-}
-
-template <bool BF16>
-static hipError_t launch_conv_pair_t(const ConvPlan& pl0, const ConvArgs& a0, const ConvPlan& pl1, const ConvArgs& a1, hipStream_t s,
-                                     hipEvent_t t0, hipEvent_t t1) {
-  const int ks = BF16 ? 16 : 8;
-  const bool aligned = a0.Cin % ks == 0;
-  if (pl0.kernel != pl1.kernel || aligned != (a1.Cin % ks == 0) || pl1.splitk != 1 || a0.c_real > 0 || a1.c_real > 0)
-    return hipErrorInvalidValue;
-  const int n0 = (int)(pl0.grid.x + 7) / 8 * 8;
-  const dim3 grid(n0 + pl1.grid.x, 1, 1);
-  const int variant = pl0.kernel - (BF16 ? K_CONVW_BF16_T1W2 : K_CONVW_F32_T1W2);
-  if (t0) (void)hipEventRecord(t0, s);
-#define DARIS_PAIR_CASE(idx, TN_, NW_)                                                                                     \
-  case idx:                                                                                                                \
-    if (aligned) hipLaunchKernelGGL((conv_wave_pair_kernel<BF16, TN_, NW_, 0>), grid, dim3(NW_ * 64), 0, s, a0, a1, n0); \
-    else hipLaunchKernelGGL((conv_wave_pair_kernel<BF16, TN_, NW_, 1>), grid, dim3(NW_ * 64), 0, s, a0, a1, n0);        \
-    break;
-  switch (variant) {
-    DARIS_PAIR_CASE(0, 1, 2)
-    DARIS_PAIR_CASE(1, 1, 4)
-    DARIS_PAIR_CASE(2, 1, 8)
-    DARIS_PAIR_CASE(3, 2, 2)
-    DARIS_PAIR_CASE(4, 2, 4)
-    DARIS_PAIR_CASE(5, 2, 8)
-    default: return hipErrorInvalidValue;
-  }
-#undef DARIS_PAIR_CASE
-  hipError_t e = hipGetLastError();
-  if (t1) (void)hipEventRecord(t1, s);
-  if (e != hipSuccess) return e;
-  if (pl0.splitk > 1) {
-    const size_t total4 = (size_t)a0.M * a0.Cout / 4;
-    hipLaunchKernelGGL((splitk_reduce_kernel<BF16>), dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, s, a0.ws, a0.bias,
-                       a0.res, a0.y, a0.M, a0.Cout, pl0.splitk, a0.act);
-    e = hipGetLastError();
-  }
-  return e;
-}
-
-hipError_t launch_conv_pair(const ConvPlan& pl0, const ConvArgs& a0, const ConvPlan& pl1, const ConvArgs& a1, int bf16, hipStream_t s,
-                            hipEvent_t t0, hipEvent_t t1) {
-  return bf16 ? launch_conv_pair_t<true>(pl0, a0, pl1, a1, s, t0, t1) : launch_conv_pair_t<false>(pl0, a0, pl1, a1, s, t0, t1);
-}
-
-hipError_t launch_conv(const ConvPlan& pl, const ConvArgs& a, int bf16, hipStream_t s, hipEvent_t t0, hipEvent_t t1) {
-  return bf16 ? launch_conv_t<true>(pl, a, s, t0, t1) : launch_conv_t<false>(pl, a, s, t0, t1);
-}
-
-#define DARIS_LAUNCH_1D(kern, total, ...)                                                                   \
-  do {                                                                                                      \
-    const size_t total_ = (total);                                                                          \
-    if (total_ == 0) return hipSuccess;                                                                     \
-    if (bf16) hipLaunchKernelGGL((kern<true>), dim3((unsigned)((total_ + 255) / 256)), dim3(256), 0, s, __VA_ARGS__); \
-    else hipLaunchKernelGGL((kern<false>), dim3((unsigned)((total_ + 255) / 256)), dim3(256), 0, s, __VA_ARGS__);     \
-    return hipGetLastError();                                                                               \
-  } while (0)
-
-hipError_t launch_dwconv(const DwArgs& a, int bf16, hipStream_t s) {
-  DARIS_LAUNCH_1D(dwconv_kernel, (size_t)a.Ho * a.Wo * (a.C / (bf16 ? 8 : 4)), a);
-}
-hipError_t launch_maxpool(const PoolArgs& a, int bf16, hipStream_t s) {
-  DARIS_LAUNCH_1D(maxpool_kernel, (size_t)a.Ho * a.Wo * (a.C / (bf16 ? 8 : 4)), a);
-}
-hipError_t launch_gavgpool(const PoolArgs& a, int bf16, hipStream_t s) { DARIS_LAUNCH_1D(gavgpool_kernel, (size_t)cdiv(a.C, 64) * 256, a); }
-hipError_t launch_fc(const FcArgs& a, int bf16, hipStream_t s) { DARIS_LAUNCH_1D(fc_kernel, (size_t)cdiv(a.Ns, 4) * 256, a); }
-hipError_t launch_ingest(const float* x, void* y, int C, int Cs, int H, int W, int bf16, hipStream_t s) {
-  DARIS_LAUNCH_1D(ingest_kernel, (size_t)H * W * Cs, x, y, C, Cs, H * W);
-}
-hipError_t launch_egress(const void* x, float* y, int C, int Cs, int H, int W, int bf16, hipStream_t s) {
-  DARIS_LAUNCH_1D(egress_kernel, (size_t)H * W * C, x, y, C, Cs, H * W);
-}
-hipError_t launch_cu_probe(uint32_t* out, int n_groups, int spin, hipStream_t s) {
-  hipLaunchKernelGGL(cu_probe_kernel, dim3(n_groups), dim3(64), 0, s, out, spin);
-  return hipGetLastError();
-}
+// ---- explicit instantiations: the host never references the kernels (they are dispatched by name from the code object) --------
+#define DARIS_INST_CONV(B, TN_, NW_)                                                              \
+  template __global__ void conv_wave_kernel<B, TN_, NW_, 0>(const ConvArgs);                      \
+  template __global__ void conv_wave_kernel<B, TN_, NW_, 1>(const ConvArgs);                      \
+  template __global__ void conv_wave_kernel<B, TN_, NW_, 2>(const ConvArgs);                      \
+  template __global__ void conv_wave_pair_kernel<B, TN_, NW_, 0>(const ConvArgs, const ConvArgs, const int); \
+  template __global__ void conv_wave_pair_kernel<B, TN_, NW_, 1>(const ConvArgs, const ConvArgs, const int);
+#define DARIS_INST_ALL(B)                                                                          \
+  DARIS_INST_CONV(B, 1, 2) DARIS_INST_CONV(B, 1, 4) DARIS_INST_CONV(B, 1, 8)                        \
+  DARIS_INST_CONV(B, 2, 2) DARIS_INST_CONV(B, 2, 4) DARIS_INST_CONV(B, 2, 8)                        \
+  template __global__ void splitk_reduce_kernel<B>(const float*, const float*, const void*, void*, int, int, int, int); \
+  template __global__ void dwconv_kernel<B>(const DwArgs);                                         \
+  template __global__ void maxpool_kernel<B>(const PoolArgs);                                      \
+  template __global__ void gavgpool_kernel<B>(const PoolArgs);                                     \
+  template __global__ void fc_kernel<B>(const FcArgs);                                             \
+  template __global__ void ingest_kernel<B>(const float*, void*, int, int, int);                   \
+  template __global__ void egress_kernel<B>(const void*, float*, int, int, int);
+DARIS_INST_ALL(false)
+DARIS_INST_ALL(true)
+#undef DARIS_INST_ALL
+#undef DARIS_INST_CONV
 
 }  // namespace daris

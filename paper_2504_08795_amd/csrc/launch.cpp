@@ -1,0 +1,256 @@
+// Host side of the kernels: names, launch plans of the convolutions, and the encoders that turn a layer's arguments
+// into ready-to-dispatch launches (kernel, geometry, argument bytes).
+#include "kernels.h"
+
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+
+#include "aql.h"
+
+namespace daris {
+
+static const char* const kNames[K_COUNT] = {
+    "none",
+    "conv_wave_f32_t1w2", "conv_wave_f32_t1w4", "conv_wave_f32_t1w8", "conv_wave_f32_t2w2", "conv_wave_f32_t2w4", "conv_wave_f32_t2w8",
+    "conv_wave_bf16_t1w2", "conv_wave_bf16_t1w4", "conv_wave_bf16_t1w8", "conv_wave_bf16_t2w2", "conv_wave_bf16_t2w4", "conv_wave_bf16_t2w8",
+    "splitk_reduce", "dwconv", "maxpool", "gavgpool", "fc", "ingest", "egress"};
+
+const char* kernel_name(int32_t id) { return (id >= 0 && id < K_COUNT) ? kNames[id] : "?"; }
+
+static inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+static const int kNominalWaveSlots = 512;  // 128 CUs x 4 SIMDs: the partition size the plans are tuned for
+
+static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16, int force_tn = 0, int force_nw = 0) {
+  // Measured on a 128-CU partition (fp32, ResNet-18 shapes): the K loop itself runs near the MFMA rate; what a
+  // launch pays for is its fixed cost and idle CUs.  Best found: 8 waves per workgroup splitting K, and enough
+  // grid.z slices that tiles * z is about the number of CUs, while a wave keeps at least ~6 steps.
+  ConvPlan pl = ConvPlan();
+  const int ks = bf16 ? 16 : 8;  // k per step: two 16-byte vectors
+  const int S = Kpad / ks;
+  const int nb = cdiv(N, 32);
+  // A wave tile two channel blocks wide halves the reads of the pixel operand, but also halves the number of tiles:
+  // below about 3/4 of the partition's CUs it is better to keep 32-channel tiles and split K less (or not at all,
+  // which saves the reduction launch).
+  int tn = (nb % 2 == 0 && cdiv(M, 32) * (nb / 2) >= 96) ? 2 : 1;
+  if (const char* e = getenv("DARIS_W_TN")) tn = (atoi(e) == 2 && nb % 2 == 0) ? 2 : 1;
+  if (force_tn) tn = force_tn;
+  const int tiles = cdiv(M, 32) * (nb / tn);
+  const int nominal_cus = kNominalWaveSlots / 4;
+  int nw = bf16 ? 4 : 8;  // bf16 steps are short: fewer waves to sum through LDS beat a finer K split (measured 0.4-0.8 us per layer)
+  while (nw > 2 && (S / nw < 4 || tiles * nw > 8 * kNominalWaveSlots)) nw /= 2;  // >= 4 steps per wave, <= 8 waves per SIMD
+  int z = nominal_cus / tiles;
+  if (z < 1) z = 1;
+  const int max_by_k = S / (nw * 6) > 0 ? S / (nw * 6) : 1;
+  if (z > max_by_k) z = max_by_k;
+  if (z > 16) z = 16;
+  if (tiles > nominal_cus) {
+    // More tiles than CUs: the launch runs in ceil(tiles * z / CUs) rounds of workgroups whose K loops take
+    // (S / z) * tn * c cycles of MFMA time per SIMD, so a K split can even out the last round (200 tiles: z = 1 and 2
+    // need the time of 2 whole tiles, z = 3 that of 5/3).  Model checked against measured VGG-16 layers (within 3 %):
+    // loop time x 1.3 + a reduction pass of 3 us + its traffic at 1.5 TB/s.
+    const double cyc = bf16 ? tn * 8.0 : tn * 64.0;
+    double best = 1e30;
+    for (int zz = 1; zz <= 6 && S / (nw * zz) >= 6; ++zz) {
+      const double rounds = (double)cdiv(tiles * zz, nominal_cus);
+      double us = 1.3 * rounds * cdiv(S, zz) * cyc / 2400.0;
+      if (zz > 1) us += 3.0 + (double)zz * M * N * 4.0 / 1.5e6;
+      if (us < best) {
+        best = us;
+        z = zz;
+      }
+    }
+  }
+  if (const char* e = getenv("DARIS_W_NW")) {
+    const int v = atoi(e);
+    if (v == 2 || v == 4 || v == 8) nw = v;
+  }
+  if (const char* e = getenv("DARIS_W_Z")) z = atoi(e) < S ? atoi(e) : S;
+  if (force_nw) {  // second problem of a two-problem launch: the first one's kernel variant, no split across workgroups
+    nw = force_nw;
+    z = 1;
+  }
+  const int sz = cdiv(S, z);
+  z = cdiv(S, sz);
+  pl.tn = tn;
+  pl.nw = nw;
+  pl.S = S;
+  pl.sz = sz;
+  pl.sw = cdiv(sz, nw);
+  pl.splitk = z;
+  pl.tiles = tiles;
+  pl.threads = nw * 64;
+  pl.MT = cdiv(M, 32);  // (the division multipliers are filled in by the caller, which knows Wo, Cin and kw)
+  pl.NTn = nb / tn;
+  pl.G = pl.NTn * z;
+  if (pl.G % 8 == 0) {
+    pl.xmode = 1;
+    pl.grid_x = (uint32_t)(pl.G * pl.MT);
+  } else if (8 % pl.G == 0) {
+    pl.xmode = 2;
+    pl.grid_x = (uint32_t)(8 * cdiv(pl.MT, 8 / pl.G));
+  } else {
+    pl.xmode = 0;
+    pl.grid_x = (uint32_t)(pl.G * pl.MT);
+  }
+  if (getenv("DARIS_W_XMODE0")) {
+    pl.xmode = 0;
+    pl.grid_x = (uint32_t)(pl.G * pl.MT);
+  }
+  pl.ws_bytes = z > 1 ? (size_t)z * M * N * sizeof(float) : 0;
+  const int wi = nw == 2 ? 0 : (nw == 4 ? 1 : 2);
+  pl.kernel = (bf16 ? K_CONVW_BF16_T1W2 : K_CONVW_F32_T1W2) + (tn - 1) * 3 + wi;
+  return pl;
+}
+
+ConvPlan plan_conv(int M, int N, int Kpad, int bf16) { return plan_conv_wave(M, N, Kpad, bf16); }
+
+ConvPlan plan_conv_like(const ConvPlan& first, int M, int N, int Kpad, int bf16) {
+  ConvPlan none = ConvPlan();
+  if (cdiv(N, 32) % first.tn != 0) return none;
+  return plan_conv_wave(M, N, Kpad, bf16, first.tn, first.nw);
+}
+
+
+// ---- kernel table ------------------------------------------------------------------------------------------------------------
+
+namespace {
+
+struct ReduceArgs {  // splitk_reduce_kernel(ws, bias, res, y, M, N, splitk, act)
+  const float* ws;
+  const float* bias;
+  const void* res;
+  void* y;
+  int M, N, splitk, act;
+};
+struct IngestArgs {  // ingest_kernel / egress_kernel (x, y, C, Cs, HW)
+  const void* x;
+  void* y;
+  int C, Cs, HW;
+};
+struct ProbeArgs {  // cu_probe_kernel(out, spin)
+  uint32_t* out;
+  int spin;
+};
+struct PairArgs {  // conv_wave_pair_kernel(p0, p1, n0)
+  ConvArgs p0, p1;
+  int n0;
+};
+constexpr uint32_t kIngestBytes = 28, kProbeBytes = 12, kPairBytes = 2 * sizeof(ConvArgs) + 4;
+static_assert(sizeof(ConvArgs) == 160 && sizeof(DwArgs) == 72 && sizeof(PoolArgs) == 48 && sizeof(FcArgs) == 56 && sizeof(ReduceArgs) == 48,
+              "argument structures must match what the kernels were compiled for");
+static_assert(offsetof(ConvArgs, x) == kConvInputOffset && offsetof(FcArgs, y) == kFcOutputOffset && offsetof(IngestArgs, x) == kIngestInputOffset &&
+                  offsetof(IngestArgs, y) == kEgressOutputOffset && offsetof(PairArgs, p1) == sizeof(ConvArgs) &&
+                  offsetof(PairArgs, n0) == 2 * sizeof(ConvArgs),
+              "argument offsets");
+
+bool push(std::vector<KernelLaunch>* out, const AqlKernel* k, int32_t id, uint32_t groups, uint32_t threads, const void* args, uint32_t nbytes) {
+  if (!k || k->kernarg_size != nbytes || nbytes > sizeof(KernelLaunch::args) || groups == 0) return false;
+  KernelLaunch l;
+  l.k = k;
+  l.kernel_id = id;
+  l.groups = groups;
+  l.threads = threads;
+  l.nbytes = nbytes;
+  std::memcpy(l.args, args, nbytes);
+  out->push_back(l);
+  return true;
+}
+
+}  // namespace
+
+std::string KernelTable::resolve(const AqlRuntime& rt) {
+  std::string missing;
+  auto get = [&](const std::string& name, uint32_t want_bytes) -> const AqlKernel* {
+    const AqlKernel* k = rt.kernel(name);
+    if ((!k || k->kernarg_size != want_bytes) && missing.empty())
+      missing = name + (k ? " (argument block of " + std::to_string(k->kernarg_size) + " bytes, expected " + std::to_string(want_bytes) + ")" : " (not in the code object)");
+    return k;
+  };
+  static const int tn_[6] = {1, 1, 1, 2, 2, 2}, nw_[6] = {2, 4, 8, 2, 4, 8};
+  for (int b = 0; b < 2; ++b) {
+    const std::string B = b ? "true" : "false";
+    for (int v = 0; v < 6; ++v) {
+      const std::string tp = B + ", " + std::to_string(tn_[v]) + ", " + std::to_string(nw_[v]) + ", ";
+      for (int m = 0; m < 3; ++m) conv[b][v][m] = get("daris::conv_wave_kernel<" + tp + std::to_string(m) + ">", sizeof(ConvArgs));
+      for (int m = 0; m < 2; ++m) pair[b][v][m] = get("daris::conv_wave_pair_kernel<" + tp + std::to_string(m) + ">", kPairBytes);
+    }
+    reduce[b] = get("daris::splitk_reduce_kernel<" + B + ">", sizeof(ReduceArgs));
+    dwconv[b] = get("daris::dwconv_kernel<" + B + ">", sizeof(DwArgs));
+    maxpool[b] = get("daris::maxpool_kernel<" + B + ">", sizeof(PoolArgs));
+    gavgpool[b] = get("daris::gavgpool_kernel<" + B + ">", sizeof(PoolArgs));
+    fc[b] = get("daris::fc_kernel<" + B + ">", sizeof(FcArgs));
+    ingest[b] = get("daris::ingest_kernel<" + B + ">", kIngestBytes);
+    egress[b] = get("daris::egress_kernel<" + B + ">", kIngestBytes);
+  }
+  cu_probe = get("daris::cu_probe_kernel", kProbeBytes);
+  return missing;
+}
+
+// ---- encoders ----------------------------------------------------------------------------------------------------------------
+
+static bool push_reduce(const KernelTable& kt, const ConvPlan& pl, const ConvArgs& a, int bf16, std::vector<KernelLaunch>* out) {
+  if (pl.splitk <= 1) return true;
+  const size_t total4 = (size_t)a.M * a.Cout / 4;
+  ReduceArgs r{a.ws, a.bias, a.res, a.y, a.M, a.Cout, pl.splitk, a.act};
+  return push(out, kt.reduce[bf16], K_SPLITK_REDUCE, (uint32_t)((total4 + 255) / 256), 256, &r, sizeof(r));
+}
+
+bool encode_conv(const KernelTable& kt, const ConvPlan& pl, const ConvArgs& a, int bf16, std::vector<KernelLaunch>* out) {
+  const int variant = pl.kernel - (bf16 ? K_CONVW_BF16_T1W2 : K_CONVW_F32_T1W2);
+  if (variant < 0 || variant >= 6 || pl.threads != 64 * pl.nw) return false;
+  // 0: a K step never straddles a filter tap; 1: general walk; 2: layer 0 reading the caller's fp32 [C][H][W] input
+  const int mode = a.c_real > 0 ? 2 : (a.Cin % (bf16 ? 16 : 8) == 0 ? 0 : 1);
+  if (mode == 2 && (a.Cin != (bf16 ? 8 : 4) || a.c_real > 4)) return false;
+  if (pl.splitk > 1 && !a.ws) return false;
+  if (!push(out, kt.conv[bf16][variant][mode], pl.kernel, pl.grid_x, (uint32_t)pl.threads, &a, sizeof(a))) return false;
+  return push_reduce(kt, pl, a, bf16, out);
+}
+
+bool encode_conv_pair(const KernelTable& kt, const ConvPlan& pl0, const ConvArgs& a0, const ConvPlan& pl1, const ConvArgs& a1, int bf16,
+                      std::vector<KernelLaunch>* out) {
+  const int ks = bf16 ? 16 : 8;
+  const bool aligned = a0.Cin % ks == 0;
+  if (pl0.kernel != pl1.kernel || aligned != (a1.Cin % ks == 0) || pl1.splitk != 1 || a0.c_real > 0 || a1.c_real > 0) return false;
+  const int variant = pl0.kernel - (bf16 ? K_CONVW_BF16_T1W2 : K_CONVW_F32_T1W2);
+  if (variant < 0 || variant >= 6 || (pl0.splitk > 1 && !a0.ws)) return false;
+  PairArgs pa;
+  std::memset(&pa, 0, sizeof(pa));
+  pa.p0 = a0;
+  pa.p1 = a1;
+  pa.n0 = (int)((pl0.grid_x + 7) / 8 * 8);  // the second problem starts at a multiple of 8: its workgroup -> XCD relation is kept
+  if (!push(out, kt.pair[bf16][variant][aligned ? 0 : 1], pl0.kernel, (uint32_t)pa.n0 + pl1.grid_x, (uint32_t)pl0.threads, &pa, kPairBytes)) return false;
+  return push_reduce(kt, pl0, a0, bf16, out);
+}
+
+bool encode_dwconv(const KernelTable& kt, const DwArgs& a, int bf16, std::vector<KernelLaunch>* out) {
+  const size_t total = (size_t)a.Ho * a.Wo * (a.C / (bf16 ? 8 : 4));
+  return push(out, kt.dwconv[bf16], K_DWCONV, (uint32_t)((total + 255) / 256), 256, &a, sizeof(a));
+}
+bool encode_maxpool(const KernelTable& kt, const PoolArgs& a, int bf16, std::vector<KernelLaunch>* out) {
+  const size_t total = (size_t)a.Ho * a.Wo * (a.C / (bf16 ? 8 : 4));
+  return push(out, kt.maxpool[bf16], K_MAXPOOL, (uint32_t)((total + 255) / 256), 256, &a, sizeof(a));
+}
+bool encode_gavgpool(const KernelTable& kt, const PoolArgs& a, int bf16, std::vector<KernelLaunch>* out) {
+  return push(out, kt.gavgpool[bf16], K_GAVGPOOL, (uint32_t)cdiv(a.C, 64), 256, &a, sizeof(a));
+}
+bool encode_fc(const KernelTable& kt, const FcArgs& a, int bf16, std::vector<KernelLaunch>* out) {
+  return push(out, kt.fc[bf16], K_FC, (uint32_t)cdiv(a.Ns, 4), 256, &a, sizeof(a));
+}
+bool encode_ingest(const KernelTable& kt, const float* x, void* y, int C, int Cs, int H, int W, int bf16, std::vector<KernelLaunch>* out) {
+  IngestArgs a{x, y, C, Cs, H * W};
+  const size_t total = (size_t)H * W * Cs;
+  return push(out, kt.ingest[bf16], K_INGEST, (uint32_t)((total + 255) / 256), 256, &a, kIngestBytes);
+}
+bool encode_egress(const KernelTable& kt, const void* x, float* y, int C, int Cs, int H, int W, int bf16, std::vector<KernelLaunch>* out) {
+  IngestArgs a{x, y, C, Cs, H * W};
+  const size_t total = (size_t)H * W * C;
+  return push(out, kt.egress[bf16], K_EGRESS, (uint32_t)((total + 255) / 256), 256, &a, kIngestBytes);
+}
+bool encode_cu_probe(const KernelTable& kt, uint32_t* out_dev, int n_groups, int spin, std::vector<KernelLaunch>* out) {
+  ProbeArgs a{out_dev, spin};
+  return push(out, kt.cu_probe, K_NONE, (uint32_t)n_groups, 64, &a, kProbeBytes);
+}
+
+}  // namespace daris
