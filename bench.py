@@ -96,7 +96,7 @@ def main():
     D.daris_run_closed_loop([args.warmup * nt] * nt, args.warmup * nt)
     torch.cuda.synchronize()
     if not args.no_profile:
-        D.daris_kernel_timing_start(args.sample_every, 20000)   # HIP-event pairs around sampled conv launches, on their streams
+        D.daris_kernel_timing_start(args.sample_every, 20000)   # dispatch time stamps of every launch of the sampled jobs
     before = [D.daris_get_stats(i) for i in range(nt)]
     t0 = time.perf_counter()
     D.daris_run_closed_loop([args.steps * nt] * nt, args.steps * nt)
@@ -135,15 +135,17 @@ def main():
                         response_ms=pct)
 
     # ---- roofline of the dominant kernel --------------------------------------------------------------------------------
-    # Durations come from HIP-event pairs recorded on the partition streams around every dense-convolution launch of
-    # each `sample_every`-th job INSIDE the timed region above (three DNNs running concurrently on overlapping
-    # partitions).  FLOPs are the algorithmic 2*MACs of the layers those launches computed.
+    # Durations are the start and end time stamps that the command processor of the queue a kernel runs on writes into
+    # that dispatch's completion signal (the figures a kernel trace reports), for every launch of each
+    # `sample_every`-th job INSIDE the timed region above (three DNNs running concurrently on overlapping
+    # partitions).  On a queue that never runs dry a dispatch's start stamp follows its predecessor's end stamp
+    # directly, so the ~1.6 us the command processor needs per packet is inside these durations.  FLOPs are the
+    # algorithmic 2*MACs of the layers those launches computed.
     roofline = None
     if timing:
         dom = max(timing, key=lambda k: timing[k][1])
         n_launch, t_raw_ms, flops = timing[dom]
-        # an event pair with nothing inside already reads pair_ms (command-processor marker latency): take it out
-        t_ms = max(t_raw_ms - n_launch * pair_ms, 1e-9)
+        t_ms = max(t_raw_ms - n_launch * pair_ms, 1e-9)   # pair_ms: fixed cost of the timing method, 0 for time stamps
         achieved = flops / (t_ms * 1e-3) / 1e12
         layers = nets[0][0]
         ms, kid, fl = D.daris_profile_layers(0, 0, 20, len(layers))          # the same task alone, for reference
@@ -153,7 +155,7 @@ def main():
             e[0] += float(m)
             e[1] += 1
         roofline = dict(bound="mfma", kernel=dom, sampled_launches=n_launch, avg_launch_us=round(t_ms * 1e3 / n_launch, 3),
-                        avg_launch_us_raw_event_pair=round(t_raw_ms * 1e3 / n_launch, 3), empty_event_pair_us=round(pair_ms * 1e3, 3),
+                        timing="dispatch time stamps in completion signals",
                         achieved=round(achieved, 3), peak=PEAK_FP32_MFMA_TFLOPS, unit="TFLOP/s",
                         frac=round(achieved / PEAK_FP32_MFMA_TFLOPS, 5), traffic=read_traffic(dom),
                         all_sampled_kernels={k: dict(launches=v[0], avg_us=round((v[1] / v[0] - pair_ms) * 1e3, 3)) for k, v in timing.items()},

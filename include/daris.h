@@ -4,8 +4,8 @@
  * DARIS (Sec. III-IV of the paper) runs several periodic, two-priority DNN inference tasks concurrently on
  * partitions ("contexts") of one GPU.  A task's DNN is cut into sequential stages; a synchronisation point
  * at every stage boundary is the only preemption / migration point (Sec. III-B1).  Here a partition is a set
- * of compute units: a CU mask plus N_s CU-masked HIP streams; the sum of partition sizes may exceed the 256
- * CUs of the device (oversubscription, Sec. III-C2).
+ * of compute units: a CU mask plus N_s CU-masked hardware queues ("streams") that the library creates and feeds
+ * itself; the sum of partition sizes may exceed the 256 CUs of the device (oversubscription, Sec. III-C2).
  *
  * General rules
  *   - Every function returns a status (0 = DARIS_OK, negative = error) or a non-negative handle; nothing
@@ -13,7 +13,10 @@
  *   - All calls come from one API thread.  The library runs one internal scheduler thread in real-time mode.
  *   - "host" pointers are ordinary CPU memory, read during the call only (the library copies what it keeps).
  *     "device" pointers are HIP device memory owned by the caller, which must stay valid until the job that
- *     uses them has completed (daris_run_until_idle() or the blocking run calls return).
+ *     uses them has completed (daris_run_until_idle() or the blocking run calls return).  The library's kernels run
+ *     on queues of its own, not on a HIP stream: what the caller's streams wrote into an input buffer must be
+ *     complete (stream or device synchronised) before the job is released, and logits are complete and visible
+ *     to every HIP stream once the job has completed.
  *   - Times are int64 nanoseconds.  In virtual-time mode they are positions on the library's virtual clock;
  *     in real-time mode they count from the library's epoch (set by daris_commit()).
  *   - Utilisations (eq. 3-7) are evaluated in Q32 fixed point: u = floor(mret * 2^32 / T).
@@ -35,7 +38,7 @@ enum {
   DARIS_OK = 0,
   DARIS_EINVAL = -1, /* bad argument / unsupported layer shape */
   DARIS_ENOMEM = -2, /* host or device allocation failed */
-  DARIS_EHIP = -3,   /* a HIP runtime call failed (text in daris_last_error) */
+  DARIS_EHIP = -3,   /* a HIP or HSA runtime call failed (text in daris_last_error) */
   DARIS_ESTATE = -4, /* call not allowed in the current state (e.g. not initialised, already committed) */
   DARIS_ERANGE = -5  /* handle or index out of range */
 };
@@ -128,9 +131,10 @@ enum {
 /* ---- life cycle ------------------------------------------------------------------------------------------ */
 
 /* Select HIP device `device` and reset all library state.  `seed` is stored for reproducibility reports only
- * (the scheduler draws no random numbers).  Returns DARIS_ESTATE if already initialised. */
+ * (the scheduler draws no random numbers).  Returns DARIS_ESTATE if already initialised.  The first call with a
+ * device loads the kernels onto it; they stay there until the process ends, and later calls must name the same device. */
 daris_status daris_init(int device, uint64_t seed, int flags);
-/* Wait for running work, stop the scheduler thread, free every stream, event and device buffer. */
+/* Wait for running work, stop the worker threads, free every queue, signal and device buffer. */
 daris_status daris_shutdown(void);
 const char* daris_last_error(void);
 
@@ -200,7 +204,9 @@ daris_status daris_migrate(daris_task t, daris_part p);
 daris_status daris_run_until_idle(void);
 
 /* Per-task I/O pool for the library-driven runs below: job m reads input (m mod n_inputs) of d_inputs =
- * device float[n_inputs][c*h*w] and writes logits row (m mod n_slots) of d_logits = device float[n_slots][n_out]. */
+ * device float[n_inputs][c*h*w] and writes logits row (m mod n_slots) of d_logits = device float[n_slots][n_out].
+ * The kernel arguments that name these buffers are prepared here, once per buffer, in device memory.
+ * DARIS_ESTATE while a job of the task is active. */
 daris_status daris_task_set_io(daris_task t, const void* d_inputs, int32_t n_inputs, void* d_logits, int32_t n_slots);
 /* Release job m of task i at phase_ns[i] + m * T_i for m < n_jobs[i] (arrays indexed by task handle, host), in
  * (time, task) order, and return when every job has finished or was rejected. */
@@ -226,28 +232,29 @@ int64_t daris_get_mret(daris_task t, int stage);
 daris_status daris_forward(daris_task t, const void* d_input, void* d_logits, daris_part p);
 /* After daris_forward with DARIS_KEEP_ACTIVATIONS: copy layer l's output to host float[c][h][w]. */
 daris_status daris_read_layer(daris_task t, int layer, float* host_out, int64_t cap_elems);
-/* Time each layer of task t on stream 0 of partition p with HIP events, `reps` runs averaged.
+/* Time each layer of task t on stream 0 of partition p: `reps` runs back to back, from the start time stamp of the
+ * first dispatch to the end time stamp of the last, divided by reps (the earlier layer of a launch pair reports 0).
  * ms_per_layer = host float[n_layers]; kernel_id = host int32[n_layers] (which kernel variant ran, see
  * daris_kernel_name); flops = host double[n_layers] algorithmic FLOPs (2*MACs) of the layer. */
 daris_status daris_profile_layers(daris_task t, daris_part p, int reps, float* ms_per_layer, int32_t* kernel_id,
                                   double* flops);
 const char* daris_kernel_name(int32_t kernel_id);
 /* Kernel timing by sampling, for roofline figures measured inside a scheduled run: from now on every `every`-th job
- * of each task (0 = off) has each dense-convolution kernel bracketed by a pair of HIP events recorded on the stream
- * it is launched on (the split-K reduction kernel is outside the bracket), for at most max_samples launches. */
+ * of each task (0 = off) has every launch complete a signal of its own, into which the command processor of the
+ * queue the kernel runs on writes the start and end time stamp of that dispatch (the figures a kernel trace shows);
+ * for at most about max_samples launches.  Sampled jobs run slightly slower (one signal per launch). */
 daris_status daris_kernel_timing_start(int every, int max_samples);
 /* Waits until idle, stops the sampling and sums the samples per kernel id: launches[id], total_ms[id], total_flops[id]
  * (algorithmic FLOPs, 2*MACs) for id < the returned count; the arrays (host) must hold `cap` >= 64 entries.
- * *empty_pair_ms (may be NULL) receives what a pair of events with nothing between them reported on a partition
- * stream when the sampling was started (median of 65): the marker latency contained in every sample. */
+ * *empty_pair_ms (may be NULL) receives the fixed cost contained in every sample: 0 for dispatch time stamps. */
 int32_t daris_kernel_timing_read(int32_t cap, int64_t* launches, double* total_ms, double* total_flops, double* empty_pair_ms);
 /* Where the wall time of a stage goes in real-time mode (the price of the synchronisation point at each stage
  * boundary, Sec. III-B1).  Waits until idle, copies the totals gathered since the last call to out (host int64[8], may
- * be NULL), clears them, and switches the gathering on (enable != 0) or off.  While it is on, each stage is bracketed by
- * two extra timed events on its stream.  out[0] stages executed; [1] host ns enqueueing the stage's kernels and events;
- * [2] host ns from the last enqueue until the boundary event was seen; [3] host ns from then until the scheduler lock
- * was held; [4] host ns in the decision core and the hand-over of the next stages; [5] GPU ns between the two markers
- * (first kernel may start .. last kernel ended); [6] host ns between a dispatch pass handing a stage to a stream's
+ * be NULL), clears them, and switches the gathering on (enable != 0) or off.  While it is on, the first launch of each
+ * stage completes a signal too.  out[0] stages executed; [1] host ns enqueueing the stage's kernels;
+ * [2] host ns from the last enqueue until the completion signal was seen; [3] host ns from then until the scheduler lock
+ * was held; [4] host ns in the decision core and the hand-over of the next stages; [5] GPU ns from the start time stamp
+ * of the stage's first dispatch to the end time stamp of its last; [6] host ns between a dispatch pass handing a stage to a stream's
  * worker and the worker starting to enqueue it; [7] reserved. */
 daris_status daris_driver_profile(int enable, int64_t* out);
 /* Measure per-stage execution times of task t alone on partition p (`reps` runs, the maximum is kept) and store

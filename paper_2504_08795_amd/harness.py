@@ -170,10 +170,15 @@ def layer_profile(net, dtype, n_cu, reps=50):
         D.daris_forward(t, x, y, p)
         ms, kid, fl = D.daris_profile_layers(t, p, reps, len(layers))
         plans = [D.daris_get_launch_plan(t, l) for l in range(len(layers))]
+        # one job after the other through the scheduler (one stage per job, buffers of an I/O pool): the production path
+        xs = x.unsqueeze(0).contiguous()
+        ys = torch.zeros(4, layers[-1].c_out, device="cuda")
         torch.cuda.synchronize()
+        D.daris_task_set_io(t, xs, 1, ys, 4)
+        D.daris_calibrate_afet(t, p, 2)
+        D.daris_run_closed_loop([20], 0)
         t0 = time.perf_counter()
-        for _ in range(200):
-            D.daris_forward(t, x, y, p)
+        D.daris_run_closed_loop([200], 0)
         latency_us = (time.perf_counter() - t0) / 200 * 1e6
     finally:
         D.daris_shutdown()
@@ -194,7 +199,7 @@ def layer_profile(net, dtype, n_cu, reps=50):
                          bound="mfma" if fl[l] / (PEAK_TFLOPS[dtype] * 1e12) > by / (PEAK_HBM_GBS * 1e9) else "hbm",
                          t_roof_us=round(t_roof, 3), frac=round(t_roof / us, 4) if us > 0.2 else None,
                          joint_launch_with=plans[l]["pair_with"] if plans[l]["pair_with"] >= 0 else None))
-    return dict(net=net, dtype=dtype, n_cu=n_cu, kernel_time_us=round(float(sum(r["us"] for r in rows)), 1), forward_latency_us=round(latency_us, 1),
+    return dict(net=net, dtype=dtype, n_cu=n_cu, kernel_time_us=round(float(sum(r["us"] for r in rows)), 1), job_latency_us=round(latency_us, 1),
                 t_roof_us=round(sum(r["t_roof_us"] for r in rows), 2), layers=rows)
 
 
@@ -228,7 +233,7 @@ def main():
         if not a.table:
             print(json.dumps(r))
             return
-        print(f"{r['net']} {r['dtype']} alone on {r['n_cu']} CUs: kernels {r['kernel_time_us']} us, forward latency {r['forward_latency_us']} us, "
+        print(f"{r['net']} {r['dtype']} alone on {r['n_cu']} CUs: kernels {r['kernel_time_us']} us, job latency through the scheduler {r['job_latency_us']} us, "
               f"sum of layer rooflines {r['t_roof_us']} us\n")
         print("| # | layer | kernel | M | N | us | GFLOP | MB | TFLOP/s | GB/s | bound | t_roof us | frac |\n|---|---|---|---|---|---|---|---|---|---|---|---|---|")
         for x in r["layers"]:

@@ -166,6 +166,69 @@ def test_driver_profile_accounts_for_the_stages_it_saw():
         g.close()
 
 
+def test_kernel_timing_covers_every_launch_of_the_sampled_jobs():
+    """Sampling every job: each kernel id is counted once per launch of the network, the durations are the dispatch
+    time stamps (positive, microseconds), and together they fit into the stages' GPU spans; logits stay right."""
+    ts = wl.make_taskset(2, n_jobs=6)
+    g = GpuTaskSet(ts)
+    try:
+        for i in range(len(ts.tasks)):
+            D.daris_calibrate_afet(i, 0, 2)
+        D.daris_commit()
+        layers = g.nets[0][0]
+        plans = [D.daris_get_launch_plan(0, l) for l in range(len(layers))]
+        per_job = {}
+        for pl in plans:
+            if pl["pair_with"] >= 0 and not pl["pair_lead"]:
+                continue                                      # launched together with the next layer
+            name = D.daris_kernel_name(pl["kernel_id"])
+            per_job[name] = per_job.get(name, 0) + 1
+            splitk = max(pl["splitk"], plans[pl["pair_with"]]["splitk"]) if pl["pair_with"] >= 0 else pl["splitk"]
+            if pl["dense_conv"] and splitk > 1:
+                per_job["splitk_reduce"] = per_job.get("splitk_reduce", 0) + 1
+        D.daris_driver_profile(True)
+        D.daris_kernel_timing_start(1, 100000)
+        D.daris_run_closed_loop([6] * 4)
+        timing, fixed_ms = D.daris_kernel_timing_read()
+        pr = D.daris_driver_profile(False)
+        assert fixed_ms == 0.0
+        assert {k: v[0] for k, v in timing.items()} == {k: n * 4 * 6 for k, n in per_job.items()}
+        for name, (n, ms, fl) in timing.items():
+            assert 0.5e-3 < ms / n < 1.0, (name, ms / n)       # between half a microsecond and a millisecond per launch
+        assert sum(v[1] for v in timing.values()) * 1e6 <= pr["gpu_ns"] * 1.001
+        D.daris_run_closed_loop([2] * 4)
+        assert D.daris_kernel_timing_read()[0] == {}           # sampling was switched off by the read
+        outs = [l.cpu().numpy() for l in g.logits]
+        want = g.oracle_logits()
+        for task in range(4):
+            for job in range(2, 6):
+                assert rel_err(outs[task][job], want[task][job % ts.n_inputs])[0] <= TOL["fp32"]
+    finally:
+        g.close()
+
+
+def test_explicit_buffers_and_pool_buffers_give_the_same_logits():
+    """A job released with explicit device pointers (argument blocks patched at launch time) and a job of the I/O pool
+    (argument blocks prepared in device memory) run the same kernels on the same data: bit-identical logits."""
+    ts = wl.make_taskset(1, n_jobs=4)
+    g = GpuTaskSet(ts)
+    try:
+        for i in range(len(ts.tasks)):
+            D.daris_calibrate_afet(i, i % 2, 2)
+        D.daris_commit()
+        D.daris_run_periodic(None, [4] * len(ts.tasks))
+        pooled = [l.cpu().numpy().copy() for l in g.logits]
+        for task in range(len(ts.tasks)):
+            for job in range(4):
+                y = torch.full((g.logits[task].shape[1],), float("nan"), dtype=torch.float32, device="cuda")
+                torch.cuda.synchronize()
+                D.daris_release_job(task, g.inputs[task][job % ts.n_inputs], y, -1)
+                D.daris_run_until_idle()
+                assert np.array_equal(y.cpu().numpy(), pooled[task][job]), (task, job)
+    finally:
+        g.close()
+
+
 def test_cu_masks_are_honoured():
     """Workgroups launched on a partition's stream run only on as many distinct CUs as the partition owns."""
     D.daris_init(0, 0, 0)

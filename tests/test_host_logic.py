@@ -384,3 +384,33 @@ def test_overrun_and_hp_queue_order():
         tr = D.trace_read_all()
         started = [r[8] for r in tr if r[2] == D.T_ACCEPT and r[6] == 0]
         assert started == sorted(started) == list(range(6))
+
+
+def test_code_object_kernels_match_the_argument_structures():
+    """Every kernel of the device code object takes exactly the argument block the host encoders write (sizes of the
+    structures in csrc/kernels.h), needs no hidden arguments and no scratch: what a bare AQL packet can provide."""
+    import shutil
+    import subprocess
+    co = os.path.join(os.path.dirname(D.LIB_PATH), "csrc", "daris_kernels.co")
+    tool = shutil.which("llvm-readelf") or "/opt/rocm/llvm/bin/llvm-readelf"
+    if not (os.path.exists(co) and os.path.exists(tool)):
+        pytest.skip("code object or llvm-readelf not available")
+    notes = subprocess.run([tool, "--notes", co], check=True, capture_output=True, text=True).stdout
+    want = {"conv_wave_kernel": 160, "conv_wave_pair_kernel": 324, "splitk_reduce_kernel": 48, "dwconv_kernel": 72,
+            "maxpool_kernel": 48, "gavgpool_kernel": 48, "fc_kernel": 56, "ingest_kernel": 28, "egress_kernel": 28,
+            "cu_probe_kernel": 12}
+    seen = {}
+    assert "hidden_" not in notes
+    for block in notes.split(".agpr_count:")[1:]:
+        name = re.search(r"\.name:\s+(\S+)", block).group(1)
+        size = int(re.search(r"\.kernarg_segment_size:\s+(\d+)", block).group(1))
+        scratch = int(re.search(r"\.private_segment_fixed_size:\s+(\d+)", block).group(1))
+        lds = int(re.search(r"\.group_segment_fixed_size:\s+(\d+)", block).group(1))
+        base = [k for k in want if re.search(r"\d+" + k + r"(I|E)", name)]
+        assert len(base) == 1, name
+        assert size == want[base[0]], (name, size)
+        assert scratch == 0 and lds <= 65536, (name, scratch, lds)
+        seen[base[0]] = seen.get(base[0], 0) + 1
+    assert seen == {"conv_wave_kernel": 36, "conv_wave_pair_kernel": 24, "splitk_reduce_kernel": 2, "dwconv_kernel": 2,
+                    "maxpool_kernel": 2, "gavgpool_kernel": 2, "fc_kernel": 2, "ingest_kernel": 2, "egress_kernel": 2,
+                    "cu_probe_kernel": 1}
