@@ -38,6 +38,39 @@ def read_traffic(kernel):
     return None
 
 
+def cpu_oracle_report(threads_note):
+    """The CPU side of the measurement on its own: the oracle's forward pass per network (median of 3, on the threads
+    OMP_NUM_THREADS allows) and the oracle's discrete-event scheduler model in events/s.  No GPU is touched."""
+    import numpy as np
+    import workloads as wl
+    from oracle import des
+    from oracle import forward as F
+    nets = {}
+    for net, dtype in (("tiny", "fp32"), ("resnet18", "fp32"), ("resnet50", "bf16"), ("mobilenet_v2", "fp32"), ("vgg16", "fp32")):
+        layers, shp = wl.build_net(net)
+        weights = wl.make_weights(layers, 1)
+        x = wl.make_inputs(shp, 1, 1, "normal")[0]
+        F.forward(layers, weights, x, dtype)             # builds / loads the checker, warms the caches
+        ts = []
+        for _ in range(3):
+            t0 = time.perf_counter()
+            F.forward(layers, weights, x, dtype)
+            ts.append(time.perf_counter() - t0)
+            print(f"oracle {net} {dtype}: {ts[-1]:.3f} s", file=sys.stderr, flush=True)
+        nets[f"{net}_{dtype}"] = round(1.0 / float(np.median(ts)), 4)
+    # scheduler model: config 2 in virtual time, 400 jobs per task
+    tset = wl.make_taskset(2, n_jobs=400)
+    et = wl.virtual_et_table(tset, load_scale=25.0)
+    afet = [[int(np.mean(et[i][j][0][:8])) for j in range(t.n_stages)] for i, t in enumerate(tset.tasks)]
+    model = des.SchedulerModel([1] * len(tset.partitions), [des.TaskParam(t.period_ns, t.deadline_ns, t.priority, afet[i]) for i, t in enumerate(tset.tasks)])
+    cmds = [("release", t, i) for t, i, _ in tset.releases()]
+    t0 = time.perf_counter()
+    trace = des.run_virtual(model, cmds, et)
+    dt = time.perf_counter() - t0
+    print(json.dumps({"cpu_oracle": {"threads": threads_note, "forward_inferences_per_s": nets,
+                                     "scheduler_model_trace_records_per_s": round(len(trace) / dt, 1), "scheduler_model_trace_records": len(trace)}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -50,7 +83,11 @@ def main():
     ap.add_argument("--pmc-pass", action="store_true",
                     help="counter-collection helper for `rocprofv3 --pmc`: three 64 MiB device copies (the known-size reference "
                          "kernel), then 20 forward passes of task 0 alone; prints nothing, times nothing")
+    ap.add_argument("--cpu-oracle-report", action="store_true",
+                    help="instead of the benchmark: time the CPU oracle alone (forward pass of every network, scheduler model); no GPU")
     args = ap.parse_args()
+    if args.cpu_oracle_report:
+        return cpu_oracle_report(os.environ.get("OMP_NUM_THREADS", str(os.cpu_count() or 1)))
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
 
@@ -108,6 +145,9 @@ def main():
     rejected = sum((a["rejected_admission"] + a["rejected_overrun"]) - (b["rejected_admission"] + b["rejected_overrun"])
                    for a, b in zip(after, before))
     value = completed / elapsed
+    # run-level roofline: time the whole chip would need for the completed inferences at each layer's roofline / wall time
+    roof_us = harness.taskset_roofline_us(ts)
+    run_frac = sum((a["completed"] - b["completed"]) * r for a, b, r in zip(after, before, roof_us)) * 1e-6 / elapsed
     sat_resp_ms = [(a["resp_sum_ns"] - b["resp_sum_ns"]) / max(a["completed"] - b["completed"], 1) / 1e6 for a, b in zip(after, before)]
 
     # ---- periodic run: the deadline metrics -----------------------------------------------------------------------
@@ -160,7 +200,8 @@ def main():
                         frac=round(achieved / PEAK_FP32_MFMA_TFLOPS, 5), traffic=read_traffic(dom),
                         all_sampled_kernels={k: dict(launches=v[0], avg_us=round((v[1] / v[0] - pair_ms) * 1e3, 3)) for k, v in timing.items()},
                         solo_layer_ms_per_inference={k: round(v[0], 4) for k, v in solo.items()},
-                        solo_network_kernel_time_ms=round(float(ms.sum()), 4))
+                        solo_network_kernel_time_ms=round(float(ms.sum()), 4),
+                        run=dict(t_roof_us_per_inference=round(roof_us[0], 2), roofline_time_over_wall=round(run_frac, 4)))
     D.daris_shutdown()
 
     # ---- CPU oracle on the host cores, bounded sample of the same workload ----------------------------------------------------

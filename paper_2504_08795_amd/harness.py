@@ -82,6 +82,9 @@ def summarise(ts, before, after, wall_s):
     out["completed"] = total
     out["inferences_per_s"] = round(total / wall_s, 2)
     out["wall_s"] = round(wall_s, 4)
+    # what the whole chip would need for the completed inferences at its rooflines, over the wall time
+    roof = taskset_roofline_us(ts)
+    out["roofline_time_over_wall"] = round(sum((after[i]["completed"] - before[i]["completed"]) * roof[i] for i in range(len(ts.tasks))) * 1e-6 / wall_s, 4)
     return out
 
 
@@ -151,6 +154,45 @@ PEAK_TFLOPS = {"fp32": 157.3, "bf16": 2500.0}   # MI355X dense MFMA peaks
 PEAK_HBM_GBS = 8000.0
 
 
+def layer_rooflines(layers, shp, dtype):
+    """Per layer: (algorithmic FLOPs, algorithmic bytes, t_roof in us on the whole chip).  Bytes = weights once + one fp32
+    bias per output channel + the input tensor(s) read once + the output written once, at the element size of the task;
+    FLOPs = 2 x MACs; t_roof = max(FLOPs / dense MFMA peak of the dtype, bytes / HBM peak).  Host arithmetic on the layer
+    table only."""
+    import workloads as wl
+    es = 4 if dtype == "fp32" else 2
+    shapes = wl.layer_shapes(layers, shp)
+    macs = wl.net_macs(layers, shp)
+    out = []
+    for l, L in enumerate(layers):
+        c, h, w = shapes[l]
+        ci, hi, wi = shp if L.in_from < 0 else shapes[L.in_from]
+        if L.op == wl.nets.OP_CONV:
+            w_elems, b_elems = L.c_out * (L.c_in // L.groups) * L.k * L.k, L.c_out
+        elif L.op == wl.nets.OP_FC:
+            w_elems, b_elems = L.c_out * L.c_in, L.c_out
+        else:
+            w_elems = b_elems = 0
+        by = w_elems * es + b_elems * 4 + ci * hi * wi * es + c * h * w * es
+        if L.res_from >= 0:
+            by += c * h * w * es
+        fl = 2.0 * macs[l]
+        out.append((fl, by, max(fl / (PEAK_TFLOPS[dtype] * 1e12), by / (PEAK_HBM_GBS * 1e9)) * 1e6))
+    return out
+
+
+def taskset_roofline_us(ts):
+    """Sum of layer rooflines (whole chip) of one inference of each task of a task set, us."""
+    import workloads as wl
+    cache, out = {}, []
+    for t in ts.tasks:
+        if (t.net, t.dtype) not in cache:
+            layers, shp = wl.build_net(t.net)
+            cache[(t.net, t.dtype)] = sum(r[2] for r in layer_rooflines(layers, shp, t.dtype))
+        out.append(cache[(t.net, t.dtype)])
+    return out
+
+
 def layer_profile(net, dtype, n_cu, reps=50):
     """Every layer of one DNN alone on an n_cu partition: kernel, time, and its roofline.  Algorithmic bytes of a layer =
     its weights and biases once + its input tensor(s) read once + its output written once (element size of the
@@ -183,16 +225,13 @@ def layer_profile(net, dtype, n_cu, reps=50):
     finally:
         D.daris_shutdown()
     shapes = wl.layer_shapes(layers, shp)
+    roofs = layer_rooflines(layers, shp, dtype)
     rows = []
     for l, L in enumerate(layers):
         c, h, w = shapes[l]
-        ci, hi, wi = shp if L.in_from < 0 else shapes[L.in_from]
-        w_elems = 0 if weights[l][0] is None else weights[l][0].size
-        by = w_elems * es + (0 if weights[l][1] is None else weights[l][1].size * 4) + ci * hi * wi * es + c * h * w * es
-        if L.res_from >= 0:
-            by += c * h * w * es
+        by, t_roof = roofs[l][1], roofs[l][2]
+        assert roofs[l][0] == fl[l], (l, roofs[l][0], fl[l])      # the library counts the same MACs as the layer table
         us = float(ms[l]) * 1e3
-        t_roof = max(fl[l] / (PEAK_TFLOPS[dtype] * 1e12), by / (PEAK_HBM_GBS * 1e9)) * 1e6
         rows.append(dict(layer=l, name=L.name, kernel=D.daris_kernel_name(kid[l]), M=h * w, N=c, us=round(us, 2),
                          gflop=round(fl[l] / 1e9, 4), mbytes=round(by / 1e6, 3),
                          tflops=round(fl[l] / us / 1e6, 2) if us > 0.2 else None, gbs=round(by / us / 1e3, 1) if us > 0.2 else None,

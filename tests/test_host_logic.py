@@ -414,3 +414,26 @@ def test_code_object_kernels_match_the_argument_structures():
     assert seen == {"conv_wave_kernel": 36, "conv_wave_pair_kernel": 24, "splitk_reduce_kernel": 2, "dwconv_kernel": 2,
                     "maxpool_kernel": 2, "gavgpool_kernel": 2, "fc_kernel": 2, "ingest_kernel": 2, "egress_kernel": 2,
                     "cu_probe_kernel": 1}
+
+
+def test_layer_rooflines_follow_the_layer_tables():
+    """The harness's roofline helper is host arithmetic on the layer tables: FLOPs are twice the pinned MAC counts, bytes
+    count every weight once, and the per-network sums are the figures the profiles quote."""
+    from paper_2504_08795_amd import harness
+    want_macs = {"resnet18": 1814073344, "resnet50": 4089184256, "vgg16": 15470264320, "mobilenet_v2": 300774272, "tiny": 12279808}
+    want_us = {("resnet18", "fp32"): 23.94, ("resnet50", "bf16"): 13.51, ("vgg16", "fp32"): 261.37, ("mobilenet_v2", "fp32"): 8.87}
+    for net, macs in want_macs.items():
+        layers, shp = wl.build_net(net)
+        r = harness.layer_rooflines(layers, shp, "fp32")
+        assert sum(x[0] for x in r) == 2.0 * macs
+        es = 4
+        weights = sum(L.c_out * (L.c_in // L.groups) * L.k * L.k for L in layers if L.op == wl.nets.OP_CONV) + \
+            sum(L.c_out * L.c_in for L in layers if L.op == wl.nets.OP_FC)
+        assert sum(x[1] for x in r) > weights * es                       # plus activations and biases
+        for x in r:
+            assert x[2] == max(x[0] / 157.3e12, x[1] / 8e12) * 1e6
+    for (net, dtype), us in want_us.items():
+        layers, shp = wl.build_net(net)
+        assert round(sum(x[2] for x in harness.layer_rooflines(layers, shp, dtype)), 2) == us
+    ts = wl.make_taskset(2)
+    assert [round(v, 2) for v in harness.taskset_roofline_us(ts)] == [23.94] * 4
