@@ -369,9 +369,6 @@ struct EnqueueOpts {
 
 // Appends launches [lo, hi) of T to S's queue (S.qmu held).  Returns nullptr or an error text.
 const char* enqueue_range(TaskRt& T, int lo, int hi, const JobIo& io, StreamRt& S, const EnqueueOpts& o) {
-  // Diagnostic: DARIS_HOST_LAUNCH_DELAY_US=n makes the host spin n microseconds before every launch, which
-  // reproduces the regime a tracing profiler puts the run in (host-bound launches, kernels starting on an idle GPU).
-  static const int delay_us = getenv("DARIS_HOST_LAUNCH_DELAY_US") ? atoi(getenv("DARIS_HOST_LAUNCH_DELAY_US")) : 0;
   if (lo < 0 || hi > (int)T.launches.size() || lo >= hi) return "empty launch range";
   if (o.sample) {
     while ((int)S.tsig.size() < hi - lo - 1) {
@@ -381,10 +378,6 @@ const char* enqueue_range(TaskRt& T, int lo, int hi, const JobIo& io, StreamRt& 
     }
   }
   for (int i = lo; i < hi; ++i) {
-    if (delay_us > 0) {
-      const auto until = std::chrono::steady_clock::now() + std::chrono::microseconds(delay_us);
-      while (std::chrono::steady_clock::now() < until) {}
-    }
     const LaunchRt& r = T.launches[i];
     hsa_signal_t sig{0};
     if (i == hi - 1 && o.done.handle) sig = o.done;
@@ -1312,7 +1305,7 @@ daris_status daris_profile_layers(daris_task t, daris_part p, int reps, float* m
     (void)hipFree(scratch_out);
     if (scratch_in) (void)hipFree(scratch_in);
     g_rt.free_signal(first);
-    return fail(DARIS_ENOMEM, "profile buffers: %s", hipGetErrorString(ea));
+    return fail(DARIS_ENOMEM, "profile buffers: %s", ea != hipSuccess ? hipGetErrorString(ea) : "signal creation failed");
   }
   JobIo io;
   io.in = scratch_in;
