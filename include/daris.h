@@ -52,9 +52,14 @@ enum {
   DARIS_NO_FIXED = 16,        /* ablation ("No Fixed"): all stages share one level, EDF only                   */
   DARIS_HP_ADMISSION = 32,    /* Overload+HPA (Sec. VI-I): HP jobs must pass the test in their own context     */
   DARIS_KEEP_ACTIVATIONS = 64, /* debugging: one buffer per layer output so daris_read_layer works             */
-  DARIS_WAVE_PRIORITY = 128   /* the convolution waves of high-priority tasks raise their issue priority on the CU:
+  DARIS_WAVE_PRIORITY = 128,  /* the convolution waves of high-priority tasks raise their issue priority on the CU:
                                  where partitions overlap, HP stages run faster and LP stages slower (measured:
                                  HP response -5 %, LP +12 %, aggregate throughput -2 %); off by default          */
+  DARIS_SHARED_QUEUE = 256    /* the N_s streams of a partition feed ONE hardware queue instead of one each: their
+                                 stages execute one after the other, but the next one is already queued when a
+                                 stage ends, so the host round trip of the boundary is hidden.  For GPUs on which
+                                 only a few hardware queues make progress at a time; scheduling decisions (and the
+                                 trace) are those of N_s streams; off by default                                */
 };
 
 enum { DARIS_LP = 0, DARIS_HP = 1 };

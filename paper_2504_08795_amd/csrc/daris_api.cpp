@@ -101,8 +101,12 @@ struct TaskRt {
 };
 
 struct StreamRt {  // one CU-masked queue and, in real-time mode, the worker thread that feeds and watches it
-  AqlQueue q;
-  std::mutex qmu;                  // one producer at a time (the worker; direct calls of the API thread)
+  struct HwQueue {
+    AqlQueue q;
+    std::mutex mu;  // one producer at a time (the streams' workers; direct calls of the API thread)
+  };
+  // the hardware queue the stream's packets go to: its own, or (DARIS_SHARED_QUEUE) one for all streams of the partition
+  std::shared_ptr<HwQueue> hw;
   hsa_signal_t done{0};            // completion of the last launch of a stage
   hsa_signal_t begin{0};           // driver profile: completion of a stage's first launch (its start time stamp)
   std::vector<hsa_signal_t> tsig;  // kernel timing: one signal per launch of a sampled stage
@@ -367,7 +371,7 @@ struct EnqueueOpts {
   bool sample = false;          // every launch completes a signal of S.tsig, so that its time stamps can be read
 };
 
-// Appends launches [lo, hi) of T to S's queue (S.qmu held).  Returns nullptr or an error text.
+// Appends launches [lo, hi) of T to S's queue (S.hw->mu held).  Returns nullptr or an error text.
 const char* enqueue_range(TaskRt& T, int lo, int hi, const JobIo& io, StreamRt& S, const EnqueueOpts& o) {
   if (lo < 0 || hi > (int)T.launches.size() || lo >= hi) return "empty launch range";
   if (o.sample) {
@@ -395,11 +399,11 @@ const char* enqueue_range(TaskRt& T, int lo, int hi, const JobIo& io, StreamRt& 
         std::memcpy(blk, r.kl.args, r.kl.nbytes);
         if (is_in) std::memcpy(blk + T.in_off, &io.in, sizeof(void*));
         if (is_out) std::memcpy(blk + T.out_off, &io.out, sizeof(void*));
-        if (!S.q.dispatch_copy(*r.kl.k, r.kl.groups, r.kl.threads, blk, r.kl.nbytes, sig, fl)) return "packet rejected";
+        if (!S.hw->q.dispatch_copy(*r.kl.k, r.kl.groups, r.kl.threads, blk, r.kl.nbytes, sig, fl)) return "packet rejected";
         continue;
       }
     }
-    if (!S.q.dispatch(*r.kl.k, r.kl.groups, r.kl.threads, dev, sig, fl)) return "packet rejected";
+    if (!S.hw->q.dispatch(*r.kl.k, r.kl.groups, r.kl.threads, dev, sig, fl)) return "packet rejected";
   }
   return nullptr;
 }
@@ -413,7 +417,7 @@ void stage_range(const TaskRt& T, int stage, int* lo, int* hi) {
   *hi = end == n ? (int)T.launches.size() : T.layer_lo[end];
 }
 
-// Enqueues one stage of a job on S (S.qmu held); S.done completes with it.  Inside a job the next stage runs on this
+// Enqueues one stage of a job on S (S.hw->mu held); S.done completes with it.  Inside a job the next stage runs on this
 // device whichever queue it gets, so its boundary releases at device scope; the last stage's boundary makes the logits
 // visible to the host.
 const char* enqueue_stage(TaskRt& T, int stage, const JobIo& io, StreamRt& S, bool sample, bool prof) {
@@ -484,7 +488,7 @@ daris_status run_direct(TaskRt& T, int lo, int hi, const JobIo& io, StreamRt& S)
   o.release_system = o.acquire_system = true;
   const char* err;
   {
-    std::lock_guard<std::mutex> ql(S.qmu);
+    std::lock_guard<std::mutex> ql(S.hw->mu);
     err = enqueue_range(T, lo, hi, io, S, o);
   }
   if (err) return fail(DARIS_EHIP, "%s", err);
@@ -497,8 +501,8 @@ daris_status run_one(const std::vector<KernelLaunch>& ks, StreamRt& S) {
   for (size_t i = 0; i < ks.size(); ++i) {
     bool ok;
     {
-      std::lock_guard<std::mutex> ql(S.qmu);
-      ok = S.q.dispatch_copy(*ks[i].k, ks[i].groups, ks[i].threads, ks[i].args, ks[i].nbytes, G->util_sig, AqlQueue::kReleaseSystem | AqlQueue::kAcquireSystem);
+      std::lock_guard<std::mutex> ql(S.hw->mu);
+      ok = S.hw->q.dispatch_copy(*ks[i].k, ks[i].groups, ks[i].threads, ks[i].args, ks[i].nbytes, G->util_sig, AqlQueue::kReleaseSystem | AqlQueue::kAcquireSystem);
     }
     if (!ok) return fail(DARIS_EHIP, "packet rejected");
     aql_wait(G->util_sig);
@@ -533,7 +537,7 @@ daris_status issue(const std::vector<Launch>& ls, int64_t t) {
       if (G->vt) {
         const char* err;
         {
-          std::lock_guard<std::mutex> ql(S.qmu);
+          std::lock_guard<std::mutex> ql(S.hw->mu);
           err = enqueue_stage(T, l.stage, io->second, S, sample, false);
         }
         if (err) return fail(DARIS_EHIP, "stage execution: %s", err);
@@ -637,7 +641,7 @@ void worker_loop(StreamRt* S) {
     const int64_t t0 = prof ? now_ns() : 0;
     const char* err;
     {
-      std::lock_guard<std::mutex> ql(S->qmu);
+      std::lock_guard<std::mutex> ql(S->hw->mu);
       err = enqueue_stage(T, l.stage, io, *S, sample, prof);
     }
     const int64_t t1 = prof ? now_ns() : 0;
@@ -796,7 +800,7 @@ daris_status daris_shutdown(void) {
     for (auto& T : G->tasks) free_task(*T);
     for (PartRt& P : G->parts)
       for (auto& S : P.streams) {
-        S->q.destroy();
+        if (S->hw) S->hw->q.destroy();  // destroying a shared queue again is a no-op
         g_rt.free_signal(S->done);
         g_rt.free_signal(S->begin);
         for (hsa_signal_t sg : S->tsig) g_rt.free_signal(sg);
@@ -986,14 +990,19 @@ static daris_status make_streams(void) {
       for (int i = 0; i < P.n_streams; ++i) {
         P.streams.emplace_back(new StreamRt());
         StreamRt& S = *P.streams.back();
-        const std::string err = S.q.create(&g_rt, P.mask);
-        if (!err.empty()) return fail(DARIS_EHIP, "queue of partition with %d CUs: %s", P.n_cu, err.c_str());
+        if (i > 0 && (G->flags & DARIS_SHARED_QUEUE)) {
+          S.hw = P.streams[0]->hw;
+        } else {
+          S.hw = std::make_shared<StreamRt::HwQueue>();
+          const std::string err = S.hw->q.create(&g_rt, P.mask);
+          if (!err.empty()) return fail(DARIS_EHIP, "queue of partition with %d CUs: %s", P.n_cu, err.c_str());
+          // completion signals receive the start and end time stamps of their dispatch; switched on before the first
+          // packet and left on (a stage carries one signal, so the cost is one record per stage)
+          S.hw->q.set_profiling(true);
+        }
         S.done = g_rt.new_signal(1);
         S.begin = g_rt.new_signal(1);
         if (!S.done.handle || !S.begin.handle) return fail(DARIS_EHIP, "signal creation failed");
-        // completion signals receive the start and end time stamps of their dispatch; switched on before the first
-        // packet and left on (a stage carries one signal, so the cost is one record per stage)
-        S.q.set_profiling(true);
       }
     }
   }
@@ -1313,7 +1322,7 @@ daris_status daris_profile_layers(daris_task t, daris_part p, int reps, float* m
   if (!var.in.empty()) io.in_args = var.in[0];
   if (!var.out.empty()) io.out_args = var.out[0];
   daris_status result = DARIS_OK;
-  std::lock_guard<std::mutex> ql(S.qmu);
+  std::lock_guard<std::mutex> ql(S.hw->mu);
   for (int l = 0; l < n && result == DARIS_OK; ++l) {
     const int lo = T.layer_lo[l], hi = T.layer_lo[l + 1];
     ms_per_layer[l] = 0.f;
@@ -1539,7 +1548,7 @@ daris_status daris_calibrate_afet_loaded(daris_task t, daris_part p, int reps) {
         EnqueueOpts eo;
         eo.done = Q.done;  // no job is active, so the stream's worker is not using its signal
         eo.acquire_system = eo.release_system = true;
-        std::lock_guard<std::mutex> ql(Q.qmu);
+        std::lock_guard<std::mutex> ql(Q.hw->mu);
         const char* err = enqueue_range(O, 0, (int)O.launches.size(), io, Q, eo);
         if (err) result = fail(DARIS_EHIP, "calibration load: %s", err);
         else loaded.push_back(&Q);

@@ -251,7 +251,7 @@ def main():
     ap.add_argument("--oversub", type=float, default=2.0, help="config 5: oversubscription level")
     ap.add_argument("--streams", type=int, default=1, help="streams per partition (N_s)")
     ap.add_argument("--stages", type=int, default=0, help="override the stage count of every task (1 = no staging)")
-    ap.add_argument("--flags", default="", help="comma list of no_last,no_prior,no_fixed,hp_admission,wave_prio")
+    ap.add_argument("--flags", default="", help="comma list of no_last,no_prior,no_fixed,hp_admission,wave_prio,shared_queue")
     ap.add_argument("--migrate-every", type=int, default=0)
     ap.add_argument("--saturated", action="store_true")
     ap.add_argument("--driver-profile", action="store_true", help="--saturated: where a stage's wall time goes")
@@ -293,7 +293,7 @@ def main():
             t.n_stages = a.stages
     fl = 0
     for name in filter(None, a.flags.split(",")):
-        fl |= {"no_last": D.NO_LAST, "no_prior": D.NO_PRIOR, "no_fixed": D.NO_FIXED, "hp_admission": D.HP_ADMISSION, "wave_prio": D.WAVE_PRIORITY}[name]
+        fl |= {"no_last": D.NO_LAST, "no_prior": D.NO_PRIOR, "no_fixed": D.NO_FIXED, "hp_admission": D.HP_ADMISSION, "wave_prio": D.WAVE_PRIORITY, "shared_queue": D.SHARED_QUEUE}[name]
     g = GpuTaskSet(ts, flags=fl, streams_per_partition=a.streams)
     try:
         g.calibrate(loaded=a.loaded_afet)

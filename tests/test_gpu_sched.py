@@ -268,11 +268,11 @@ def test_stress_set_with_forced_migrations_between_chunks():
 
 
 @pytest.mark.parametrize("streams,lib_flags,des_flags", [(2, 0, 0), (1, D.NO_FIXED, des.F_NO_FIXED), (2, D.NO_LAST | D.NO_PRIOR, des.F_NO_LAST | des.F_NO_PRIOR),
-                                                         (1, D.WAVE_PRIORITY, 0)])
+                                                         (1, D.WAVE_PRIORITY, 0), (2, D.SHARED_QUEUE, 0), (3, D.SHARED_QUEUE, 0)])
 def test_saturated_run_with_streams_and_ablation_flags(streams, lib_flags, des_flags):
-    """Two streams per partition (the paper's MPS+STR shape), the ablation switches and the wave-priority option (which
-    changes kernel timing only), saturated so that stages really compete: the recorded trace replays through the oracle
-    with the same switches, logits match."""
+    """Two streams per partition (the paper's MPS+STR shape), the ablation switches, the wave-priority option and the
+    streams of a partition sharing one hardware queue (both change kernel timing only), saturated so that stages really
+    compete: the recorded trace replays through the oracle with the same switches, logits match."""
     ts = wl.make_taskset(2, n_jobs=30)
     g = GpuTaskSet(ts, flags=lib_flags, streams=streams)
     try:
@@ -283,7 +283,7 @@ def test_saturated_run_with_streams_and_ablation_flags(streams, lib_flags, des_f
         _replay_and_check(ts, afet, got, [streams] * 3, des_flags)
         worst, n = g.check_logits(got)
         assert n == 120
-        if streams == 2:
+        if streams >= 2:
             assert any(r[2] == des.DISPATCH and r[7] == 1 for r in got), "second stream never used"
     finally:
         g.close()
