@@ -16,7 +16,8 @@
  *     uses them has completed (daris_run_until_idle() or the blocking run calls return).  The library's kernels run
  *     on queues of its own, not on a HIP stream: what the caller's streams wrote into an input buffer must be
  *     complete (stream or device synchronised) before the job is released, and logits are complete and visible
- *     to every HIP stream once the job has completed.
+ *     to every HIP stream once the job has completed.  daris_task_set_io and daris_forward synchronise the device
+ *     themselves; daris_release_job, the hot path, does not.
  *   - Times are int64 nanoseconds.  In virtual-time mode they are positions on the library's virtual clock;
  *     in real-time mode they count from the library's epoch (set by daris_commit()).
  *   - Utilisations (eq. 3-7) are evaluated in Q32 fixed point: u = floor(mret * 2^32 / T).

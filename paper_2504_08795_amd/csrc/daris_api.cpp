@@ -1107,6 +1107,9 @@ daris_status daris_task_set_io(daris_task t, const void* d_inputs, int32_t n_inp
   T.n_inputs = n_inputs;
   T.n_slots = n_slots;
   if (!G->nodev) {
+    // The jobs run on queues of the library's own, unordered with the caller's HIP streams: wait here, once, for whatever
+    // those streams are still writing into the pools (inputs being uploaded, logits being pre-filled).
+    HIP_TRY(hipDeviceSynchronize());
     // argument blocks for every buffer of the two pools, so that a release writes nothing but packets
     free_variants(&T.pool);
     if ((int64_t)n_inputs + n_slots <= (1 << 20)) {
@@ -1261,6 +1264,7 @@ daris_status daris_forward(daris_task t, const void* d_input, void* d_logits, da
   std::lock_guard<std::mutex> lk(G->mu);
   if (G->core.has_active(t)) return fail(DARIS_ESTATE, "task %d has an active job", t);
   TaskRt& T = *G->tasks[t];
+  HIP_TRY(hipDeviceSynchronize());  // the caller's streams may still be writing the two buffers (see daris_task_set_io)
   JobIo io;
   io.in = d_input;
   io.out = d_logits;

@@ -34,7 +34,6 @@ static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16, int force_tn = 
   // below about 3/4 of the partition's CUs it is better to keep 32-channel tiles and split K less (or not at all,
   // which saves the reduction launch).
   int tn = (nb % 2 == 0 && cdiv(M, 32) * (nb / 2) >= 96) ? 2 : 1;
-  if (const char* e = getenv("DARIS_W_TN")) tn = (atoi(e) == 2 && nb % 2 == 0) ? 2 : 1;
   if (force_tn) tn = force_tn;
   const int tiles = cdiv(M, 32) * (nb / tn);
   const int nominal_cus = kNominalWaveSlots / 4;
@@ -62,11 +61,6 @@ static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16, int force_tn = 
       }
     }
   }
-  if (const char* e = getenv("DARIS_W_NW")) {
-    const int v = atoi(e);
-    if (v == 2 || v == 4 || v == 8) nw = v;
-  }
-  if (const char* e = getenv("DARIS_W_Z")) z = atoi(e) < S ? atoi(e) : S;
   if (force_nw) {  // second problem of a two-problem launch: the first one's kernel variant, no split across workgroups
     nw = force_nw;
     z = 1;
@@ -91,10 +85,6 @@ static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16, int force_tn = 
     pl.xmode = 2;
     pl.grid_x = (uint32_t)(8 * cdiv(pl.MT, 8 / pl.G));
   } else {
-    pl.xmode = 0;
-    pl.grid_x = (uint32_t)(pl.G * pl.MT);
-  }
-  if (getenv("DARIS_W_XMODE0")) {
     pl.xmode = 0;
     pl.grid_x = (uint32_t)(pl.G * pl.MT);
   }

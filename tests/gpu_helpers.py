@@ -40,6 +40,7 @@ class GpuNet:
     def forward(self, x, part=0):
         xd = torch.from_numpy(np.ascontiguousarray(x, np.float32)).cuda()
         yd = torch.full((self.n_out,), float("nan"), dtype=torch.float32, device="cuda")
+        torch.cuda.synchronize()          # the library runs on queues of its own: the buffers must be complete first
         D.daris_forward(self.task, xd, yd, self.parts[part])
         return yd.cpu().numpy()
 

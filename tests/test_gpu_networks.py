@@ -43,6 +43,30 @@ def test_logits_bit_identical_across_splits_and_partitions(net, dtype):
         np.testing.assert_array_equal(o, outs[0])
 
 
+@pytest.mark.parametrize("net,dtype", [("resnet18", "fp32"), ("resnet50", "bf16")])
+def test_plain_launch_shapes_agree_with_the_fused_ones(net, dtype, monkeypatch):
+    """The launch-count optimisations -- a residual block's shortcut and first convolution in one launch, the input layout
+    conversion folded into the first convolution -- can be switched off when a task is registered: the plain launches
+    must meet the same tolerance against the oracle, and agree with the fused ones to rounding."""
+    layers, shp = wl.build_net(net)
+    weights = wl.make_weights(layers, 11)
+    x = wl.make_inputs(shp, 11, 1, "normal")[0]
+    want = oracle_logits(layers, weights, x, dtype)
+    with GpuNet(layers, weights, shp, dtype, k=3) as g:
+        fused = g.forward(x)
+        n_pairs = sum(1 for l in range(len(layers)) if D.daris_get_launch_plan(g.task, l)["pair_lead"])
+    assert n_pairs >= 3
+    monkeypatch.setenv("DARIS_NO_PAIR", "1")
+    monkeypatch.setenv("DARIS_NO_FUSED_INGEST", "1")
+    with GpuNet(layers, weights, shp, dtype, k=3) as g:
+        plain = g.forward(x)
+        assert not any(D.daris_get_launch_plan(g.task, l)["pair_lead"] for l in range(len(layers)))
+    for got in (fused, plain):
+        e_max, e_l2 = rel_err(got, want)
+        assert e_max <= TOL[dtype] and e_l2 <= TOL[dtype], (e_max, e_l2)
+    assert rel_err(plain, fused)[0] <= TOL[dtype]
+
+
 @pytest.mark.parametrize("net,dtype", [("resnet18", "fp32"), ("resnet50", "bf16"), ("mobilenet_v2", "fp32")])
 def test_every_layer_output(net, dtype):
     """Drill-down with one buffer per layer: each intermediate tensor against the oracle's."""
