@@ -229,6 +229,54 @@ def test_explicit_buffers_and_pool_buffers_give_the_same_logits():
         g.close()
 
 
+@pytest.mark.parametrize("shape", ["conversions", "single_fc", "two_convs"])
+def test_pool_jobs_of_networks_with_unusual_first_and_last_launches(shape):
+    """The launches that read a job's input and write its logits differ by network: a layout conversion before an
+    8-channel first convolution and another one after a last layer that is not an FC; an FC that does both at once
+    behind the input conversion; a fused 3-channel first convolution.  Jobs of an I/O pool (argument blocks prepared per
+    buffer) must give what a direct forward pass with explicit pointers gives, bit for bit, and agree with the oracle."""
+    N = wl.nets
+    rng = np.random.default_rng(5)
+    if shape == "conversions":
+        layers, shp = [N.Layer(op=N.OP_CONV, c_in=8, c_out=24, k=3, stride=1, pad=1, act=1, in_from=-1),
+                       N.Layer(op=N.OP_CONV, c_in=24, c_out=12, k=1, stride=1, pad=0, act=0, in_from=0)], (8, 9, 11)
+    elif shape == "single_fc":
+        layers, shp = [N.Layer(op=N.OP_FC, c_in=5 * 4 * 3, c_out=7, in_from=-1)], (5, 4, 3)
+    else:
+        layers, shp = [N.Layer(op=N.OP_CONV, c_in=3, c_out=16, k=3, stride=2, pad=1, act=1, in_from=-1),
+                       N.Layer(op=N.OP_CONV, c_in=16, c_out=8, k=3, stride=1, pad=1, act=2, in_from=0)], (3, 17, 15)
+    weights = []
+    for L in layers:
+        cg = L.c_in // L.groups
+        w = rng.normal(0, 0.2, (L.c_out, cg, L.k, L.k) if L.op == N.OP_CONV else (L.c_out, L.c_in)).astype(np.float32)
+        weights.append((w, rng.normal(0, 0.3, L.c_out).astype(np.float32)))
+    n_in, n_slots, n_jobs = 3, 5, 7
+    xs = rng.normal(0, 1, (n_in,) + shp).astype(np.float32)
+    want = [F.forward(layers, weights, x, "fp32").ravel() for x in xs]
+    n_out = want[0].size
+    D.daris_init(0, 0, 0)
+    try:
+        p = D.daris_create_partition(64)
+        dnn, keep = D.make_dnn(layers, weights, shp, "fp32")
+        t = D.daris_register_task(dnn, 2_000_000, 2_000_000, D.HP)
+        xd = torch.from_numpy(xs).cuda()
+        yd = torch.full((n_slots, n_out), float("nan"), dtype=torch.float32, device="cuda")
+        D.daris_task_set_io(t, xd, n_in, yd, n_slots)
+        D.daris_calibrate_afet(t, p, 2)
+        D.daris_run_periodic(None, [n_jobs])
+        assert D.daris_get_stats(t)["completed"] == n_jobs
+        got = yd.cpu().numpy()
+        for slot in range(n_slots):
+            job = max(j for j in range(n_jobs) if j % n_slots == slot)      # the last job that wrote this row
+            direct = torch.full((n_out,), float("nan"), dtype=torch.float32, device="cuda")
+            D.daris_forward(t, xd[job % n_in], direct, p)
+            assert np.array_equal(got[slot], direct.cpu().numpy()), (shape, slot)
+            e_max, e_l2 = rel_err(got[slot], want[job % n_in])
+            assert e_max <= 2e-5 and e_l2 <= 2e-5, (shape, slot, e_max, e_l2)
+    finally:
+        D.daris_shutdown()
+
+
 def test_cu_masks_are_honoured():
     """Workgroups launched on a partition's stream run only on as many distinct CUs as the partition owns."""
     D.daris_init(0, 0, 0)
