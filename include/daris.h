@@ -72,7 +72,7 @@ enum { DARIS_ACT_NONE = 0, DARIS_ACT_RELU = 1, DARIS_ACT_RELU6 = 2 };
 enum {
   DARIS_ACCEPTED = 1,         /* admitted in the task's current partition                                      */
   DARIS_MIGRATED = 2,         /* admitted after migration to another partition (LP only)                       */
-  DARIS_REJECT_ADMISSION = 3, /* failed eq. (11) in every partition                                            */
+  DARIS_REJECT_ADMISSION = 3, /* failed eq. (12) in every partition                                            */
   DARIS_REJECT_OVERRUN = 4,   /* LP: the task's previous job is still active                                   */
   DARIS_QUEUED = 5            /* HP: waits behind the task's previous job, starts when it ends                 */
 };
@@ -200,7 +200,7 @@ daris_part daris_get_partition(daris_task t);
  * calls (events before it are simulated first; stage completions at exactly release_ns are processed before the
  * release, dispatching at release_ns happens after all releases of that instant); real-time mode -- the nominal
  * release used for deadlines and response times, or -1 for "now".  *decision (may be NULL) receives a
- * DARIS_ACCEPTED.. code.  LP jobs take the admission test eq. (10)-(11); HP jobs are always scheduled. */
+ * DARIS_ACCEPTED.. code.  LP jobs take the admission test eq. (11)-(12); HP jobs are always scheduled. */
 daris_status daris_release_job(daris_task t, const void* d_input, void* d_logits, int64_t release_ns,
                                int32_t* decision);
 /* Forced migration of task t to partition p: applied at once unless a stage of t is running, else at that

@@ -3,7 +3,7 @@
 Pure-Python integers (nanoseconds, Q32 utilisations).  The steps follow the
 paper's Sec. III (task model, MRET eq. 1-2, utilisation eq. 3-7, virtual
 deadline eq. 8, partition size formula of Sec. III-C2) and Sec. IV (Algorithm 1,
-admission test eq. 10-11, stage scheduler), in the paper's notation.  Where the
+admission test eq. 11-12, stage scheduler), in the paper's notation.  Where the
 paper is silent the reading taken is written next to the step.
 
 Nothing here is shared with the HIP library; the library's host scheduler is a
@@ -179,7 +179,7 @@ class SchedulerModel:
 
     # ---- online phase ----------------------------------------------------------------------------
     def admission_ok(self, k: int, u: int) -> bool:
-        """Eq. (10)-(11): U^{l,a}_k + u < N_s - U^{h,t}_k, strict, in Q32 integers."""
+        """Eq. (11)-(12): U^{l,a}_k + u < N_s - U^{h,t}_k, strict, in Q32 integers."""
         return self.ula[k] + u + self.u_high_total(k) < self.n_streams[k] * Q
 
     def release(self, t: int, i: int, r: Optional[int] = None) -> int:

@@ -92,7 +92,7 @@ u128 SchedCore::u_high_total(int part) const {
   return s;
 }
 
-// eq. (10)-(11): U^{l,a}_k + u < N_s - U^{h,t}_k, rearranged so that nothing goes negative
+// eq. (11)-(12): U^{l,a}_k + u < N_s - U^{h,t}_k, rearranged so that nothing goes negative
 bool SchedCore::admission_ok(int part, u128 u) const {
   return parts_[part].ula + u + u_high_total(part) < (u128)parts_[part].n_streams * kOne;
 }

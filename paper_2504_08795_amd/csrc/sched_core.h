@@ -3,7 +3,7 @@
 // virtual-time and real-time drivers feed it and act on what dispatch() returns.
 //
 // Follows Sec. III (task model, MRET eq. 1-2, utilisation eq. 3-7, virtual deadlines eq. 8) and Sec. IV
-// (Algorithm 1, admission test eq. 10-11, the eight-level stage scheduler with EDF inside a level).
+// (Algorithm 1, admission test eq. 11-12, the eight-level stage scheduler with EDF inside a level).
 #pragma once
 #include <cstdint>
 #include <deque>

@@ -16,14 +16,26 @@ def load_golden(name):
     ntask = len(g["tasks"])
     et = []
     for i in range(ntask):
-        per_stage = g["et"][str(i)]
+        per_stage = g.get("et", {}).get(str(i), [])
         et.append([[list(jobs) for _ in range(npart)] for jobs in per_stage])
-    cmds = [tuple(c) for c in g["commands"]]
+    cmds = [tuple(c) for c in g.get("commands", [])]
     trace = [(s, r[0], NAME2TYPE[r[1]], *r[2:]) for s, r in enumerate(g["trace"])]
     return g, cmds, et, trace
 
 
-def model_from_golden(g, flags=0):
+GOLDEN_FLAGS = {"no_last": des.F_NO_LAST, "no_prior": des.F_NO_PRIOR, "no_fixed": des.F_NO_FIXED, "hp_admission": des.F_HP_ADMISSION}
+
+
+def golden_flags(g):
+    """Scheduler switches a golden file asks for (its "flags" list), as the oracle's flag bits."""
+    f = 0
+    for name in g.get("flags", []):
+        f |= GOLDEN_FLAGS[name]
+    return f
+
+
+def model_from_golden(g, flags=None):
+    flags = golden_flags(g) if flags is None else flags
     tasks = [des.TaskParam(t["period"], t["deadline"], t["prio"], list(t["afet"])) for t in g["tasks"]]
     return des.SchedulerModel(g["partitions"], tasks, ws=g.get("ws", 5), flags=flags)
 

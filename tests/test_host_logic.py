@@ -225,10 +225,13 @@ def test_stage_split_known_results():
         assert layers[f].name.endswith((".ds", ".c1")) or layers[f].name in ("stem.pool", "gap", "fc")
 
 
-@pytest.mark.parametrize("name", ["sched_single_task.json", "sched_hp_preempts_lp.json", "sched_admission_migration.json"])
+@pytest.mark.parametrize("name", ["sched_single_task.json", "sched_hp_preempts_lp.json", "sched_admission_migration.json",
+                                  "sched_migration_target_choice.json", "sched_forced_migration_at_boundary.json",
+                                  "sched_hp_admission.json"])
 def test_library_reproduces_golden_traces(name):
     g, cmds, et, want = load_golden(name)
-    with Session(HOST):
+    lib_flags = {"no_last": D.NO_LAST, "no_prior": D.NO_PRIOR, "no_fixed": D.NO_FIXED, "hp_admission": D.HP_ADMISSION}
+    with Session(HOST | sum(lib_flags[f] for f in g.get("flags", []))):
         register_plain_tasks(g["partitions"], g["tasks"])
         load_et(et, len(g["partitions"]))
         run_commands(cmds)
@@ -365,7 +368,7 @@ def test_overrun_and_hp_queue_order():
     """A period far shorter than the execution time: LP releases are rejected as overruns, HP releases queue up FIFO and
     every one of them is eventually served in release order."""
     # the LP task's AFET (5) under-estimates its real time (25): job 0 is admitted (u = 0.5), the releases at 10 and 20
-    # find it still active (overrun), and from then on MRET = 25 makes u = 2.5, which eq. 11 rejects
+    # find it still active (overrun), and from then on MRET = 25 makes u = 2.5, which eq. 12 rejects
     tasks = [dict(period=10, deadline=10, prio=D.HP, afet=[25]), dict(period=10, deadline=10, prio=D.LP, afet=[5])]
     with Session(HOST):
         register_plain_tasks([1, 1], tasks)

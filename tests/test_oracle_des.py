@@ -86,7 +86,11 @@ def test_level_order():
 
 
 # ---- hand-worked traces --------------------------------------------------------------------------------
-@pytest.mark.parametrize("name", ["sched_single_task.json", "sched_hp_preempts_lp.json", "sched_admission_migration.json"])
+VIRTUAL_GOLDENS = ["sched_single_task.json", "sched_hp_preempts_lp.json", "sched_admission_migration.json",
+                   "sched_migration_target_choice.json", "sched_forced_migration_at_boundary.json", "sched_hp_admission.json"]
+
+
+@pytest.mark.parametrize("name", VIRTUAL_GOLDENS)
 def test_golden_traces(name):
     g, cmds, et, want = load_golden(name)
     m = model_from_golden(g)
@@ -94,7 +98,32 @@ def test_golden_traces(name):
     for a, b in zip(got, want):
         assert a == b, f"first difference at seq {a[0]}: got {a}, want {b}"
     assert len(got) == len(want)
-    check_trace_invariants(got, g["partitions"], [t["prio"] for t in g["tasks"]], [len(t["afet"]) for t in g["tasks"]])
+    check_trace_invariants(got, g["partitions"], [t["prio"] for t in g["tasks"]], [len(t["afet"]) for t in g["tasks"]], flags=m.flags)
+
+
+def test_golden_traces_make_the_choices_they_were_written_for():
+    """What each of the later hand-worked traces is there to pin, read off the trace itself."""
+    _g, _c, _e, tr = load_golden("sched_migration_target_choice.json")
+    mig = [(r[1], r[5], r[9]) for r in tr if r[2] == des.MIGRATE and r[6] == 5]
+    assert mig == [(35, 2, 0), (100, 0, 258), (125, 1, 0)]      # higher index by predicted finish; forced; tie -> lowest index
+    _g, _c, _e, tr = load_golden("sched_forced_migration_at_boundary.json")
+    assert [(r[1], r[2]) for r in tr if r[6] == 0 and r[2] in (des.CMD_MIGRATE, des.MIGRATE)] == [(10, des.CMD_MIGRATE), (30, des.MIGRATE)]
+    _g, _c, _e, tr = load_golden("sched_hp_admission.json")
+    assert [(r[1], r[9]) for r in tr if r[2] == des.REJECT and r[6] == 0] == [(100, des.REJECT_ADMISSION), (240, des.REJECT_OVERRUN)]
+    assert not any(r[2] in (des.MIGRATE, des.QUEUED) for r in tr)
+
+
+def test_replay_uses_the_recorded_dispatch_clock():
+    """A hand-written recording whose DISPATCH clock lags the events: execution times, the next job's virtual deadlines
+    and a stage's miss flag all depend on it (see the file's `why`)."""
+    g, _cmds, _et, rec = load_golden("sched_replay_dispatch_clock.json")
+    assert any(r[2] == des.DISPATCH and r[1] != rec[i - 1][1] for i, r in enumerate(rec))
+    m = model_from_golden(g)
+    got = des.run_replay(m, rec)
+    for a, b in zip(got, rec):
+        assert a == b, f"first difference at seq {a[0]}: got {a}, want {b}"
+    assert len(got) == len(rec)
+    assert m.tasks[0].rings == [[30, 73], [10, 15]]             # et = completion - dispatch clock
 
 
 # ---- reductions to textbook schedulers -------------------------------------------------------------------

@@ -248,3 +248,42 @@ def test_network_integer_totals():
     assert dw == 20_716_416
     layers, shp = wl.build_net("vgg16")
     assert sum(m for m, L in zip(wl.net_macs(layers, shp), layers) if L.op == wl.nets.OP_FC) == 123_633_664
+
+
+def test_bf16_mode_rounds_at_every_stated_point_hand_worked():
+    """A 1-channel toy worked by hand (bfloat16 keeps 8 significant bits; nearest, ties to even).  Each rounding point of
+    the bf16 mode -- input, weights, every layer output after bias + residual + activation, the residual operand being the
+    STORED tensor, the pooled value, and the logits NOT rounded -- changes at least one of the numbers below.
+
+    x = [2, 7, 3, 1+2^-8] (2x2).  Input rounding: 1+2^-8 is a tie between 1 and 1+2^-7 -> even -> 1.
+    L0 conv1x1 w = 515/512 -> bf16 129/128 (515/512 lies 1/512 below 129/128, 3/512 above 1); b = 31/128 (kept fp32).
+       2*129/128 + 31/128 = 144.5/64  tie, 144 even -> 2.25        (ties away would give 145/64)
+       7*129/128 + 31/128 = 233.5/32  tie, 234 even -> 7.3125      (unrounded w: 233.06/32 -> 7.28125)
+       3*129/128 + 31/128 = 209/64    exact         -> 3.265625
+       1*129/128 + 31/128 = 160/128   exact         -> 1.25        (unrounded input: 160.5/128 -> 161/128)
+    L1 conv1x1 w = 0.5, b = 0, residual = L0's stored output, ReLU: 1.5 * stored
+       3.375 exact; 10.96875 = 175.5/16 tie, 176 even -> 11.0 (with the unrounded residual 7.296875: 175.25/16 -> 10.9375);
+       4.8984375 = 156.75/32 -> 157/32 = 4.90625; 1.875 exact.
+    L2 global average: (3.375 + 11 + 4.90625 + 1.875) / 4 = 5.2890625 = 169.25/32 -> 5.28125.
+    L3 FC w = [515/512 -> 129/128, -2], b = [2^-8, 0]: logits = [129/128 * 169/32 + 1/256, -10.5625]
+       = [21817/4096, -10.5625] = [5.326416015625, -10.5625], exact in fp32 and left unrounded (bf16 would give 5.3125)."""
+    N = wl.nets
+    layers = [N.Layer(op=N.OP_CONV, c_in=1, c_out=1, k=1, in_from=-1),
+              N.Layer(op=N.OP_CONV, c_in=1, c_out=1, k=1, act=N.ACT_RELU, in_from=0, res_from=0),
+              N.Layer(op=N.OP_GAVGPOOL, c_in=1, c_out=1, in_from=1),
+              N.Layer(op=N.OP_FC, c_in=1, c_out=2, in_from=2)]
+    f = np.float32
+    weights = [(np.full((1, 1, 1, 1), 515 / 512, f), np.array([31 / 128], f)),
+               (np.full((1, 1, 1, 1), 0.5, f), np.zeros(1, f)),
+               (None, None),
+               (np.array([[515 / 512], [-2.0]], f), np.array([2.0 ** -8, 0.0], f))]
+    x = np.array([[[2.0, 7.0], [3.0, 1 + 2.0 ** -8]]], f)
+    logits, outs = F.forward(layers, weights, x, "bf16", return_all=True)
+    np.testing.assert_array_equal(outs[0].ravel(), np.array([2.25, 7.3125, 3.265625, 1.25], f))
+    np.testing.assert_array_equal(outs[1].ravel(), np.array([3.375, 11.0, 4.90625, 1.875], f))
+    np.testing.assert_array_equal(outs[2].ravel(), np.array([5.28125], f))
+    np.testing.assert_array_equal(logits, np.array([21817 / 4096, -10.5625], f))
+    # the same toy in fp32 mode rounds nowhere: 515/512 * x + 31/128 etc. stay as computed
+    l32, o32 = F.forward(layers, weights, x, "fp32", return_all=True)
+    np.testing.assert_array_equal(o32[0].ravel(), (np.array([2.0, 7.0, 3.0, 1 + 2.0 ** -8]) * (515 / 512) + 31 / 128).astype(f))
+    assert l32[1] == f(-2.0) * o32[2].ravel()[0]
