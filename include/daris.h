@@ -52,15 +52,19 @@ enum {
   DARIS_NO_PRIOR = 8,         /* ablation ("No Prior"): a missed predecessor gives no extra level              */
   DARIS_NO_FIXED = 16,        /* ablation ("No Fixed"): all stages share one level, EDF only                   */
   DARIS_HP_ADMISSION = 32,    /* Overload+HPA (Sec. VI-I): HP jobs must pass the test in their own context     */
-  DARIS_KEEP_ACTIVATIONS = 64, /* debugging: one buffer per layer output so daris_read_layer works             */
+  DARIS_KEEP_ACTIVATIONS = 64, /* debugging: one buffer per layer output so daris_read_layer (daris_debug.h) works */
   DARIS_WAVE_PRIORITY = 128,  /* the convolution waves of high-priority tasks raise their issue priority on the CU:
                                  where partitions overlap, HP stages run faster and LP stages slower (measured:
                                  HP response -5 %, LP +12 %, aggregate throughput -2 %); off by default          */
-  DARIS_SHARED_QUEUE = 256    /* the N_s streams of a partition feed ONE hardware queue instead of one each: their
+  DARIS_SHARED_QUEUE = 256,   /* the N_s streams of a partition feed ONE hardware queue instead of one each: their
                                  stages execute one after the other, but the next one is already queued when a
                                  stage ends, so the host round trip of the boundary is hidden.  For GPUs on which
                                  only a few hardware queues make progress at a time; scheduling decisions (and the
                                  trace) are those of N_s streams; off by default                                */
+  DARIS_NO_PAIR = 512,        /* tasks registered under this flag launch a residual block's shortcut convolution and
+                                 first convolution separately instead of in one two-problem launch (A/B and tests)  */
+  DARIS_NO_FUSED_INGEST = 1024 /* ... and convert the input layout in a launch of its own instead of inside the first
+                                 convolution                                                                     */
 };
 
 enum { DARIS_LP = 0, DARIS_HP = 1 };
@@ -143,6 +147,13 @@ daris_status daris_init(int device, uint64_t seed, int flags);
 /* Wait for running work, stop the worker threads, free every queue, signal and device buffer. */
 daris_status daris_shutdown(void);
 const char* daris_last_error(void);
+/* Bound, in nanoseconds (> 0, default 20 s, process-wide, kept across daris_init), on every wait of the host for the GPU: a
+ * stage boundary, a direct execution, room in a queue.  When it expires -- or when the runtime reports an error on a queue
+ * -- the call that waited returns DARIS_EHIP (a scheduled run: daris_run_until_idle and the blocking run calls do), and
+ * because the state of the GPU work is unknown from then on, every later call except daris_shutdown, daris_last_error and
+ * the read-only accessors returns DARIS_EHIP too.  daris_shutdown then lets the queues run dry for at most 5 s each before
+ * it frees the buffers. */
+daris_status daris_set_timeout(int64_t ns);
 
 /* ---- partitions (Sec. III-C) ------------------------------------------------------------------------------- */
 
@@ -169,15 +180,6 @@ daris_task daris_register_task(const daris_dnn* dnn, int64_t period_ns, int64_t 
 daris_status daris_split_stages(daris_task t, int k);
 /* Writes the index of the first layer of each stage into first_layer[0..cap) and returns the stage count. */
 int32_t daris_get_stage_cuts(daris_task t, int32_t* first_layer, int32_t cap);
-/* Launch plan of one layer, for inspection and for host-side checks of what the kernels assume (no device needed).
- * Writes 24 values into out (host int64[cap >= 24]) and returns 24: [0] kernel id (daris_kernel_name), [1] 1 = dense
- * convolution (the rest is meaningful only then), [2] 1 (one kernel family), [3] M = output
- * pixels, [4] N = output channels incl. padding, [5] K, [6] K padded, [7] channel blocks of 32 per wave tile, [8] waves
- * per workgroup, [9] K steps in total, [10] per workgroup slice, [11] per wave, [12] split-K factor, [13] pixel tiles,
- * [14] channel tiles, [15] weight groups, [16] workgroup order mode, [17..19] grid x y z, [20] threads per workgroup,
- * [21] split-K workspace bytes, [22] layer it shares a launch with or -1, [23] 1 = the joint launch is issued at this
- * layer. */
-int32_t daris_get_launch_plan(daris_task t, int layer, int64_t* out, int32_t cap);
 /* Per-stage AFET (Sec. IV-A1), ns > 0: the execution-time estimate used until the stage has run once. */
 daris_status daris_set_afet(daris_task t, int stage, int64_t ns);
 /* MRET window size ws (eq. 1), default 5. */
@@ -231,38 +233,11 @@ int64_t daris_trace_read(void* buf, int64_t cap_bytes);
 /* Current MRET of a stage (eq. 1), ns. */
 int64_t daris_get_mret(daris_task t, int stage);
 
-/* ---- direct execution (parity tests, calibration, profiling) --------------------------------------------------- */
+/* ---- direct execution and calibration (instrumentation lives in daris_debug.h) --------------------------------- */
 
 /* Run the whole DNN of task t once, stage after stage, on stream 0 of partition p, and wait for it.  No scheduler
  * state is touched.  The logits do not depend on p or on the stage split. */
 daris_status daris_forward(daris_task t, const void* d_input, void* d_logits, daris_part p);
-/* After daris_forward with DARIS_KEEP_ACTIVATIONS: copy layer l's output to host float[c][h][w]. */
-daris_status daris_read_layer(daris_task t, int layer, float* host_out, int64_t cap_elems);
-/* Time each layer of task t on stream 0 of partition p: `reps` runs back to back, from the start time stamp of the
- * first dispatch to the end time stamp of the last, divided by reps (the earlier layer of a launch pair reports 0).
- * ms_per_layer = host float[n_layers]; kernel_id = host int32[n_layers] (which kernel variant ran, see
- * daris_kernel_name); flops = host double[n_layers] algorithmic FLOPs (2*MACs) of the layer. */
-daris_status daris_profile_layers(daris_task t, daris_part p, int reps, float* ms_per_layer, int32_t* kernel_id,
-                                  double* flops);
-const char* daris_kernel_name(int32_t kernel_id);
-/* Kernel timing by sampling, for roofline figures measured inside a scheduled run: from now on every `every`-th job
- * of each task (0 = off) has every launch complete a signal of its own, into which the command processor of the
- * queue the kernel runs on writes the start and end time stamp of that dispatch (the figures a kernel trace shows);
- * for at most about max_samples launches.  Sampled jobs run slightly slower (one signal per launch). */
-daris_status daris_kernel_timing_start(int every, int max_samples);
-/* Waits until idle, stops the sampling and sums the samples per kernel id: launches[id], total_ms[id], total_flops[id]
- * (algorithmic FLOPs, 2*MACs) for id < the returned count; the arrays (host) must hold `cap` >= 64 entries.
- * *empty_pair_ms (may be NULL) receives the fixed cost contained in every sample: 0 for dispatch time stamps. */
-int32_t daris_kernel_timing_read(int32_t cap, int64_t* launches, double* total_ms, double* total_flops, double* empty_pair_ms);
-/* Where the wall time of a stage goes in real-time mode (the price of the synchronisation point at each stage
- * boundary, Sec. III-B1).  Waits until idle, copies the totals gathered since the last call to out (host int64[8], may
- * be NULL), clears them, and switches the gathering on (enable != 0) or off.  While it is on, the first launch of each
- * stage completes a signal too.  out[0] stages executed; [1] host ns enqueueing the stage's kernels;
- * [2] host ns from the last enqueue until the completion signal was seen; [3] host ns from then until the scheduler lock
- * was held; [4] host ns in the decision core and the hand-over of the next stages; [5] GPU ns from the start time stamp
- * of the stage's first dispatch to the end time stamp of its last; [6] host ns between a dispatch pass handing a stage to a stream's
- * worker and the worker starting to enqueue it; [7] reserved. */
-daris_status daris_driver_profile(int enable, int64_t* out);
 /* Measure per-stage execution times of task t alone on partition p (`reps` runs, the maximum is kept) and store
  * them as the task's AFET values. */
 daris_status daris_calibrate_afet(daris_task t, daris_part p, int reps);
@@ -271,12 +246,6 @@ daris_status daris_calibrate_afet(daris_task t, daris_part p, int reps);
  * partition runs one forward pass of a distinct other task drawn with the generator seeded by daris_init's seed;
  * the per-stage averages over `reps` runs become the task's AFET values.  Call while no job is active. */
 daris_status daris_calibrate_afet_loaded(daris_task t, daris_part p, int reps);
-/* Mask probing: launch n_groups (<= 65536) short workgroups on stream 0 of partition p; out = host
- * uint32[2 * n_groups] receives, per workgroup, the XCC (die) id and the hardware id register of the compute unit
- * it ran on.  `spin` (0..100000) bounds a sleep loop that keeps workgroups resident so that they spread over
- * every CU the mask allows. */
-daris_status daris_probe_cus(daris_part p, int n_groups, int spin, uint32_t* out);
-
 #ifdef __cplusplus
 }
 #endif

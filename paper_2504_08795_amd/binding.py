@@ -13,6 +13,7 @@ LIB_PATH = os.environ.get("DARIS_LIB") or os.path.join(_HERE, "libdaris.so")   #
 
 OK, EINVAL, ENOMEM, EHIP, ESTATE, ERANGE = 0, -1, -2, -3, -4, -5
 VIRTUAL_TIME, NO_DEVICE, NO_LAST, NO_PRIOR, NO_FIXED, HP_ADMISSION, KEEP_ACTIVATIONS, WAVE_PRIORITY, SHARED_QUEUE = 1, 2, 4, 8, 16, 32, 64, 128, 256
+NO_PAIR, NO_FUSED_INGEST = 512, 1024
 LP, HP = 0, 1
 FP32, BF16 = 0, 1
 ACCEPTED, MIGRATED, REJECT_ADMISSION, REJECT_OVERRUN, QUEUED = 1, 2, 3, 4, 5
@@ -51,6 +52,7 @@ _lib = None
 _SIGS = {
     "daris_init": (C.c_int32, [C.c_int, C.c_uint64, C.c_int]),
     "daris_shutdown": (C.c_int32, []),
+    "daris_set_timeout": (C.c_int32, [C.c_int64]),
     "daris_last_error": (C.c_char_p, []),
     "daris_cu_per_partition": (C.c_int32, [C.c_int32] * 4),
     "daris_create_partition": (C.c_int32, [C.c_int]),
@@ -127,6 +129,10 @@ def daris_shutdown():
     return _chk(lib().daris_shutdown())
 
 
+def daris_set_timeout(ns):
+    return _chk(lib().daris_set_timeout(int(ns)))
+
+
 def daris_cu_per_partition(os_num, os_den, n_cu_max, n_c):
     return _chk(lib().daris_cu_per_partition(os_num, os_den, n_cu_max, n_c))
 
@@ -183,12 +189,12 @@ def daris_get_stage_cuts(t):
 
 
 PLAN_FIELDS = ("kernel_id", "dense_conv", "wave", "M", "N", "K", "Kpad", "tn", "nw", "S", "sz", "sw", "splitk", "MT", "NTn", "G", "xmode",
-               "grid_x", "grid_y", "grid_z", "threads", "ws_bytes", "pair_with", "pair_lead")
+               "grid_x", "grid_y", "grid_z", "threads", "ws_bytes", "pair_with", "pair_lead", "out_slot", "in_slot", "res_slot")
 
 
 def daris_get_launch_plan(t, layer):
-    buf = (C.c_int64 * 24)()
-    _chk(lib().daris_get_launch_plan(t, layer, buf, 24))
+    buf = (C.c_int64 * 27)()
+    _chk(lib().daris_get_launch_plan(t, layer, buf, 27))
     return dict(zip(PLAN_FIELDS, (int(v) for v in buf)))
 
 

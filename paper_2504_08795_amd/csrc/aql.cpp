@@ -3,6 +3,7 @@
 #include <cxxabi.h>
 #include <hip/hip_runtime.h>
 
+#include <chrono>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -215,9 +216,40 @@ bool AqlRuntime::dispatch_time_us(hsa_signal_t s, double* start_us, double* end_
   return true;
 }
 
+void AqlQueue::on_error(hsa_status_t, hsa_queue_t*, void* data) {
+  // called by the runtime's own thread when the queue goes inactive (a fault in a kernel, a malformed packet)
+  static_cast<AqlQueue*>(data)->dead_.store(true, std::memory_order_release);
+}
+
+bool AqlQueue::drain(hsa_signal_t s, int64_t limit_ns) {
+  if (!q_ || !s.handle) return false;
+  bool ok = false;
+  const int64_t saved = aql_wait_limit_ns();
+  aql_set_wait_limit_ns(limit_ns);
+  const uint64_t idx = dead() ? kNoSlot : claim_slot();
+  if (idx != kNoSlot) {
+    hsa_barrier_and_packet_t* p = (hsa_barrier_and_packet_t*)q_->base_address + (idx & (q_->size - 1));
+    p->reserved0 = 0;
+    p->reserved1 = 0;
+    for (int i = 0; i < 5; ++i) p->dep_signal[i] = hsa_signal_t{0};
+    p->reserved2 = 0;
+    p->completion_signal = s;
+    const uint16_t header = (uint16_t)((HSA_PACKET_TYPE_BARRIER_AND << HSA_PACKET_HEADER_TYPE) | (1u << HSA_PACKET_HEADER_BARRIER) |
+                                       (HSA_FENCE_SCOPE_SYSTEM << HSA_PACKET_HEADER_SCACQUIRE_FENCE_SCOPE) |
+                                       (HSA_FENCE_SCOPE_SYSTEM << HSA_PACKET_HEADER_SCRELEASE_FENCE_SCOPE));
+    __atomic_store_n((uint16_t*)p, header, __ATOMIC_RELEASE);
+    hsa_signal_store_screlease(q_->doorbell_signal, (hsa_signal_value_t)idx);
+    ok = aql_spin(s, this);
+  }
+  aql_set_wait_limit_ns(saved);
+  if (ok) hsa_signal_destroy(s);  // a signal the GPU may still write is left alone
+  return ok;
+}
+
 std::string AqlQueue::create(AqlRuntime* rt, const uint32_t mask[8]) {
   rt_ = rt;
-  hsa_status_t st = hsa_queue_create(rt->gpu(), kSlots, HSA_QUEUE_TYPE_SINGLE, nullptr, nullptr, UINT32_MAX, UINT32_MAX, &q_);
+  dead_.store(false);
+  hsa_status_t st = hsa_queue_create(rt->gpu(), kSlots, HSA_QUEUE_TYPE_SINGLE, &AqlQueue::on_error, this, UINT32_MAX, UINT32_MAX, &q_);
   if (st != HSA_STATUS_SUCCESS) {
     q_ = nullptr;
     return hsa_err("hsa_queue_create", st);
@@ -280,35 +312,70 @@ void AqlQueue::write_packet(uint64_t idx, const AqlKernel& k, uint32_t groups, u
 // Next packet index.  Waits while the ring is full but for one slot, so that the packet which used this slot (and its
 // argument slot) before has not only been fetched but, the queue being in order, has completed.
 uint64_t AqlQueue::claim_slot() {
-  const uint64_t idx = hsa_queue_add_write_index_relaxed(q_, 1);
-  while (idx - hsa_queue_load_read_index_scacquire(q_) >= q_->size - 1) {
+  // one producer at a time, so the index can be read first and taken only once there is room
+  const uint64_t idx = hsa_queue_load_write_index_relaxed(q_);
+  if (idx - hsa_queue_load_read_index_scacquire(q_) >= q_->size - 1) {
+    const auto t0 = std::chrono::steady_clock::now();
+    const int64_t limit = aql_wait_limit_ns();
+    for (uint32_t spins = 0; idx - hsa_queue_load_read_index_scacquire(q_) >= q_->size - 1; ++spins) {
+      if (dead()) return kNoSlot;
+      if ((spins & 1023u) == 1023u &&
+          std::chrono::duration_cast<std::chrono::nanoseconds>(std::chrono::steady_clock::now() - t0).count() > limit)
+        return kNoSlot;
+      __builtin_ia32_pause();
+    }
   }
+  hsa_queue_store_write_index_relaxed(q_, idx + 1);
   return idx;
 }
 
 bool AqlQueue::dispatch(const AqlKernel& k, uint32_t groups, uint32_t threads, const void* kernarg, hsa_signal_t completion, unsigned flags) {
-  if (!q_ || !kernarg || groups == 0 || threads == 0 || threads > 1024 || (uint64_t)groups * threads > 0xffffffffull) return false;
-  write_packet(claim_slot(), k, groups, threads, kernarg, completion, flags);
+  if (!q_ || dead() || !kernarg || groups == 0 || threads == 0 || threads > 1024 || (uint64_t)groups * threads > 0xffffffffull) return false;
+  const uint64_t idx = claim_slot();
+  if (idx == kNoSlot) return false;
+  write_packet(idx, k, groups, threads, kernarg, completion, flags);
   return true;
 }
 
 bool AqlQueue::dispatch_copy(const AqlKernel& k, uint32_t groups, uint32_t threads, const void* args, uint32_t bytes, hsa_signal_t completion,
                              unsigned flags) {
-  if (!q_ || bytes != k.kernarg_size || bytes > kSlotBytes || groups == 0 || threads == 0 || threads > 1024 ||
+  if (!q_ || dead() || bytes != k.kernarg_size || bytes > kSlotBytes || groups == 0 || threads == 0 || threads > 1024 ||
       (uint64_t)groups * threads > 0xffffffffull)
     return false;
   const uint64_t idx = claim_slot();
+  if (idx == kNoSlot) return false;
   char* slot = ring_ + (size_t)(idx & (kSlots - 1)) * kSlotBytes;
   std::memcpy(slot, args, bytes);
   write_packet(idx, k, groups, threads, slot, completion, flags);
   return true;
 }
 
-void aql_wait(hsa_signal_t s) {
-  while (hsa_signal_load_scacquire(s) != 0) {
+namespace {
+std::atomic<int64_t> g_wait_limit_ns{20ll * 1000 * 1000 * 1000};  // 20 s: far above any stage of the configured networks
+}
+
+void aql_set_wait_limit_ns(int64_t ns) { g_wait_limit_ns.store(ns < 1 ? 1 : ns, std::memory_order_relaxed); }
+int64_t aql_wait_limit_ns() { return g_wait_limit_ns.load(std::memory_order_relaxed); }
+
+bool aql_spin(hsa_signal_t s, const AqlQueue* q, const std::atomic<bool>* stop) {
+  if (aql_done(s)) return true;
+  const auto t0 = std::chrono::steady_clock::now();
+  const int64_t limit = aql_wait_limit_ns();
+  for (uint32_t spins = 0;; ++spins) {
     for (int i = 0; i < 8; ++i) __builtin_ia32_pause();
+    if (aql_done(s)) return true;
+    if ((spins & 255u) == 255u) {  // the clock and the flags every ~10 us only: the common case is a wait of microseconds
+      if (q && q->dead()) return false;
+      if (stop && stop->load(std::memory_order_relaxed)) return false;
+      if (std::chrono::duration_cast<std::chrono::nanoseconds>(std::chrono::steady_clock::now() - t0).count() > limit) return aql_done(s);
+    }
   }
+}
+
+bool aql_wait(hsa_signal_t s, const AqlQueue* q) {
+  if (!aql_spin(s, q)) return false;
   hsa_signal_store_relaxed(s, 1);
+  return true;
 }
 
 }  // namespace daris

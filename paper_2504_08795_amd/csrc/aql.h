@@ -14,6 +14,7 @@
 #include <hsa/hsa.h>
 #include <hsa/hsa_ext_amd.h>
 
+#include <atomic>
 #include <cstdint>
 #include <string>
 #include <unordered_map>
@@ -64,6 +65,11 @@ class AqlQueue {
   std::string create(AqlRuntime* rt, const uint32_t mask[8]);
   void destroy();
   bool valid() const { return q_ != nullptr; }
+  // The runtime reported an error on this queue (its packet processor stopped): nothing queued on it will complete.
+  bool dead() const { return dead_.load(std::memory_order_acquire); }
+  // Appends a barrier packet that completes `s` (a fresh signal of value 1, destroyed here) once every earlier packet
+  // has completed, and waits for it for at most limit_ns.  True when the queue ran dry in time.
+  bool drain(hsa_signal_t s, int64_t limit_ns);
 
   enum : unsigned {
     kReleaseSystem = 1,  // when the kernel completes its writes are visible to the host too (default: to this device)
@@ -86,16 +92,27 @@ class AqlQueue {
  private:
   static constexpr uint32_t kSlots = 1024;     // packets in the ring = argument slots of dispatch_copy
   static constexpr uint32_t kSlotBytes = 384;  // >= the largest argument block (two convolution problems: 324)
+  static void on_error(hsa_status_t status, hsa_queue_t* source, void* data);
+  // Next packet index, or kNoSlot when the ring stayed full for the whole wait limit (or the queue is dead).
+  static constexpr uint64_t kNoSlot = ~0ull;
   uint64_t claim_slot();
   void write_packet(uint64_t idx, const AqlKernel& k, uint32_t groups, uint32_t threads, const void* kernarg, hsa_signal_t completion,
                     unsigned flags);
   AqlRuntime* rt_ = nullptr;
   hsa_queue_t* q_ = nullptr;
   char* ring_ = nullptr;  // host-coherent argument slots
+  std::atomic<bool> dead_{false};
 };
 
-// Spins until the signal reads 0 (its dispatch has completed), then re-arms it to 1.
-void aql_wait(hsa_signal_t s);
+// Every host wait for the GPU is bounded: a kernel that never completes (or a queue whose packet processor has stopped)
+// must surface as an error code, not as a hung thread.  The limit is process-wide, in nanoseconds.
+void aql_set_wait_limit_ns(int64_t ns);
+int64_t aql_wait_limit_ns();
 inline bool aql_done(hsa_signal_t s) { return hsa_signal_load_scacquire(s) == 0; }
+// Spins until the signal reads 0 (its dispatch has completed).  False when the wait limit expired first, when `q` (may be
+// null) reported an error, or when *stop (may be null) became true.
+bool aql_spin(hsa_signal_t s, const AqlQueue* q = nullptr, const std::atomic<bool>* stop = nullptr);
+// aql_spin, then re-arms the signal to 1 on success.
+bool aql_wait(hsa_signal_t s, const AqlQueue* q = nullptr);
 
 }  // namespace daris

@@ -24,6 +24,7 @@
 #include <vector>
 
 #include "../../include/daris.h"
+#include "../../include/daris_debug.h"
 #include "aql.h"
 #include "kernels.h"
 #include "net_plan.h"
@@ -161,6 +162,10 @@ struct Global {
   std::atomic<bool> stop_flag{false};  // mirrors `stop` for the workers' lock-free spin
   std::chrono::steady_clock::time_point epoch;
   std::string async_error;
+  // A wait for the GPU ran into the limit, or a queue reported an error: what the GPU still does with the buffers is
+  // unknown, so every later call but daris_shutdown (and the read-only accessors) is refused.
+  std::atomic<bool> failed{false};
+  std::string failed_why;
   int tm_every = 0;                 // kernel timing: sample every n-th job of a task, 0 = off
   int64_t tm_left = 0;              // samples still to take
   int64_t tm_launches[K_COUNT] = {0};
@@ -184,13 +189,13 @@ AqlRuntime g_rt;
 KernelTable g_kt;
 int g_rt_device = -1;
 
-ConvArgs conv_args(TaskRt& T, int l, void* y) {
+ConvArgs conv_args(TaskRt& T, int l, void* y, const std::vector<void*>& slots, float* ws) {
   NetPlan& net = T.net;
   LayerPlan& L = net.layers[l];
   const TensorInfo& in = net.tensor(L.in_t);
   ConvArgs a;
-  a.x = T.slots[in.slot]; a.w = L.w_dev; a.bias = L.b_dev; a.y = y; a.ws = T.ws; a.wave_prio = (T.prio == DARIS_HP && (G->flags & DARIS_WAVE_PRIORITY)) ? 1 : 0;
-  a.res = L.res_t >= 0 ? T.slots[net.tensor(L.res_t).slot] : nullptr;
+  a.x = slots[in.slot]; a.w = L.w_dev; a.bias = L.b_dev; a.y = y; a.ws = ws; a.wave_prio = (T.prio == DARIS_HP && (G->flags & DARIS_WAVE_PRIORITY)) ? 1 : 0;
+  a.res = L.res_t >= 0 ? slots[net.tensor(L.res_t).slot] : nullptr;
   a.H = in.H; a.W = in.W; a.Cin = in.Cs; a.Ho = L.out.H; a.Wo = L.out.W; a.Cout = L.out.Cs;
   a.kh = a.kw = L.d.k; a.stride = L.d.stride; a.pad = L.d.pad;
   a.K = L.K; a.Kpad = L.Kpad; a.M = L.out.H * L.out.W; a.act = L.d.act;
@@ -205,40 +210,48 @@ ConvArgs conv_args(TaskRt& T, int l, void* y) {
   return a;
 }
 
-// Encodes the whole network of T as launches (weights, activation buffers and workspace must exist) and uploads their
-// argument blocks.  The two pointers that change from job to job (the input of the first launch, the logits of the last)
-// stay null in these blocks; a job brings its own copies of the two blocks (JobIo).  Returns "" or an error text.
-std::string build_launches(TaskRt& T) {
+// Where the launch sequence of a network reads a job's input and writes its logits.
+struct IoLaunches {
+  int in_launch = -1, out_launch = -1;  // indices into the launch sequence
+  uint32_t in_off = 0, out_off = 0;     // byte offset of that pointer inside the argument block
+};
+
+// Encodes the whole network of T as launches in execution order, with its activation tensors in `slots` (one device
+// buffer per slot of the plan) and its split-K partial sums in `ws`; the weights must be on the device.  The two pointers
+// that change from job to job (the input of the first launch, the logits of the last) stay null in the argument blocks.
+// Returns "" or an error text.
+std::string encode_network(TaskRt& T, const std::vector<void*>& slots, float* ws, std::vector<LaunchRt>* launches, std::vector<int>* layer_lo,
+                           IoLaunches* iol) {
   NetPlan& net = T.net;
   const int n = (int)net.layers.size();
   const int bf16 = net.bf16;
   std::vector<KernelLaunch> ks;
-  T.launches.clear();
-  T.layer_lo.assign(n + 1, 0);
-  T.in_launch = T.out_launch = -1;
+  launches->clear();
+  layer_lo->assign(n + 1, 0);
+  *iol = IoLaunches();
   auto take = [&](double flops) {
     for (size_t i = 0; i < ks.size(); ++i) {
       LaunchRt r;
       r.kl = ks[i];
       r.flops = i == 0 ? flops : 0;
-      T.launches.push_back(r);
+      launches->push_back(r);
     }
     ks.clear();
   };
   if (!net.fuse_ingest) {
-    if (!encode_ingest(g_kt, nullptr, T.slots[net.ingest.slot], net.ingest.C, net.ingest.Cs, net.ingest.H, net.ingest.W, bf16, &ks))
+    if (!encode_ingest(g_kt, nullptr, slots[net.ingest.slot], net.ingest.C, net.ingest.Cs, net.ingest.H, net.ingest.W, bf16, &ks))
       return "input conversion launch";
-    T.in_launch = 0;
-    T.in_off = kIngestInputOffset;
+    iol->in_launch = 0;
+    iol->in_off = kIngestInputOffset;
     take(0);
   }
   for (int l = 0; l < n; ++l) {
-    T.layer_lo[l] = (int)T.launches.size();
+    (*layer_lo)[l] = (int)launches->size();
     LayerPlan& L = net.layers[l];
     const TensorInfo& in = net.tensor(L.in_t);
-    const void* x = T.slots[in.slot];
+    const void* x = slots[in.slot];
     const bool direct = l == n - 1 && net.final_direct;  // writes the job's logits
-    void* y = direct ? nullptr : T.slots[L.out.slot];
+    void* y = direct ? nullptr : slots[L.out.slot];
     bool ok = false;
     double flops = 0;
     switch (L.d.op) {
@@ -252,18 +265,18 @@ std::string build_launches(TaskRt& T) {
         } else if (L.pair_with >= 0 && !L.pair_lead) {
           ok = true;  // issued together with the next layer
         } else {
-          const ConvArgs a = conv_args(T, l, y);
+          const ConvArgs a = conv_args(T, l, y, slots, ws);
           flops = 2.0 * (double)L.macs;
           if (L.pair_with >= 0) {
             LayerPlan& O = net.layers[L.pair_with];
-            const ConvArgs b = conv_args(T, L.pair_with, T.slots[O.out.slot]);
+            const ConvArgs b = conv_args(T, L.pair_with, slots[O.out.slot], slots, ws);
             flops += 2.0 * (double)O.macs;
             // the heavier convolution is the first problem (its plan was kept)
             ok = L.macs >= O.macs ? encode_conv_pair(g_kt, L.cp, a, O.cp, b, bf16, &ks) : encode_conv_pair(g_kt, O.cp, b, L.cp, a, bf16, &ks);
           } else {
             if (l == 0 && net.fuse_ingest) {
-              T.in_launch = (int)T.launches.size();
-              T.in_off = kConvInputOffset;
+              iol->in_launch = (int)launches->size();
+              iol->in_off = kConvInputOffset;
             }
             ok = encode_conv(g_kt, L.cp, a, bf16, &ks);
           }
@@ -283,8 +296,8 @@ std::string build_launches(TaskRt& T) {
         a.K = L.K; a.N = L.d.c_out; a.Ns = direct ? L.d.c_out : L.out.Cs;
         a.act = L.d.act; a.out_f32 = direct ? 1 : 0;
         if (direct) {
-          T.out_launch = (int)T.launches.size();
-          T.out_off = kFcOutputOffset;
+          iol->out_launch = (int)launches->size();
+          iol->out_off = kFcOutputOffset;
         }
         ok = encode_fc(g_kt, a, bf16, &ks);
         break;
@@ -293,14 +306,27 @@ std::string build_launches(TaskRt& T) {
     if (!ok) return "launch of layer " + std::to_string(l) + " (" + kernel_name(L.kernel_id) + ")";
     take(flops);
   }
-  T.layer_lo[n] = (int)T.launches.size();
+  (*layer_lo)[n] = (int)launches->size();
   if (!net.final_direct) {
     const TensorInfo& o = net.layers[n - 1].out;
-    if (!encode_egress(g_kt, T.slots[o.slot], nullptr, o.C, o.Cs, o.H, o.W, bf16, &ks)) return "output conversion launch";
-    T.out_launch = (int)T.launches.size();
-    T.out_off = kEgressOutputOffset;
+    if (!encode_egress(g_kt, slots[o.slot], nullptr, o.C, o.Cs, o.H, o.W, bf16, &ks)) return "output conversion launch";
+    iol->out_launch = (int)launches->size();
+    iol->out_off = kEgressOutputOffset;
     take(0);
   }
+  return "";
+}
+
+// Encodes T's network on its own buffers and uploads the argument blocks into one device buffer; a job brings its own
+// copies of the two job-dependent blocks (JobIo).  Returns "" or an error text.
+std::string build_launches(TaskRt& T) {
+  IoLaunches iol;
+  std::string err = encode_network(T, T.slots, T.ws, &T.launches, &T.layer_lo, &iol);
+  if (!err.empty()) return err;
+  T.in_launch = iol.in_launch;
+  T.out_launch = iol.out_launch;
+  T.in_off = iol.in_off;
+  T.out_off = iol.out_off;
   // one device buffer for all argument blocks, 64 bytes apart at least
   std::vector<unsigned char> img;
   std::vector<size_t> off;
@@ -475,10 +501,14 @@ int64_t finish_stage(TaskRt& T, StreamRt& S) {
   return span_ns;
 }
 
-void spin_until_done(hsa_signal_t sg) {
-  while (!aql_done(sg)) {
-    for (int i = 0; i < 8; ++i) __builtin_ia32_pause();
-  }
+// Marks the library failed (under G->mu or from the API thread) and returns the status for the caller.
+daris_status gpu_wait_failed(const StreamRt& S, const char* what) {
+  const bool dead = S.hw && S.hw->q.dead();
+  char buf[256];
+  snprintf(buf, sizeof buf, "%s: %s; the library accepts no further work (daris_shutdown only)", what,
+           dead ? "the queue reported an error" : "the GPU did not complete it within the wait limit (daris_set_timeout)");
+  if (!G->failed.exchange(true)) G->failed_why = buf;
+  return fail(DARIS_EHIP, "%s", buf);
 }
 
 // API thread, G->mu held: runs launches [lo, hi) of T on S and waits for them.
@@ -492,7 +522,7 @@ daris_status run_direct(TaskRt& T, int lo, int hi, const JobIo& io, StreamRt& S)
     err = enqueue_range(T, lo, hi, io, S, o);
   }
   if (err) return fail(DARIS_EHIP, "%s", err);
-  aql_wait(G->util_sig);
+  if (!aql_wait(G->util_sig, &S.hw->q)) return gpu_wait_failed(S, "direct execution");
   return DARIS_OK;
 }
 
@@ -505,7 +535,7 @@ daris_status run_one(const std::vector<KernelLaunch>& ks, StreamRt& S) {
       ok = S.hw->q.dispatch_copy(*ks[i].k, ks[i].groups, ks[i].threads, ks[i].args, ks[i].nbytes, G->util_sig, AqlQueue::kReleaseSystem | AqlQueue::kAcquireSystem);
     }
     if (!ok) return fail(DARIS_EHIP, "packet rejected");
-    aql_wait(G->util_sig);
+    if (!aql_wait(G->util_sig, &S.hw->q)) return gpu_wait_failed(S, "direct launch");
   }
   return DARIS_OK;
 }
@@ -541,7 +571,7 @@ daris_status issue(const std::vector<Launch>& ls, int64_t t) {
           err = enqueue_stage(T, l.stage, io->second, S, sample, false);
         }
         if (err) return fail(DARIS_EHIP, "stage execution: %s", err);
-        spin_until_done(S.done);
+        if (!aql_spin(S.done, &S.hw->q)) return gpu_wait_failed(S, "stage execution");
         finish_stage(T, S);
       } else {
         // real time: the stream's own worker enqueues the kernels and watches the boundary signal
@@ -645,15 +675,25 @@ void worker_loop(StreamRt* S) {
       err = enqueue_stage(T, l.stage, io, *S, sample, prof);
     }
     const int64_t t1 = prof ? now_ns() : 0;
-    if (!err) spin_until_done(S->done);
+    const bool completed = !err && aql_spin(S->done, &S->hw->q, &G->stop_flag);
     const int64_t t2 = prof ? now_ns() : 0;
     lk.lock();
+    if (G->stop) return;
     int64_t gpu_ns = 0;
-    if (err) {
-      if (G->async_error.empty()) G->async_error = std::string("stage execution: ") + err;
-    } else {
-      gpu_ns = finish_stage(T, *S);
+    if (err || !completed) {
+      // The stage did not run to its boundary: the decision core keeps it as running, nothing more is dispatched, and
+      // whoever waits for idleness gets the error.  This worker ends here.
+      if (err) {
+        if (G->async_error.empty()) G->async_error = std::string("stage execution: ") + err;
+        if (!G->failed.exchange(true)) G->failed_why = G->async_error;
+      } else {
+        gpu_wait_failed(*S, "stage execution");
+        if (G->async_error.empty()) G->async_error = G->failed_why;
+      }
+      G->cv_idle.notify_all();
+      return;
     }
+    gpu_ns = finish_stage(T, *S);
     const int64_t now = now_ns();
     if (prof) {
       G->prof_acc[0] += 1;
@@ -685,13 +725,21 @@ void worker_loop(StreamRt* S) {
   }
 }
 
-daris_status check_task(daris_task t) {
+daris_status check_failed() {
+  if (G && G->failed.load()) return fail(DARIS_EHIP, "%s", G->failed_why.c_str());
+  return DARIS_OK;
+}
+
+// `observe`: a read-only accessor, allowed in the failed state too
+daris_status check_task(daris_task t, bool observe = false) {
   if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
+  if (!observe && check_failed() != DARIS_OK) return DARIS_EHIP;
   if (t < 0 || t >= (int)G->tasks.size()) return fail(DARIS_ERANGE, "task handle %d out of range", t);
   return DARIS_OK;
 }
-daris_status check_part(daris_part p) {
+daris_status check_part(daris_part p, bool observe = false) {
   if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
+  if (!observe && check_failed() != DARIS_OK) return DARIS_EHIP;
   if (p < 0 || p >= (int)G->parts.size()) return fail(DARIS_ERANGE, "partition handle %d out of range", p);
   return DARIS_OK;
 }
@@ -699,9 +747,10 @@ daris_status check_part(daris_part p) {
 daris_status wait_idle() {
   std::unique_lock<std::mutex> lk(G->mu);
   while (!G->core.idle()) {
-    if (!G->async_error.empty()) break;
+    if (!G->async_error.empty() || G->failed.load()) break;
     G->cv_idle.wait_for(lk, std::chrono::milliseconds(1));
   }
+  if (G->failed.load() && G->async_error.empty()) G->async_error = G->failed_why;
   if (!G->async_error.empty()) {
     daris_status st = fail(DARIS_EHIP, "%s", G->async_error.c_str());
     G->async_error.clear();
@@ -783,6 +832,12 @@ daris_status daris_init(int device, uint64_t seed, int flags) {
   return DARIS_OK;
 }
 
+daris_status daris_set_timeout(int64_t ns) {
+  if (ns < 1) return fail(DARIS_EINVAL, "the wait limit must be positive");
+  aql_set_wait_limit_ns(ns);
+  return DARIS_OK;
+}
+
 daris_status daris_shutdown(void) {
   if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
   {
@@ -796,6 +851,13 @@ daris_status daris_shutdown(void) {
       if (S->thr.joinable()) S->thr.join();
     }
   if (!G->nodev) {
+    // Work that a failed wait left behind may still be executing: let every queue run dry (bounded) before its buffers
+    // are freed; destroying the queue afterwards stops whatever is left on it.
+    if (G->failed.load()) {
+      for (PartRt& P : G->parts)
+        for (auto& S : P.streams)
+          if (S->hw && S->hw->q.valid()) (void)S->hw->q.drain(g_rt.new_signal(1), 5ll * 1000 * 1000 * 1000);
+    }
     (void)hipDeviceSynchronize();
     for (auto& T : G->tasks) free_task(*T);
     for (PartRt& P : G->parts)
@@ -840,7 +902,7 @@ daris_status daris_partition_set_streams(daris_part p, int n_s) {
 }
 
 daris_status daris_partition_get_mask(daris_part p, uint32_t mask_out[8]) {
-  daris_status st = check_part(p);
+  daris_status st = check_part(p, true);
   if (st != DARIS_OK) return st;
   if (!mask_out) return fail(DARIS_EINVAL, "mask_out is NULL");
   std::memcpy(mask_out, G->parts[p].mask, sizeof(uint32_t) * 8);
@@ -849,13 +911,14 @@ daris_status daris_partition_get_mask(daris_part p, uint32_t mask_out[8]) {
 
 daris_task daris_register_task(const daris_dnn* dnn, int64_t period_ns, int64_t deadline_ns, int priority) {
   if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
+  if (check_failed() != DARIS_OK) return DARIS_EHIP;
   if (G->committed) return fail(DARIS_ESTATE, "tasks must be registered before daris_commit");
   if (!dnn) return fail(DARIS_EINVAL, "dnn is NULL");
   if (period_ns <= 0 || deadline_ns <= 0) return fail(DARIS_EINVAL, "period and deadline must be positive");
   if (priority != DARIS_HP && priority != DARIS_LP) return fail(DARIS_EINVAL, "priority must be DARIS_HP or DARIS_LP");
   if (G->tasks.size() >= 65535) return fail(DARIS_ERANGE, "too many tasks");
   std::unique_ptr<TaskRt> T(new TaskRt());
-  std::string err = build_plan(*dnn, G->flags & DARIS_KEEP_ACTIVATIONS, &T->net);
+  std::string err = build_plan(*dnn, G->flags & DARIS_KEEP_ACTIVATIONS, !(G->flags & DARIS_NO_PAIR), !(G->flags & DARIS_NO_FUSED_INGEST), &T->net);
   if (!err.empty()) return fail(DARIS_EINVAL, "%s", err.c_str());
   if (!G->nodev) {
     NetPlan& net = T->net;
@@ -927,7 +990,7 @@ daris_status daris_split_stages(daris_task t, int k) {
 }
 
 int32_t daris_get_stage_cuts(daris_task t, int32_t* first_layer, int32_t cap) {
-  daris_status st = check_task(t);
+  daris_status st = check_task(t, true);
   if (st != DARIS_OK) return st;
   const std::vector<int>& f = G->tasks[t]->net.stage_first;
   for (int i = 0; i < (int)f.size() && i < cap && first_layer; ++i) first_layer[i] = f[i];
@@ -935,19 +998,20 @@ int32_t daris_get_stage_cuts(daris_task t, int32_t* first_layer, int32_t cap) {
 }
 
 int32_t daris_get_launch_plan(daris_task t, int layer, int64_t* out, int32_t cap) {
-  daris_status st = check_task(t);
+  daris_status st = check_task(t, true);
   if (st != DARIS_OK) return st;
   const NetPlan& net = G->tasks[t]->net;
   if (layer < 0 || layer >= (int)net.layers.size()) return fail(DARIS_ERANGE, "layer %d out of range", layer);
-  if (!out || cap < 24) return fail(DARIS_EINVAL, "out must hold 24 entries");
+  if (!out || cap < 27) return fail(DARIS_EINVAL, "out must hold 27 entries");
   const LayerPlan& L = net.layers[layer];
   const ConvPlan& c = L.cp;
   const bool conv = L.d.op == DARIS_OP_CONV && !L.depthwise;
-  const int64_t v[24] = {L.kernel_id, conv ? 1 : 0, conv ? 1 : 0, (int64_t)L.out.H * L.out.W, L.out.Cs, L.K, L.Kpad,
+  const int64_t v[27] = {L.kernel_id, conv ? 1 : 0, conv ? 1 : 0, (int64_t)L.out.H * L.out.W, L.out.Cs, L.K, L.Kpad,
                          c.tn, c.nw, c.S, c.sz, c.sw, c.splitk, c.MT, c.NTn, c.G, c.xmode, (int64_t)c.grid_x, 1, 1,
-                         c.threads, (int64_t)c.ws_bytes, L.pair_with, L.pair_lead ? 1 : 0};
-  for (int i = 0; i < 24; ++i) out[i] = v[i];
-  return 24;
+                         c.threads, (int64_t)c.ws_bytes, L.pair_with, L.pair_lead ? 1 : 0,
+                         L.out.slot, net.tensor(L.in_t).slot, L.res_t >= 0 ? net.tensor(L.res_t).slot : -1};
+  for (int i = 0; i < 27; ++i) out[i] = v[i];
+  return 27;
 }
 
 daris_status daris_set_afet(daris_task t, int stage, int64_t ns) {
@@ -1012,6 +1076,7 @@ static daris_status make_streams(void) {
 
 daris_status daris_commit(void) {
   if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
+  if (check_failed() != DARIS_OK) return DARIS_EHIP;
   if (G->committed) return DARIS_OK;
   if (G->tasks.empty()) return fail(DARIS_ESTATE, "no task");
   daris_status st0 = make_streams();
@@ -1026,7 +1091,7 @@ daris_status daris_commit(void) {
 }
 
 daris_part daris_get_partition(daris_task t) {
-  daris_status st = check_task(t);
+  daris_status st = check_task(t, true);
   if (st != DARIS_OK) return st;
   if (!G->committed) return fail(DARIS_ESTATE, "not committed");
   std::lock_guard<std::mutex> lk(G->mu);
@@ -1085,6 +1150,7 @@ daris_status daris_migrate(daris_task t, daris_part p) {
 
 daris_status daris_run_until_idle(void) {
   if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
+  if (check_failed() != DARIS_OK) return DARIS_EHIP;
   if (!G->committed) return DARIS_OK;
   if (G->vt) {
     daris_status st = vt_advance(0, true);
@@ -1124,6 +1190,7 @@ daris_status daris_task_set_io(daris_task t, const void* d_inputs, int32_t n_inp
 
 daris_status daris_run_periodic(const int64_t* phase_ns, const int32_t* n_jobs) {
   if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
+  if (check_failed() != DARIS_OK) return DARIS_EHIP;
   if (!n_jobs) return fail(DARIS_EINVAL, "n_jobs is NULL");
   daris_status st = daris_commit();
   if (st != DARIS_OK) return st;
@@ -1173,6 +1240,7 @@ daris_status daris_run_periodic(const int64_t* phase_ns, const int32_t* n_jobs) 
 
 daris_status daris_run_closed_loop(const int32_t* n_jobs, int64_t total_jobs) {
   if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
+  if (check_failed() != DARIS_OK) return DARIS_EHIP;
   if (G->vt) return fail(DARIS_ESTATE, "closed-loop runs need real-time mode");
   if (!n_jobs) return fail(DARIS_EINVAL, "n_jobs is NULL");
   daris_status st = daris_commit();
@@ -1206,7 +1274,7 @@ daris_status daris_run_closed_loop(const int32_t* n_jobs, int64_t total_jobs) {
 }
 
 daris_status daris_get_stats(daris_task t, daris_task_stats* out) {
-  daris_status st = check_task(t);
+  daris_status st = check_task(t, true);
   if (st != DARIS_OK) return st;
   if (!out) return fail(DARIS_EINVAL, "out is NULL");
   std::lock_guard<std::mutex> lk(G->mu);
@@ -1239,7 +1307,7 @@ int64_t daris_trace_read(void* buf, int64_t cap_bytes) {
 }
 
 int64_t daris_get_mret(daris_task t, int stage) {
-  daris_status st = check_task(t);
+  daris_status st = check_task(t, true);
   if (st != DARIS_OK) return st;
   if (stage < 0 || stage >= G->core.n_stages(t)) return fail(DARIS_ERANGE, "stage %d out of range", stage);
   std::lock_guard<std::mutex> lk(G->mu);
@@ -1348,7 +1416,10 @@ daris_status daris_profile_layers(daris_task t, daris_part p, int reps, float* m
       result = fail(DARIS_EHIP, "profiling layer %d: %s", l, err);
       break;  // nothing was given the completion signal: do not wait
     }
-    spin_until_done(G->util_sig);
+    if (!aql_spin(G->util_sig, &S.hw->q)) {
+      result = gpu_wait_failed(S, "layer profile");
+      break;
+    }
     double a0 = 0, b0 = 0, a1 = 0, b1 = 0;
     bool ok = g_rt.dispatch_time_us(G->util_sig, &a1, &b1);
     if (one) a0 = a1;
@@ -1570,7 +1641,8 @@ daris_status daris_calibrate_afet_loaded(daris_task t, daris_part p, int reps) {
       auto t1 = std::chrono::steady_clock::now();
       if (r > 0) sum[j] += std::chrono::duration_cast<std::chrono::nanoseconds>(t1 - t0).count();
     }
-    for (StreamRt* Q : loaded) aql_wait(Q->done);
+    for (StreamRt* Q : loaded)
+      if (!aql_wait(Q->done, &Q->hw->q) && result == DARIS_OK) result = gpu_wait_failed(*Q, "calibration load");
   }
   cleanup();
   if (result != DARIS_OK) return result;

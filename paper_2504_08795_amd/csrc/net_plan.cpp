@@ -17,7 +17,7 @@ uint16_t host_f32_to_bf16(float f) {
   return (uint16_t)(u >> 16);
 }
 
-std::string build_plan(const daris_dnn& dnn, bool keep_activations, NetPlan* out) {
+std::string build_plan(const daris_dnn& dnn, bool keep_activations, bool pair_launches, bool fuse_ingest, NetPlan* out) {
   NetPlan& net = *out;
   net = NetPlan();
   if (dnn.n_layers < 1 || !dnn.layers) return "DNN has no layers";
@@ -113,7 +113,7 @@ std::string build_plan(const daris_dnn& dnn, bool keep_activations, NetPlan* out
     o.bytes = (size_t)o.H * o.W * o.Cs * es;
   }
   // launch pairs (a residual block's first convolution and its shortcut convolution)
-  for (int l = 0; l + 1 < n && !getenv("DARIS_NO_PAIR"); ++l) {
+  for (int l = 0; l + 1 < n && pair_launches; ++l) {
     LayerPlan& A = net.layers[l];
     LayerPlan& B = net.layers[l + 1];
     if (A.d.op != DARIS_OP_CONV || B.d.op != DARIS_OP_CONV || A.depthwise || B.depthwise) continue;
@@ -136,7 +136,7 @@ std::string build_plan(const daris_dnn& dnn, bool keep_activations, NetPlan* out
     bool only_reader = true;
     for (int l = 1; l < n; ++l)
       if (net.layers[l].in_t == 0 || net.layers[l].res_t == 0) only_reader = false;
-    net.fuse_ingest = !keep_activations && !getenv("DARIS_NO_FUSED_INGEST") && L0.d.op == DARIS_OP_CONV && !L0.depthwise &&
+    net.fuse_ingest = !keep_activations && fuse_ingest && L0.d.op == DARIS_OP_CONV && !L0.depthwise &&
                       L0.in_t == 0 && L0.res_t < 0 && L0.pair_with < 0 && only_reader && net.ingest.Cs == vec && dnn.in_c <= 4;
   }
   const TensorInfo& fin = net.layers[n - 1].out;
@@ -156,10 +156,14 @@ std::string build_plan(const daris_dnn& dnn, bool keep_activations, NetPlan* out
   net.stage_first.assign(1, 0);
 
   // activation slots: a tensor's slot is free again once its last reader has been issued (same stream, in order)
+  // The earlier member of a launch pair is issued with the later one (and its split-K reduction after that launch):
+  // what it reads must stay in place until then, so its reads count as reads of the later layer.
   std::vector<int> last_use(n + 1, -1);
   for (int l = 0; l < n; ++l) {
-    last_use[net.layers[l].in_t] = std::max(last_use[net.layers[l].in_t], l);
-    if (net.layers[l].res_t >= 0) last_use[net.layers[l].res_t] = std::max(last_use[net.layers[l].res_t], l);
+    const LayerPlan& L = net.layers[l];
+    const int at = std::max(l, L.pair_with);
+    last_use[L.in_t] = std::max(last_use[L.in_t], at);
+    if (L.res_t >= 0) last_use[L.res_t] = std::max(last_use[L.res_t], at);
   }
   std::vector<int> slot_owner;  // tensor currently held by each slot, -1 = free
   auto take_slot = [&](int tensor, size_t bytes) {

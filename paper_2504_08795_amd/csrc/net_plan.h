@@ -49,8 +49,10 @@ struct NetPlan {
   const TensorInfo& tensor(int t) const { return t == 0 ? ingest : layers[t - 1].out; }
 };
 
-// Builds shapes, MACs, legal cuts, buffer slots and kernel plans.  Returns "" or an error text.
-std::string build_plan(const daris_dnn& dnn, bool keep_activations, NetPlan* out);
+// Builds shapes, MACs, legal cuts, buffer slots and kernel plans.  pair_launches: two independent convolutions on one
+// tensor share a launch; fuse_ingest: the first convolution may read the caller's input layout itself.  Returns "" or an
+// error text.
+std::string build_plan(const daris_dnn& dnn, bool keep_activations, bool pair_launches, bool fuse_ingest, NetPlan* out);
 // Chooses k - 1 cuts minimising the largest per-stage MAC count, ties to the lexicographically smallest cut
 // list.  Returns false when k exceeds the number of legal cuts + 1.
 bool split_stages(NetPlan* net, int k);

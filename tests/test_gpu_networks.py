@@ -44,7 +44,7 @@ def test_logits_bit_identical_across_splits_and_partitions(net, dtype):
 
 
 @pytest.mark.parametrize("net,dtype", [("resnet18", "fp32"), ("resnet50", "bf16")])
-def test_plain_launch_shapes_agree_with_the_fused_ones(net, dtype, monkeypatch):
+def test_plain_launch_shapes_agree_with_the_fused_ones(net, dtype):
     """The launch-count optimisations -- a residual block's shortcut and first convolution in one launch, the input layout
     conversion folded into the first convolution -- can be switched off when a task is registered: the plain launches
     must meet the same tolerance against the oracle, and agree with the fused ones to rounding."""
@@ -56,9 +56,7 @@ def test_plain_launch_shapes_agree_with_the_fused_ones(net, dtype, monkeypatch):
         fused = g.forward(x)
         n_pairs = sum(1 for l in range(len(layers)) if D.daris_get_launch_plan(g.task, l)["pair_lead"])
     assert n_pairs >= 3
-    monkeypatch.setenv("DARIS_NO_PAIR", "1")
-    monkeypatch.setenv("DARIS_NO_FUSED_INGEST", "1")
-    with GpuNet(layers, weights, shp, dtype, k=3) as g:
+    with GpuNet(layers, weights, shp, dtype, k=3, flags=D.NO_PAIR | D.NO_FUSED_INGEST) as g:
         plain = g.forward(x)
         assert not any(D.daris_get_launch_plan(g.task, l)["pair_lead"] for l in range(len(layers)))
     for got in (fused, plain):

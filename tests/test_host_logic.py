@@ -17,7 +17,7 @@ HOST = D.VIRTUAL_TIME | D.NO_DEVICE
 
 
 def test_library_exports_every_declared_symbol(repo_root):
-    hdr = open(os.path.join(repo_root, "include", "daris.h")).read()
+    hdr = "".join(open(os.path.join(repo_root, "include", f)).read() for f in sorted(os.listdir(os.path.join(repo_root, "include"))) if f.endswith(".h"))
     declared = set(re.findall(r"\b(daris_[a-z_0-9]+)\s*\(", hdr))
     assert declared, "no declarations found"
     lib = ctypes.CDLL(D.binding.LIB_PATH)
@@ -440,3 +440,69 @@ def test_layer_rooflines_follow_the_layer_tables():
         assert round(sum(x[2] for x in harness.layer_rooflines(layers, shp, dtype)), 2) == us
     ts = wl.make_taskset(2)
     assert [round(v, 2) for v in harness.taskset_roofline_us(ts)] == [23.94] * 4
+
+
+def _check_slot_lifetimes(layers, plans, name):
+    """Replay the launches in issue order: a launch group (a layer, or the two layers of a joint launch, issued at the later
+    one) must not write a slot that holds a tensor some launch at or after this group still reads, and must not write a
+    slot it reads itself."""
+    n = len(layers)
+    issue = [max(l, plans[l]["pair_with"]) for l in range(n)]                     # when layer l's launch is issued
+    readers = {}                                                                  # tensor (layer index, -1 = input) -> issue times of its readers
+    for l, L in enumerate(layers):
+        readers.setdefault(L.in_from, []).append(issue[l])
+        if L.res_from >= 0:
+            readers.setdefault(L.res_from, []).append(issue[l])
+    holds = {}                                                                    # slot -> tensor it holds
+    if plans[0]["in_slot"] >= 0 and layers[0].in_from == -1:
+        holds[plans[0]["in_slot"]] = -1
+    for l in range(n):
+        group = [q for q in range(n) if issue[q] == issue[l]]
+        s = plans[l]["out_slot"]
+        if s < 0:
+            continue
+        for q in group:                                                           # nothing the group reads may be overwritten by it
+            assert s != plans[q]["in_slot"] and s != plans[q]["res_slot"], (name, l, q, s)
+        if s in holds:
+            old = holds[s]
+            assert all(t < issue[l] for t in readers.get(old, [])), (name, "layer", l, "overwrites tensor", old, "still read at", readers.get(old))
+        holds[s] = l
+    for l, L in enumerate(layers):                                                # and every read finds its tensor where the plan says
+        assert plans[l]["in_slot"] == (plans[L.in_from]["out_slot"] if L.in_from >= 0 else plans[l]["in_slot"])
+        if L.res_from >= 0:
+            assert plans[l]["res_slot"] == plans[L.res_from]["out_slot"]
+
+
+def paired_residual_net():
+    """A graph none of the configured networks has: the EARLIER member of a joint launch (L2) carries a residual operand
+    (L0's output) whose last reader it is, so that operand's buffer falls free exactly when the later member's output is
+    placed."""
+    c = lambda i, r=-1, co=32, k=3: N_.Layer(op=N_.OP_CONV, c_in=32 if i >= 0 else 3, c_out=co, k=k, stride=1, pad=k // 2, act=1, in_from=i, res_from=r)  # noqa: E731
+    layers = [c(-1), c(0), c(1, 0), c(1, -1, 32, 1), c(3, 2), N_.Layer(op=N_.OP_GAVGPOOL, c_in=32, c_out=32, in_from=4),
+              N_.Layer(op=N_.OP_FC, c_in=32, c_out=10, in_from=5)]
+    return layers, (3, 12, 12)
+
+
+N_ = wl.nets
+
+
+@pytest.mark.parametrize("net", ["resnet18", "resnet50", "mobilenet_v2", "vgg16", "paired_residual"])
+def test_activation_slots_outlive_their_readers(net):
+    layers, shp = paired_residual_net() if net == "paired_residual" else wl.build_net(net)
+    with Session(HOST):
+        D.daris_create_partition(64)
+        dnn, keep = D.make_dnn(layers, None, shp, "fp32")
+        t = D.daris_register_task(dnn, 10**7, 10**7, D.LP)
+        plans = [D.daris_get_launch_plan(t, l) for l in range(len(layers))]
+    if net == "paired_residual":
+        assert plans[2]["pair_with"] == 3 and plans[3]["pair_lead"] == 1          # the case is what it claims to be
+        assert plans[3]["out_slot"] != plans[2]["res_slot"]
+    _check_slot_lifetimes(layers, plans, net)
+    assert len({p["out_slot"] for p in plans if p["out_slot"] >= 0}) <= 6         # and buffers are still shared
+
+
+def test_timeout_setter_validates():
+    with pytest.raises(D.DarisError) as e:
+        D.daris_set_timeout(0)
+    assert e.value.code == D.EINVAL
+    D.daris_set_timeout(20_000_000_000)
