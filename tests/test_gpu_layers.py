@@ -152,3 +152,15 @@ def test_identity_passthrough_is_exact():
     x = RNG.normal(0, 1, (5, 6, 7)).astype(np.float32)
     with GpuNet(layers, [(None, None)], (5, 6, 7), "fp32") as net:
         np.testing.assert_array_equal(net.forward(x), x.reshape(-1))
+
+
+def test_joint_launch_whose_earlier_member_has_a_residual_operand():
+    """L2 (3x3, + L0's output as residual) and L3 (1x1) both read L1 and share a launch that is issued at L3.  L0's output
+    is read last by L2, so its buffer falls free exactly when L3's output is placed: it must not be reused before the
+    joint launch (and L2's split-K reduction) have read it."""
+    def c(i, r=-1, k=3, cin=32):
+        return N.Layer(op=N.OP_CONV, c_in=cin, c_out=32, k=k, stride=1, pad=k // 2, act=1, in_from=i, res_from=r)
+    layers = [c(-1, cin=3), c(0), c(1, 0), c(1, -1, 1), c(3, 2), N.Layer(op=N.OP_GAVGPOOL, c_in=32, c_out=32, in_from=4),
+              N.Layer(op=N.OP_FC, c_in=32, c_out=10, in_from=5)]
+    for dtype in ("fp32", "bf16"):
+        run_case(layers, (3, 12, 12), dtype, tol={"fp32": 2e-5, "bf16": 2e-2}[dtype])

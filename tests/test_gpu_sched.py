@@ -277,18 +277,86 @@ def test_pool_jobs_of_networks_with_unusual_first_and_last_launches(shape):
         D.daris_shutdown()
 
 
+def _probe(p, n_groups=8192, spin=3000):
+    """Distinct compute units (XCC id, and bits 8..15 of the hardware id register: CU, shader array, shader engine) that
+    the workgroups of one probe launch on partition p ran on."""
+    ids = D.daris_probe_cus(p, n_groups, spin)
+    return {(int(x) & 0xF, (int(h) >> 8) & 0xFF) for x, h in ids}
+
+
 def test_cu_masks_are_honoured():
-    """Workgroups launched on a partition's stream run only on as many distinct CUs as the partition owns."""
+    """A partition's workgroups run on exactly as many distinct CUs as the partition owns, an eighth of them on each of
+    the eight XCDs (mask bit i lands on XCD i mod 8, so a cyclic run of n bits is spread evenly); partitions whose CU ranges
+    do not overlap use disjoint CUs, and together the whole chip."""
     D.daris_init(0, 0, 0)
     try:
         sizes = (32, 128, 256)
         parts = [D.daris_create_partition(n) for n in sizes]
         for p, n in zip(parts, sizes):
-            ids = D.daris_probe_cus(p, 4096, 3000)
-            distinct = {(int(x), (int(h) >> 8) & 0xFF) for x, h in ids}      # HW_ID bits 8..15: CU, shader array, shader engine
-            xccs = sorted({int(x) for x, _ in ids})
-            print(f"partition of {n} CUs: {len(distinct)} distinct (xcc, se/sh/cu) triples over XCCs {xccs}")
-            assert len(distinct) <= n
+            cus = _probe(p)
+            per_xcc = [sum(1 for x, _ in cus if x == k) for k in range(8)]
+            print(f"partition of {n} CUs: {len(cus)} distinct CUs, per XCC {per_xcc}")
+            assert len(cus) == n, (n, len(cus), per_xcc)
+            assert per_xcc == [n // 8] * 8, per_xcc
+    finally:
+        D.daris_shutdown()
+    D.daris_init(0, 0, 0)
+    try:
+        sizes = (64, 64, 96, 32)                      # 256 in all: cyclic ranges [0,64) [64,128) [128,224) [224,256)
+        parts = [D.daris_create_partition(n) for n in sizes + (64,)]   # the fifth wraps around onto the first one's CUs
+        sets = [_probe(p) for p in parts[:4]]
+        for n, c in zip(sizes, sets):
+            assert len(c) == n, (n, len(c))
+        for i in range(len(sets)):
+            for j in range(i + 1, len(sets)):
+                assert not (sets[i] & sets[j]), (i, j, len(sets[i] & sets[j]))
+        assert len(set().union(*sets)) == 256
+        assert _probe(parts[4]) == sets[0]              # oversubscription (Sec. III-C2): the same CUs, shared
+    finally:
+        D.daris_shutdown()
+
+
+def test_wait_limit_turns_a_late_gpu_into_an_error_and_the_library_recovers_after_shutdown():
+    """Host-side failure handling, forced from the host: with a wait limit of 1 ns the host gives up on a ResNet-18
+    forward pass (about 0.2 ms of kernels, which all complete normally on the GPU) at its first look at the clock.  The
+    call returns DARIS_EHIP instead of hanging, later calls are refused, the accessors still answer, daris_shutdown lets
+    the queue run dry before freeing the buffers, and a fresh session computes the right logits."""
+    layers, shp = wl.build_net("resnet18")
+    weights = wl.make_weights(layers, 77)
+    x = wl.make_inputs(shp, 77, 1, "normal")[0]
+    xd = torch.from_numpy(x).cuda()
+    try:
+        D.daris_init(0, 0, 0)
+        p = D.daris_create_partition(128)
+        dnn, keep = D.make_dnn(layers, weights, shp, "fp32")
+        t = D.daris_register_task(dnn, 10_000_000, 10_000_000, D.LP)
+        y = torch.zeros(1000, device="cuda")
+        torch.cuda.synchronize()
+        D.daris_forward(t, xd, y, p)                  # creates the streams, warms up
+        good = y.cpu().numpy().copy()
+        D.daris_set_timeout(1)
+        with pytest.raises(D.DarisError) as e:
+            D.daris_forward(t, xd, y, p)
+        assert e.value.code == D.EHIP and "wait limit" in str(e.value)
+        with pytest.raises(D.DarisError) as e:
+            D.daris_forward(t, xd, y, p)              # refused: the state of the GPU work is unknown
+        assert e.value.code == D.EHIP
+        with pytest.raises(D.DarisError):
+            D.daris_run_closed_loop([1], 0)
+        assert D.daris_get_stats(t)["released"] == 0  # read-only accessors still answer
+    finally:
+        D.daris_set_timeout(20_000_000_000)
+        D.daris_shutdown()
+    D.daris_init(0, 0, 0)
+    try:
+        p = D.daris_create_partition(128)
+        dnn, keep = D.make_dnn(layers, weights, shp, "fp32")
+        t = D.daris_register_task(dnn, 10_000_000, 10_000_000, D.LP)
+        y = torch.full((1000,), float("nan"), device="cuda")
+        torch.cuda.synchronize()
+        D.daris_forward(t, xd, y, p)
+        np.testing.assert_array_equal(y.cpu().numpy(), good)
+        assert rel_err(good, F.forward(layers, weights, x, "fp32"))[0] <= TOL["fp32"]
     finally:
         D.daris_shutdown()
 
