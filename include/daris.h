@@ -238,6 +238,21 @@ int64_t daris_get_mret(daris_task t, int stage);
 /* Run the whole DNN of task t once, stage after stage, on stream 0 of partition p, and wait for it.  No scheduler
  * state is touched.  The logits do not depend on p or on the stage split. */
 daris_status daris_forward(daris_task t, const void* d_input, void* d_logits, daris_part p);
+/* daris_forward for callers that cannot allocate device memory: code that runs while another part of the process
+ * captures a HIP graph, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels in the same
+ * order, hence bit-identical logits; but the task's activation tensors and split-K partial sums live in a static device
+ * array of 16 MiB that the library's device image brings along (every GPU the library was initialised on holds its own
+ * copy until the process ends) instead of the buffers allocated at registration, and every launch's argument block goes
+ * through the queue's ring of host-visible memory.  The call allocates nothing: no hipMalloc / hipFree, no pinned memory,
+ * no queue or signal; the first call for a task encodes that task's launches against the array in ordinary host memory.
+ *   - The streams must exist already (daris_commit, or any execution, came first: creating them allocates);
+ *     DARIS_ESTATE otherwise.
+ *   - The task's activation slots plus workspace must fit the array (every configured network but VGG-16 does);
+ *     DARIS_ERANGE otherwise, with both sizes in daris_last_error().
+ *   - All calls on a GPU share that GPU's array, which keeps whatever the last call left in it.  Nothing in it has to be
+ *     cleared: every kernel reads only what an earlier kernel of the same call wrote.  Two calls that overlapped on one
+ *     GPU would race on it; the library runs them one at a time.  Weights stay where registration put them. */
+daris_status daris_forward_static(daris_task t, const void* d_input, void* d_logits, daris_part p);
 /* Measure per-stage execution times of task t alone on partition p (`reps` runs, the maximum is kept) and store
  * them as the task's AFET values. */
 daris_status daris_calibrate_afet(daris_task t, daris_part p, int reps);

@@ -76,6 +76,7 @@ _SIGS = {
     "daris_trace_read": (C.c_int64, [C.c_void_p, C.c_int64]),
     "daris_get_mret": (C.c_int64, [C.c_int32, C.c_int]),
     "daris_forward": (C.c_int32, [C.c_int32, C.c_void_p, C.c_void_p, C.c_int32]),
+    "daris_forward_static": (C.c_int32, [C.c_int32, C.c_void_p, C.c_void_p, C.c_int32]),
     "daris_read_layer": (C.c_int32, [C.c_int32, C.c_int, C.POINTER(C.c_float), C.c_int64]),
     "daris_profile_layers": (C.c_int32, [C.c_int32, C.c_int32, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_int32), C.POINTER(C.c_double)]),
     "daris_kernel_name": (C.c_char_p, [C.c_int32]),
@@ -278,6 +279,10 @@ def daris_get_mret(t, stage):
 
 def daris_forward(t, d_input, d_logits, p=0):
     return _chk(lib().daris_forward(t, _ptr(d_input), _ptr(d_logits), p))
+
+
+def daris_forward_static(t, d_input, d_logits, p=0):
+    return _chk(lib().daris_forward_static(t, _ptr(d_input), _ptr(d_logits), p))
 
 
 def daris_read_layer(t, layer, n_elems):

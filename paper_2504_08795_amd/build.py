@@ -42,6 +42,10 @@ def build(verbose: bool = False) -> str:
     objs = [os.path.join(CSRC, "kernels_blob.o")]
     _run(["gcc", "-c", blob_s, "-o", objs[0]], verbose)
     os.remove(blob_s)
+    # the one translation unit with both host and device code: the static scratch array and its address lookup
+    obj = os.path.join(CSRC, "static_scratch.hip.o")
+    _run([hipcc] + HOST_FLAGS + ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-c", os.path.join(CSRC, "static_scratch.hip"), "-o", obj], verbose)
+    objs.append(obj)
     for src in HOST_SOURCES:
         obj = os.path.join(CSRC, src + ".o")
         _run([hipcc] + HOST_FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj], verbose)

@@ -29,6 +29,7 @@
 #include "kernels.h"
 #include "net_plan.h"
 #include "sched_core.h"
+#include "static_scratch.h"
 
 using namespace daris;
 
@@ -95,6 +96,11 @@ struct TaskRt {
   int in_launch = -1, out_launch = -1;  // the launches that read the job's input / write its logits
   uint32_t in_off = 0, out_off = 0;     // byte offset of that pointer inside the argument block
   IoVariants pool;                      // argument blocks for the buffers of daris_task_set_io
+  // the same network encoded on the static device scratch (daris_forward_static), built at its first call; host memory only
+  std::vector<LaunchRt> static_launches;
+  std::vector<int> static_layer_lo;
+  int static_in = -1, static_out = -1;
+  uint32_t static_in_off = 0, static_out_off = 0;
   // virtual execution times: (stage, partition) -> (job_lo, values)
   std::map<std::pair<int, int>, std::pair<int64_t, std::vector<int64_t>>> vt;
   // library-driven runs
@@ -818,6 +824,7 @@ daris_status daris_init(int device, uint64_t seed, int flags) {
     } else if (device != g_rt_device) {
       err = "the kernels are loaded on device " + std::to_string(g_rt_device) + "; one device per process";
     }
+    if (err.empty()) err = static_scratch_init(device);  // this GPU's copy of the static scratch array (device is current)
     if (err.empty()) {
       G->util_sig = g_rt.new_signal(1);
       if (!G->util_sig.handle) err = "signal creation failed";
@@ -1337,6 +1344,70 @@ daris_status daris_forward(daris_task t, const void* d_input, void* d_logits, da
   io.in = d_input;
   io.out = d_logits;
   return run_direct(T, 0, (int)T.launches.size(), io, *G->parts[p].streams[0]);
+}
+
+// For callers that cannot allocate device memory.  Nothing below calls hipMalloc, hipFree or any routine that allocates
+// device or pinned memory: the queues, signals and argument rings exist already, the network's tensors go into the static
+// device array, and each launch's argument block travels through its queue's ring of host-coherent memory.
+daris_status daris_forward_static(daris_task t, const void* d_input, void* d_logits, daris_part p) {
+  daris_status st = check_task(t);
+  if (st != DARIS_OK) return st;
+  st = check_part(p);
+  if (st != DARIS_OK) return st;
+  if (G->nodev) return fail(DARIS_ESTATE, "no device in DARIS_NO_DEVICE mode");
+  if (!G->frozen) return fail(DARIS_ESTATE, "the streams do not exist yet (creating them allocates): call daris_commit, or run anything once, before daris_forward_static");
+  if (!d_input || !d_logits) return fail(DARIS_EINVAL, "NULL device buffer");
+  std::lock_guard<std::mutex> lk(G->mu);
+  if (G->core.has_active(t)) return fail(DARIS_ESTATE, "task %d has an active job", t);
+  TaskRt& T = *G->tasks[t];
+  unsigned char* base = static_cast<unsigned char*>(static_scratch_ptr(G->device));
+  if (!base) return fail(DARIS_EHIP, "the static scratch of device %d was not set up", G->device);
+  // layout: the plan's activation slots one after the other, 256 bytes apart at least, then the split-K workspace
+  const NetPlan& net = T.net;
+  auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+  size_t need = up(net.ws_bytes);
+  for (size_t b : net.slot_bytes) need += up(b);
+  if (need > (size_t)DARIS_STATIC_SCRATCH_BYTES)
+    return fail(DARIS_ERANGE, "task %d needs %zu bytes of activation buffers and split-K workspace; the static scratch holds %u", t, need,
+                (unsigned)DARIS_STATIC_SCRATCH_BYTES);
+  if (T.static_launches.empty()) {
+    std::vector<void*> slots(net.slot_bytes.size());
+    size_t off = 0;
+    for (size_t i = 0; i < slots.size(); ++i) {
+      slots[i] = base + off;
+      off += up(net.slot_bytes[i]);
+    }
+    IoLaunches iol;
+    const std::string err = encode_network(T, slots, reinterpret_cast<float*>(base + off), &T.static_launches, &T.static_layer_lo, &iol);
+    if (!err.empty()) {
+      T.static_launches.clear();
+      return fail(DARIS_EHIP, "%s", err.c_str());
+    }
+    T.static_in = iol.in_launch;
+    T.static_out = iol.out_launch;
+    T.static_in_off = iol.in_off;
+    T.static_out_off = iol.out_off;
+  }
+  HIP_TRY(hipDeviceSynchronize());  // the caller's streams may still be writing the two buffers (see daris_task_set_io)
+  StreamRt& S = *G->parts[p].streams[0];
+  const int n = (int)T.static_launches.size();
+  {
+    std::lock_guard<std::mutex> ql(S.hw->mu);
+    for (int i = 0; i < n; ++i) {
+      const KernelLaunch& kl = T.static_launches[i].kl;
+      alignas(8) unsigned char blk[sizeof(KernelLaunch::args)];
+      std::memcpy(blk, kl.args, kl.nbytes);
+      if (i == T.static_in) std::memcpy(blk + T.static_in_off, &d_input, sizeof(void*));
+      if (i == T.static_out) std::memcpy(blk + T.static_out_off, &d_logits, sizeof(void*));
+      const unsigned fl = (i == 0 ? AqlQueue::kAcquireSystem : 0u) | (i == n - 1 ? AqlQueue::kReleaseSystem : 0u);
+      if (!S.hw->q.dispatch_copy(*kl.k, kl.groups, kl.threads, blk, kl.nbytes, i == n - 1 ? G->util_sig : hsa_signal_t{0}, fl)) {
+        // Launches already queued keep running on the static array; the next call would race with them.
+        return gpu_wait_failed(S, "daris_forward_static: packet rejected");
+      }
+    }
+  }
+  if (!aql_wait(G->util_sig, &S.hw->q)) return gpu_wait_failed(S, "daris_forward_static");
+  return DARIS_OK;
 }
 
 daris_status daris_read_layer(daris_task t, int layer, float* host_out, int64_t cap_elems) {
