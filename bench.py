@@ -108,7 +108,7 @@ def measure(config, args, full):
     import workloads as wl
 
     ts = wl.make_taskset(config, n_jobs=64)
-    g = harness.GpuTaskSet(ts, seed=wl.tasksets.SEED)
+    g = harness.GpuTaskSet(ts, flags=args.flags, seed=wl.tasksets.SEED)
     nt = g.n_tasks
     try:
         g.calibrate(3)
@@ -259,6 +259,7 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU-oracle baseline; 0 skips it")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--sample-every", type=int, default=8, help="kernel timing: time stamps for the launches of every n-th job")
+    ap.add_argument("--flags", type=int, default=0, help="extra daris_init flags (A/B switches of daris.h)")
     ap.add_argument("--pmc-pass", action="store_true",
                     help="counter-collection helper for `rocprofv3 --pmc` (see pmc_pass); prints nothing, times nothing")
     ap.add_argument("--cpu-oracle-report", action="store_true",

@@ -63,8 +63,10 @@ enum {
                                  trace) are those of N_s streams; off by default                                */
   DARIS_NO_PAIR = 512,        /* tasks registered under this flag launch a residual block's shortcut convolution and
                                  first convolution separately instead of in one two-problem launch (A/B and tests)  */
-  DARIS_NO_FUSED_INGEST = 1024 /* ... and convert the input layout in a launch of its own instead of inside the first
+  DARIS_NO_FUSED_INGEST = 1024, /* ... and convert the input layout in a launch of its own instead of inside the first
                                  convolution                                                                     */
+  DARIS_NO_STAGED_ROWS = 2048 /* ... and feed every convolution's pixel operand straight from global memory to registers
+                                 instead of fetching whole 64-byte rows through LDS where the shape allows (A/B)   */
 };
 
 enum { DARIS_LP = 0, DARIS_HP = 1 };

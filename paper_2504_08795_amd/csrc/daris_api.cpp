@@ -925,7 +925,7 @@ daris_task daris_register_task(const daris_dnn* dnn, int64_t period_ns, int64_t 
   if (priority != DARIS_HP && priority != DARIS_LP) return fail(DARIS_EINVAL, "priority must be DARIS_HP or DARIS_LP");
   if (G->tasks.size() >= 65535) return fail(DARIS_ERANGE, "too many tasks");
   std::unique_ptr<TaskRt> T(new TaskRt());
-  std::string err = build_plan(*dnn, G->flags & DARIS_KEEP_ACTIVATIONS, !(G->flags & DARIS_NO_PAIR), !(G->flags & DARIS_NO_FUSED_INGEST), &T->net);
+  std::string err = build_plan(*dnn, G->flags & DARIS_KEEP_ACTIVATIONS, !(G->flags & DARIS_NO_PAIR), !(G->flags & DARIS_NO_FUSED_INGEST), !(G->flags & DARIS_NO_STAGED_ROWS), &T->net);
   if (!err.empty()) return fail(DARIS_EINVAL, "%s", err.c_str());
   if (!G->nodev) {
     NetPlan& net = T->net;

@@ -67,17 +67,21 @@ struct ConvPlan {
   int32_t kernel;  // KernelId
   int splitk;      // K slices across workgroups (1 = none); > 1 needs the workspace and the reduction launch
   int tn, nw, S, sz, sw, MT, NTn, G, xmode;
+  int step_align;                  // K slices are multiples of this many steps (2: staged pixel operand possible)
   int tiles;                       // output tiles per grid.z slice
   size_t ws_bytes;                 // split-K workspace this launch needs
   uint32_t grid_x;                 // workgroups of the launch
   int threads;
 };
+// True when every pixel's channel vector is a whole number of 64-byte rows, the shape for which the convolution kernel
+// fetches the pixel operand in coalesced rows through LDS (chunks of two K steps).
+inline bool conv_rows_staged(int cin_stride, int bf16) { return cin_stride > 0 && (cin_stride * (bf16 ? 2 : 4)) % 64 == 0; }
 // bf16 = 0/1.  Chooses tile shape, waves per workgroup and split-K from (M, N, Kpad) only, so results do not depend on the
-// partition a stage runs in.
-ConvPlan plan_conv(int M, int N, int Kpad, int bf16);
+// partition a stage runs in.  step_align = 2 cuts K in whole chunks of two steps (for conv_rows_staged shapes), else 1.
+ConvPlan plan_conv(int M, int N, int Kpad, int bf16, int step_align);
 // Plan for a second convolution that is to share a launch with `first`: the same wave-tile kernel variant, K not split
 // across workgroups.  Returns a plan with kernel == K_NONE when that is not possible.
-ConvPlan plan_conv_like(const ConvPlan& first, int M, int N, int Kpad, int bf16);
+ConvPlan plan_conv_like(const ConvPlan& first, int M, int N, int Kpad, int bf16, int step_align);
 // Multiplier for fast_div: floor(2^32 / d) + 1, or 0 for d == 1.  Exact for every n >= 0 with n * d < 2^32.
 inline uint32_t div_magic(uint32_t d) { return d <= 1 ? 0u : (uint32_t)((1ull << 32) / d) + 1u; }
 
@@ -99,8 +103,8 @@ struct KernelLaunch {
 
 // Every kernel of the code object, looked up once.
 struct KernelTable {
-  const AqlKernel* conv[2][6][3] = {};  // [bf16][(tn - 1) * 3 + log2(nw) - 1][gather mode]
-  const AqlKernel* pair[2][6][2] = {};
+  const AqlKernel* conv[2][6][4] = {};  // [bf16][(tn - 1) * 3 + log2(nw) - 1][gather mode 0..3]
+  const AqlKernel* pair[2][6][3] = {};  // gather modes 0, 1, 3
   const AqlKernel *reduce[2] = {}, *dwconv[2] = {}, *maxpool[2] = {}, *gavgpool[2] = {}, *fc[2] = {}, *ingest[2] = {}, *egress[2] = {};
   const AqlKernel* cu_probe = nullptr;
   // "" or the name of the first kernel that is missing or whose argument size is not what this header declares

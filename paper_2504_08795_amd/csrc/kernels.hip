@@ -130,17 +130,22 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 // measured to cost several times the extra launch).
 template <bool BF16, int TN, int NW, int MODE>
 __device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L) {
-  constexpr bool ALIGNED = MODE == 0;   // 0: Cin a multiple of KS; 1: any Cin; 2: the network input itself, fp32 [C][H][W]
+  // MODE 0: Cin a multiple of KS; 1: any Cin; 2: the network input itself, fp32 [C][H][W]; 3: a pixel's channels are whole
+  // 64-byte rows (Cin * ES a multiple of 64): the pixel operand is fetched in coalesced rows and transposed through LDS
+  constexpr bool ALIGNED = MODE == 0;
+  constexpr bool STAGED = MODE == 3;
   constexpr int ES = BF16 ? 2 : 4;
   constexpr int VEC = 16 / ES;
   constexpr int KS = 2 * VEC;
   constexpr int NT = NW * 64;
   constexpr int TILE = TN * 1024;
   constexpr int D = 4;
+  constexpr int STAGE_V = 32 * 5;  // 16-byte vectors of one wave's staging buffer: 32 pixels x (4 pieces + 1 pad)
+  constexpr int LDS_F = (STAGED && NW * STAGE_V * 4 > NW * TILE) ? NW * STAGE_V * 4 : NW * TILE;
   static_assert(TN == 1 || TN == 2, "the epilogue selects between at most two channel blocks");
   static_assert((TILE / 4) % NT == 0 || NT % (TILE / 4) == 0, "tile / thread mismatch");
 
-  __shared__ __align__(16) float red[NW * TILE];
+  __shared__ __align__(16) float red[LDS_F];
 
   if (p.wave_prio) __builtin_amdgcn_s_setprio(3);
   const int tid = threadIdx.x, lane = tid & 63;
@@ -288,6 +293,23 @@ __device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
 
+  auto mma = [&](uint4 a4, const uint4* b) {
+    if (BF16) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a4), __builtin_bit_cast(bf16x8, b[j]), acc[j], 0, 0, 0);
+    } else {
+      // the TN accumulators alternate so that consecutive MFMAs are independent
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a4.x), __uint_as_float(b[j].x), acc[j], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a4.y), __uint_as_float(b[j].y), acc[j], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a4.z), __uint_as_float(b[j].z), acc[j], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a4.w), __uint_as_float(b[j].w), acc[j], 0, 0, 0);
+    }
+  };
   auto compute = [&](int d) {
     uint4 a4 = keep_if(av[d], ar[d]);
     if (MODE == 2 && BF16) {  // four fp32 channels -> the 8-channel bf16 vector of the tap (same rounding as the conversion kernel)
@@ -296,26 +318,7 @@ __device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L) {
       a4.z = 0u;
       a4.w = 0u;
     }
-    if (BF16) {
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a4), __builtin_bit_cast(bf16x8, br[d][j]),
-                                                         acc[j], 0, 0, 0);
-    } else {
-      // the TN accumulators alternate so that consecutive MFMAs are independent
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-        acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a4.x), __uint_as_float(br[d][j].x), acc[j], 0, 0, 0);
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-        acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a4.y), __uint_as_float(br[d][j].y), acc[j], 0, 0, 0);
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-        acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a4.z), __uint_as_float(br[d][j].z), acc[j], 0, 0, 0);
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-        acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a4.w), __uint_as_float(br[d][j].w), acc[j], 0, 0, 0);
-    }
+    mma(a4, br[d]);
   };
 
   // Software pipeline, D steps deep.  Every load in the prologue and in the steady-state loop is unconditional and
@@ -323,19 +326,111 @@ __device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L) {
   // wait only for the oldest slot.  Refills past the end of the wave's K slice fetch valid memory that is never used
   // (the weight buffer carries D KiB of slack; the A pointer always points into the input); only the computes of the
   // ragged tail are conditional.
+  if constexpr (!STAGED) {
 #pragma unroll
-  for (int d = 0; d < D; ++d) load(d);
-  int done = 0;
-  for (; done + D <= nsteps; done += D) {
+    for (int d = 0; d < D; ++d) load(d);
+    int done = 0;
+    for (; done + D <= nsteps; done += D) {
 #pragma unroll
-    for (int d = 0; d < D; ++d) {
-      compute(d);
-      load(d);
+      for (int d = 0; d < D; ++d) {
+        compute(d);
+        load(d);
+      }
     }
-  }
 #pragma unroll
-  for (int d = 0; d < D; ++d)
-    if (done + d < nsteps) compute(d);
+    for (int d = 0; d < D; ++d)
+      if (done + d < nsteps) compute(d);
+  } else {
+    // Staged pixel operand.  A load instruction is served 64 bytes per cycle only when four neighbouring lanes read one
+    // 64-byte segment; the register-fed path above has every lane in a different pixel (a different cache line), which
+    // makes the pixel operand cost four times the cycles of the same bytes of weights and binds the small layers to
+    // the load unit instead of the matrix pipe.  Here a wave fetches, per chunk of two K steps, 64 contiguous bytes
+    // of each of its 32 pixels as whole rows (lane = (pixel, 16-byte piece): 4 lanes per row, 16 rows per
+    // instruction), parks them in its own corner of LDS, and reads them back in MFMA order (lane = pixel row, half =
+    // K half).  No workgroup barrier is involved: the buffer is private to the wave.  Two chunks of rows and four steps
+    // of weights are in flight.  The plan makes every wave's K slice a whole number of chunks.
+    uint4* const st = reinterpret_cast<uint4*>(red) + wave * STAGE_V;
+    const int piece = lane & 3, prow = lane >> 2;
+    int siy0[2], six0[2];
+    bool sok[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int mj = m0 + 16 * j + prow;
+      sok[j] = mj < p.M;
+      const int y = fast_div(mj, p.mg_wo), x = mj - y * p.Wo;
+      siy0[j] = y * p.stride - p.pad;
+      six0[j] = x * p.stride - p.pad;
+    }
+    const unsigned char* gp[2];
+    bool gv[2];
+    auto enter_rows = [&]() {  // (ky, kx, ci) are wave-uniform
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int iy = siy0[j] + ky, ix = six0[j] + kx;
+        gv[j] = sok[j] && ky < p.kh && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
+        gp[j] = xb + ((size_t)(gv[j] ? iy * p.W + ix : 0) * p.Cin + ci) * ES + piece * 16;  // always a valid address
+      }
+    };
+    enter_rows();
+    uint4 gr[2][2];
+    bool gok[2][2];
+    auto load_rows = [&](int slot) {  // the chunk at (tap, ci) into register slot `slot`, then on to the next chunk
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        gr[slot][j] = *(const uint4*)gp[j];
+        gok[slot][j] = gv[j];
+      }
+      ci += 2 * KS;
+      if (ci >= p.Cin) {  // wave-uniform
+        ci -= p.Cin;
+        if (++kx == p.kw) { kx = 0; ++ky; }
+        enter_rows();
+      } else {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) gp[j] += 64;
+      }
+    };
+    auto load_w = [&](int d) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        br[d][j] = *(const uint4*)wptr[j];
+        wptr[j] += 1024;
+      }
+    };
+    // one chunk: rows of register slot `slot` -> LDS -> MFMA order; weights of pipeline slots d0, d0 + 1
+    auto chunk = [&](int slot, int d0) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) st[(16 * j + prow) * 5 + piece] = keep_if(gok[slot][j], gr[slot][j]);
+      load_rows(slot);  // two chunks ahead (past the end of the slice: valid memory, never used)
+      // lanes exchange data through the wave's buffer: order the accesses of the whole wave, not only of each lane
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      uint4 a4[2];
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) a4[s2] = st[li * 5 + 2 * s2 + lh];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        mma(a4[s2], br[d0 + s2]);
+        load_w(d0 + s2);
+      }
+    };
+    load_rows(0);
+    load_rows(1);
+#pragma unroll
+    for (int d = 0; d < D; ++d) load_w(d);
+    const int nchunks = nsteps >> 1;
+    int c = 0;
+    for (; c + 2 <= nchunks; c += 2) {
+      chunk(0, 0);
+      chunk(1, 2);
+    }
+    if (c < nchunks) chunk(0, 0);
+    __syncthreads();  // the partial tiles below reuse the LDS of every wave's staging buffer
+  }
 
   // --- sum the NW partial tiles in wave order; tile element e = (j*16 + v)*64 + lane --------------------------------
 #pragma unroll
@@ -582,8 +677,10 @@ __global__ __launch_bounds__(64) void cu_probe_kernel(uint32_t* out, int spin) {
   template __global__ void conv_wave_kernel<B, TN_, NW_, 0>(const ConvArgs);                      \
   template __global__ void conv_wave_kernel<B, TN_, NW_, 1>(const ConvArgs);                      \
   template __global__ void conv_wave_kernel<B, TN_, NW_, 2>(const ConvArgs);                      \
+  template __global__ void conv_wave_kernel<B, TN_, NW_, 3>(const ConvArgs);                      \
   template __global__ void conv_wave_pair_kernel<B, TN_, NW_, 0>(const ConvArgs, const ConvArgs, const int); \
-  template __global__ void conv_wave_pair_kernel<B, TN_, NW_, 1>(const ConvArgs, const ConvArgs, const int);
+  template __global__ void conv_wave_pair_kernel<B, TN_, NW_, 1>(const ConvArgs, const ConvArgs, const int); \
+  template __global__ void conv_wave_pair_kernel<B, TN_, NW_, 3>(const ConvArgs, const ConvArgs, const int);
 #define DARIS_INST_ALL(B)                                                                          \
   DARIS_INST_CONV(B, 1, 2) DARIS_INST_CONV(B, 1, 4) DARIS_INST_CONV(B, 1, 8)                        \
   DARIS_INST_CONV(B, 2, 2) DARIS_INST_CONV(B, 2, 4) DARIS_INST_CONV(B, 2, 8)                        \

@@ -22,7 +22,7 @@ static inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
 static const int kNominalWaveSlots = 512;  // 128 CUs x 4 SIMDs: the partition size the plans are tuned for
 
-static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16, int force_tn = 0, int force_nw = 0) {
+static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16, int step_align, int force_tn = 0, int force_nw = 0) {
   // Measured on a 128-CU partition (fp32, ResNet-18 shapes): the K loop itself runs near the MFMA rate; what a
   // launch pays for is its fixed cost and idle CUs.  Best found: 8 waves per workgroup splitting K, and enough
   // grid.z slices that tiles * z is about the number of CUs, while a wave keeps at least ~6 steps.
@@ -35,6 +35,10 @@ static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16, int force_tn = 
   // which saves the reduction launch).
   int tn = (nb % 2 == 0 && cdiv(M, 32) * (nb / 2) >= 96) ? 2 : 1;
   if (force_tn) tn = force_tn;
+  // Fetching the pixel operand as coalesced rows through LDS pays where a launch is bound by its loads: every bf16 shape
+  // (+11 % on the saturated ResNet-50 set) and 32-channel fp32 tiles.  fp32 tiles of 64 channels are bound by the matrix
+  // pipe; there the extra LDS round trip and registers cost 10-25 % (measured on VGG-16's layers), so they stay register-fed.
+  if (step_align > 1 && !bf16 && tn == 2) step_align = 1;
   const int tiles = cdiv(M, 32) * (nb / tn);
   const int nominal_cus = kNominalWaveSlots / 4;
   int nw = bf16 ? 4 : 8;  // bf16 steps are short: fewer waves to sum through LDS beat a finer K split (measured 0.4-0.8 us per layer)
@@ -65,13 +69,16 @@ static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16, int force_tn = 
     nw = force_nw;
     z = 1;
   }
-  const int sz = cdiv(S, z);
+  // K slices of workgroups and waves in whole multiples of step_align steps (2 when the kernel fetches the pixel
+  // operand in chunks of two steps; S is then even as well)
+  const int sz = cdiv(cdiv(S, z), step_align) * step_align;
   z = cdiv(S, sz);
   pl.tn = tn;
   pl.nw = nw;
   pl.S = S;
   pl.sz = sz;
-  pl.sw = cdiv(sz, nw);
+  pl.sw = cdiv(cdiv(sz, nw), step_align) * step_align;
+  pl.step_align = step_align;
   pl.splitk = z;
   pl.tiles = tiles;
   pl.threads = nw * 64;
@@ -94,12 +101,12 @@ static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16, int force_tn = 
   return pl;
 }
 
-ConvPlan plan_conv(int M, int N, int Kpad, int bf16) { return plan_conv_wave(M, N, Kpad, bf16); }
+ConvPlan plan_conv(int M, int N, int Kpad, int bf16, int step_align) { return plan_conv_wave(M, N, Kpad, bf16, step_align); }
 
-ConvPlan plan_conv_like(const ConvPlan& first, int M, int N, int Kpad, int bf16) {
+ConvPlan plan_conv_like(const ConvPlan& first, int M, int N, int Kpad, int bf16, int step_align) {
   ConvPlan none = ConvPlan();
   if (cdiv(N, 32) % first.tn != 0) return none;
-  return plan_conv_wave(M, N, Kpad, bf16, first.tn, first.nw);
+  return plan_conv_wave(M, N, Kpad, bf16, step_align, first.tn, first.nw);
 }
 
 
@@ -163,8 +170,9 @@ std::string KernelTable::resolve(const AqlRuntime& rt) {
     const std::string B = b ? "true" : "false";
     for (int v = 0; v < 6; ++v) {
       const std::string tp = B + ", " + std::to_string(tn_[v]) + ", " + std::to_string(nw_[v]) + ", ";
-      for (int m = 0; m < 3; ++m) conv[b][v][m] = get("daris::conv_wave_kernel<" + tp + std::to_string(m) + ">", sizeof(ConvArgs));
-      for (int m = 0; m < 2; ++m) pair[b][v][m] = get("daris::conv_wave_pair_kernel<" + tp + std::to_string(m) + ">", kPairBytes);
+      for (int m = 0; m < 4; ++m) conv[b][v][m] = get("daris::conv_wave_kernel<" + tp + std::to_string(m) + ">", sizeof(ConvArgs));
+      static const int pair_modes[3] = {0, 1, 3};
+      for (int m = 0; m < 3; ++m) pair[b][v][m] = get("daris::conv_wave_pair_kernel<" + tp + std::to_string(pair_modes[m]) + ">", kPairBytes);
     }
     reduce[b] = get("daris::splitk_reduce_kernel<" + B + ">", sizeof(ReduceArgs));
     dwconv[b] = get("daris::dwconv_kernel<" + B + ">", sizeof(DwArgs));
@@ -190,8 +198,10 @@ static bool push_reduce(const KernelTable& kt, const ConvPlan& pl, const ConvArg
 bool encode_conv(const KernelTable& kt, const ConvPlan& pl, const ConvArgs& a, int bf16, std::vector<KernelLaunch>* out) {
   const int variant = pl.kernel - (bf16 ? K_CONVW_BF16_T1W2 : K_CONVW_F32_T1W2);
   if (variant < 0 || variant >= 6 || pl.threads != 64 * pl.nw) return false;
-  // 0: a K step never straddles a filter tap; 1: general walk; 2: layer 0 reading the caller's fp32 [C][H][W] input
-  const int mode = a.c_real > 0 ? 2 : (a.Cin % (bf16 ? 16 : 8) == 0 ? 0 : 1);
+  // 0: a K step never straddles a filter tap; 1: general walk; 2: layer 0 reading the caller's fp32 [C][H][W] input;
+  // 3: a pixel's channels are whole 64-byte rows and the plan cuts K in chunks of two steps: pixel operand through LDS
+  const int mode = a.c_real > 0 ? 2 : (conv_rows_staged(a.Cin, bf16) && pl.step_align == 2 ? 3 : (a.Cin % (bf16 ? 16 : 8) == 0 ? 0 : 1));
+  if (mode == 3 && (pl.S % 2 || pl.sz % 2 || pl.sw % 2)) return false;
   if (mode == 2 && (a.Cin != (bf16 ? 8 : 4) || a.c_real > 4)) return false;
   if (pl.splitk > 1 && !a.ws) return false;
   if (!push(out, kt.conv[bf16][variant][mode], pl.kernel, pl.grid_x, (uint32_t)pl.threads, &a, sizeof(a))) return false;
@@ -203,6 +213,8 @@ bool encode_conv_pair(const KernelTable& kt, const ConvPlan& pl0, const ConvArgs
   const int ks = bf16 ? 16 : 8;
   const bool aligned = a0.Cin % ks == 0;
   if (pl0.kernel != pl1.kernel || aligned != (a1.Cin % ks == 0) || pl1.splitk != 1 || a0.c_real > 0 || a1.c_real > 0) return false;
+  const bool staged = conv_rows_staged(a0.Cin, bf16) && conv_rows_staged(a1.Cin, bf16) && pl0.step_align == 2 && pl1.step_align == 2;
+  if (staged && (pl0.S % 2 || pl0.sz % 2 || pl0.sw % 2 || pl1.S % 2 || pl1.sz % 2 || pl1.sw % 2)) return false;
   const int variant = pl0.kernel - (bf16 ? K_CONVW_BF16_T1W2 : K_CONVW_F32_T1W2);
   if (variant < 0 || variant >= 6 || (pl0.splitk > 1 && !a0.ws)) return false;
   PairArgs pa;
@@ -210,7 +222,7 @@ bool encode_conv_pair(const KernelTable& kt, const ConvPlan& pl0, const ConvArgs
   pa.p0 = a0;
   pa.p1 = a1;
   pa.n0 = (int)((pl0.grid_x + 7) / 8 * 8);  // the second problem starts at a multiple of 8: its workgroup -> XCD relation is kept
-  if (!push(out, kt.pair[bf16][variant][aligned ? 0 : 1], pl0.kernel, (uint32_t)pa.n0 + pl1.grid_x, (uint32_t)pl0.threads, &pa, kPairBytes)) return false;
+  if (!push(out, kt.pair[bf16][variant][staged ? 2 : (aligned ? 0 : 1)], pl0.kernel, (uint32_t)pa.n0 + pl1.grid_x, (uint32_t)pl0.threads, &pa, kPairBytes)) return false;
   return push_reduce(kt, pl0, a0, bf16, out);
 }
 

@@ -17,7 +17,7 @@ uint16_t host_f32_to_bf16(float f) {
   return (uint16_t)(u >> 16);
 }
 
-std::string build_plan(const daris_dnn& dnn, bool keep_activations, bool pair_launches, bool fuse_ingest, NetPlan* out) {
+std::string build_plan(const daris_dnn& dnn, bool keep_activations, bool pair_launches, bool fuse_ingest, bool staged_rows, NetPlan* out) {
   NetPlan& net = *out;
   net = NetPlan();
   if (dnn.n_layers < 1 || !dnn.layers) return "DNN has no layers";
@@ -67,7 +67,7 @@ std::string build_plan(const daris_dnn& dnn, bool keep_activations, bool pair_la
           // the kernels divide pixel and k indices by Wo, Cin and kw with 32-bit multipliers: operands must stay small
           if ((uint64_t)(o.H * (uint64_t)o.W + 64) * (uint64_t)o.W >= (1ull << 32) || (uint64_t)(L.Kpad + 64) * (uint64_t)in.Cs >= (1ull << 32))
             return "layer " + std::to_string(l) + ": tensor too large for the kernels' index arithmetic";
-          L.cp = plan_conv(o.H * o.W, o.Cs, L.Kpad, net.bf16);
+          L.cp = plan_conv(o.H * o.W, o.Cs, L.Kpad, net.bf16, staged_rows && conv_rows_staged(in.Cs, net.bf16) ? 2 : 1);
           L.kernel_id = L.cp.kernel;
           net.ws_bytes = std::max(net.ws_bytes, L.cp.ws_bytes);
         } else {
@@ -120,7 +120,8 @@ std::string build_plan(const daris_dnn& dnn, bool keep_activations, bool pair_la
     if (A.in_t != B.in_t || B.res_t == l + 1) continue;
     LayerPlan& heavy = A.macs > B.macs ? A : B;
     LayerPlan& light = A.macs > B.macs ? B : A;
-    const ConvPlan like = plan_conv_like(heavy.cp, light.out.H * light.out.W, light.out.Cs, light.Kpad, net.bf16);
+    const ConvPlan like = plan_conv_like(heavy.cp, light.out.H * light.out.W, light.out.Cs, light.Kpad, net.bf16,
+                                         staged_rows && conv_rows_staged(net.tensor(light.in_t).Cs, net.bf16) ? 2 : 1);
     if (like.kernel == K_NONE) continue;
     light.cp = like;
     light.kernel_id = like.kernel;

@@ -50,9 +50,9 @@ struct NetPlan {
 };
 
 // Builds shapes, MACs, legal cuts, buffer slots and kernel plans.  pair_launches: two independent convolutions on one
-// tensor share a launch; fuse_ingest: the first convolution may read the caller's input layout itself.  Returns "" or an
-// error text.
-std::string build_plan(const daris_dnn& dnn, bool keep_activations, bool pair_launches, bool fuse_ingest, NetPlan* out);
+// tensor share a launch; fuse_ingest: the first convolution may read the caller's input layout itself; staged_rows:
+// convolutions whose pixels are whole 64-byte rows fetch them coalesced through LDS.  Returns "" or an error text.
+std::string build_plan(const daris_dnn& dnn, bool keep_activations, bool pair_launches, bool fuse_ingest, bool staged_rows, NetPlan* out);
 // Chooses k - 1 cuts minimising the largest per-stage MAC count, ties to the lexicographically smallest cut
 // list.  Returns false when k exceeds the number of legal cuts + 1.
 bool split_stages(NetPlan* net, int k);

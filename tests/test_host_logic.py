@@ -414,7 +414,7 @@ def test_code_object_kernels_match_the_argument_structures():
         assert size == want[base[0]], (name, size)
         assert scratch == 0 and lds <= 65536, (name, scratch, lds)
         seen[base[0]] = seen.get(base[0], 0) + 1
-    assert seen == {"conv_wave_kernel": 36, "conv_wave_pair_kernel": 24, "splitk_reduce_kernel": 2, "dwconv_kernel": 2,
+    assert seen == {"conv_wave_kernel": 48, "conv_wave_pair_kernel": 36, "splitk_reduce_kernel": 2, "dwconv_kernel": 2,
                     "maxpool_kernel": 2, "gavgpool_kernel": 2, "fc_kernel": 2, "ingest_kernel": 2, "egress_kernel": 2,
                     "cu_probe_kernel": 1}
 
