@@ -67,6 +67,8 @@ enum {
                                  convolution                                                                     */
   DARIS_NO_STAGED_ROWS = 2048 /* ... and feed every convolution's pixel operand straight from global memory to registers
                                  instead of fetching whole 64-byte rows through LDS where the shape allows (A/B)   */
+  ,DARIS_NO_SMALL_TILES = 4096 /* ... and keep 32-pixel tiles with a K split across workgroups (and its reduction launch)
+                                 for deep layers of few pixels, instead of 16-pixel tiles (A/B)                  */
 };
 
 enum { DARIS_LP = 0, DARIS_HP = 1 };

@@ -14,8 +14,8 @@ extern "C" {
 
 /* Launch plan of one layer, for inspection and for host-side checks of what the kernels assume (no device needed).
  * Writes 27 values into out (host int64[cap >= 27]) and returns 27: [0] kernel id (daris_kernel_name), [1] 1 = dense
- * convolution (the rest is meaningful only then), [2] 1 (one kernel family), [3] M = output
- * pixels, [4] N = output channels incl. padding, [5] K, [6] K padded, [7] channel blocks of 32 per wave tile, [8] waves
+ * convolution (the rest is meaningful only then), [2] pixels per wave tile (32, or 16: then channel blocks are 16 wide too), [3] M = output
+ * pixels, [4] N = output channels incl. padding, [5] K, [6] K padded, [7] channel blocks per wave tile, [8] waves
  * per workgroup, [9] K steps in total, [10] per workgroup slice, [11] per wave, [12] split-K factor, [13] pixel tiles,
  * [14] channel tiles, [15] weight groups, [16] workgroup order mode, [17..19] grid x y z, [20] threads per workgroup,
  * [21] split-K workspace bytes, [22] layer it shares a launch with or -1, [23] 1 = the joint launch is issued at this

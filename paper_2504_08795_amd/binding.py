@@ -13,7 +13,7 @@ LIB_PATH = os.environ.get("DARIS_LIB") or os.path.join(_HERE, "libdaris.so")   #
 
 OK, EINVAL, ENOMEM, EHIP, ESTATE, ERANGE = 0, -1, -2, -3, -4, -5
 VIRTUAL_TIME, NO_DEVICE, NO_LAST, NO_PRIOR, NO_FIXED, HP_ADMISSION, KEEP_ACTIVATIONS, WAVE_PRIORITY, SHARED_QUEUE = 1, 2, 4, 8, 16, 32, 64, 128, 256
-NO_PAIR, NO_FUSED_INGEST, NO_STAGED_ROWS = 512, 1024, 2048
+NO_PAIR, NO_FUSED_INGEST, NO_STAGED_ROWS, NO_SMALL_TILES = 512, 1024, 2048, 4096
 LP, HP = 0, 1
 FP32, BF16 = 0, 1
 ACCEPTED, MIGRATED, REJECT_ADMISSION, REJECT_OVERRUN, QUEUED = 1, 2, 3, 4, 5
@@ -189,7 +189,7 @@ def daris_get_stage_cuts(t):
     return list(buf[:n])
 
 
-PLAN_FIELDS = ("kernel_id", "dense_conv", "wave", "M", "N", "K", "Kpad", "tn", "nw", "S", "sz", "sw", "splitk", "MT", "NTn", "G", "xmode",
+PLAN_FIELDS = ("kernel_id", "dense_conv", "rows", "M", "N", "K", "Kpad", "tn", "nw", "S", "sz", "sw", "splitk", "MT", "NTn", "G", "xmode",
                "grid_x", "grid_y", "grid_z", "threads", "ws_bytes", "pair_with", "pair_lead", "out_slot", "in_slot", "res_slot")
 
 

@@ -925,7 +925,7 @@ daris_task daris_register_task(const daris_dnn* dnn, int64_t period_ns, int64_t 
   if (priority != DARIS_HP && priority != DARIS_LP) return fail(DARIS_EINVAL, "priority must be DARIS_HP or DARIS_LP");
   if (G->tasks.size() >= 65535) return fail(DARIS_ERANGE, "too many tasks");
   std::unique_ptr<TaskRt> T(new TaskRt());
-  std::string err = build_plan(*dnn, G->flags & DARIS_KEEP_ACTIVATIONS, !(G->flags & DARIS_NO_PAIR), !(G->flags & DARIS_NO_FUSED_INGEST), !(G->flags & DARIS_NO_STAGED_ROWS), &T->net);
+  std::string err = build_plan(*dnn, G->flags & DARIS_KEEP_ACTIVATIONS, !(G->flags & DARIS_NO_PAIR), !(G->flags & DARIS_NO_FUSED_INGEST), !(G->flags & DARIS_NO_STAGED_ROWS), !(G->flags & DARIS_NO_SMALL_TILES), &T->net);
   if (!err.empty()) return fail(DARIS_EINVAL, "%s", err.c_str());
   if (!G->nodev) {
     NetPlan& net = T->net;
@@ -1013,7 +1013,7 @@ int32_t daris_get_launch_plan(daris_task t, int layer, int64_t* out, int32_t cap
   const LayerPlan& L = net.layers[layer];
   const ConvPlan& c = L.cp;
   const bool conv = L.d.op == DARIS_OP_CONV && !L.depthwise;
-  const int64_t v[27] = {L.kernel_id, conv ? 1 : 0, conv ? 1 : 0, (int64_t)L.out.H * L.out.W, L.out.Cs, L.K, L.Kpad,
+  const int64_t v[27] = {L.kernel_id, conv ? 1 : 0, conv ? c.rows : 0, (int64_t)L.out.H * L.out.W, L.out.Cs, L.K, L.Kpad,
                          c.tn, c.nw, c.S, c.sz, c.sw, c.splitk, c.MT, c.NTn, c.G, c.xmode, (int64_t)c.grid_x, 1, 1,
                          c.threads, (int64_t)c.ws_bytes, L.pair_with, L.pair_lead ? 1 : 0,
                          L.out.slot, net.tensor(L.in_t).slot, L.res_t >= 0 ? net.tensor(L.res_t).slot : -1};

@@ -16,6 +16,9 @@ enum KernelId : int32_t {
   // wave-tile implicit GEMM: TN 32-channel blocks per wave, NW waves splitting K inside the workgroup
   K_CONVW_F32_T1W2, K_CONVW_F32_T1W4, K_CONVW_F32_T1W8, K_CONVW_F32_T2W2, K_CONVW_F32_T2W4, K_CONVW_F32_T2W8,
   K_CONVW_BF16_T1W2, K_CONVW_BF16_T1W4, K_CONVW_BF16_T1W8, K_CONVW_BF16_T2W2, K_CONVW_BF16_T2W4, K_CONVW_BF16_T2W8,
+  // the same with 16-pixel tiles of TN 16-channel blocks (deep, skinny layers)
+  K_CONV16_F32_T1W2, K_CONV16_F32_T1W4, K_CONV16_F32_T1W8, K_CONV16_F32_T2W2, K_CONV16_F32_T2W4, K_CONV16_F32_T2W8,
+  K_CONV16_BF16_T1W2, K_CONV16_BF16_T1W4, K_CONV16_BF16_T1W8, K_CONV16_BF16_T2W2, K_CONV16_BF16_T2W4, K_CONV16_BF16_T2W8,
   K_SPLITK_REDUCE, K_DWCONV, K_MAXPOOL, K_GAVGPOOL, K_FC, K_INGEST, K_EGRESS,
   K_COUNT
 };
@@ -66,6 +69,7 @@ struct FcArgs {
 struct ConvPlan {
   int32_t kernel;  // KernelId
   int splitk;      // K slices across workgroups (1 = none); > 1 needs the workspace and the reduction launch
+  int rows;                        // pixels per wave tile: 32 (conv_wave_*: channel blocks of 32) or 16 (conv_wave16_*: blocks of 16)
   int tn, nw, S, sz, sw, MT, NTn, G, xmode;
   int step_align;                  // K slices are multiples of this many steps (2: staged pixel operand possible)
   int tiles;                       // output tiles per grid.z slice
@@ -78,7 +82,9 @@ struct ConvPlan {
 inline bool conv_rows_staged(int cin_stride, int bf16) { return cin_stride > 0 && (cin_stride * (bf16 ? 2 : 4)) % 64 == 0; }
 // bf16 = 0/1.  Chooses tile shape, waves per workgroup and split-K from (M, N, Kpad) only, so results do not depend on the
 // partition a stage runs in.  step_align = 2 cuts K in whole chunks of two steps (for conv_rows_staged shapes), else 1.
-ConvPlan plan_conv(int M, int N, int Kpad, int bf16, int step_align);
+// cin_stride = the input tensor's channel stride: when it is a whole number of the 16-row kernel's K steps and the 32-row
+// plan would split K across workgroups, a 16-row plan that does not need to is chosen instead (cin_stride 0: never).
+ConvPlan plan_conv(int M, int N, int Kpad, int bf16, int step_align, int cin_stride = 0);
 // Plan for a second convolution that is to share a launch with `first`: the same wave-tile kernel variant, K not split
 // across workgroups.  Returns a plan with kernel == K_NONE when that is not possible.
 ConvPlan plan_conv_like(const ConvPlan& first, int M, int N, int Kpad, int bf16, int step_align);
@@ -105,6 +111,8 @@ struct KernelLaunch {
 struct KernelTable {
   const AqlKernel* conv[2][6][4] = {};  // [bf16][(tn - 1) * 3 + log2(nw) - 1][gather mode 0..3]
   const AqlKernel* pair[2][6][3] = {};  // gather modes 0, 1, 3
+  const AqlKernel* conv16[2][6] = {};   // 16-row tiles: [bf16][(tn - 1) * 3 + log2(nw) - 1]
+  const AqlKernel* pair16[2][6] = {};
   const AqlKernel *reduce[2] = {}, *dwconv[2] = {}, *maxpool[2] = {}, *gavgpool[2] = {}, *fc[2] = {}, *ingest[2] = {}, *egress[2] = {};
   const AqlKernel* cu_probe = nullptr;
   // "" or the name of the first kernel that is missing or whose argument size is not what this header declares

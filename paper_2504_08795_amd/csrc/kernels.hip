@@ -505,6 +505,223 @@ __global__ __launch_bounds__(NW * 64) void conv_wave_pair_kernel(const ConvArgs 
   else conv_wave_body<BF16, TN, NW, MODE>(p1, L - n0);
 }
 
+// ---- 16-row wave tiles for deep, skinny layers -----------------------------------------------------------------------
+//
+// A layer with few output pixels and many channels (the 14x14 and 7x7 stages of a ResNet) has too few 32 x 32 tiles to
+// fill a partition; the kernel above then splits K across workgroups and a second launch sums the partial tiles.  Here a
+// wave owns 16 pixels x (16 * TB) channels (v_mfma_f32_16x16x4_f32 / 16x16x32_bf16): at the same matrix rate there are
+// two to four times as many tiles, so the partition fills with K split only among the NW waves of a workgroup, the sum
+// goes through LDS as before, and the reduction launch disappears.  One K step is 64 bytes of a pixel: lane (i, q) =
+// (pixel row i = lane % 16, quarter q = lane / 16) loads the 16 bytes at k = step * KS + q * VEC, and the weights were
+// packed at registration as [channel block of 16][step][lane (j, q)][16 B] with the same k order.  Cin is a multiple of
+// KS, so a step never straddles a filter tap and the K walk is wave-uniform.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <bool BF16, int TB, int NW>
+__device__ __forceinline__ void conv_wave16_body(const ConvArgs& p, const int L) {
+  constexpr int ES = BF16 ? 2 : 4;
+  constexpr int VEC = 16 / ES;
+  constexpr int KS = 4 * VEC;  // k per step: 16 (fp32) / 32 (bf16)
+  constexpr int TILE = TB * 256;
+  constexpr int D = 4;
+  constexpr int STAGE_V = 16 * 5;  // 16-byte vectors of one wave's staging buffer: 16 pixels x (4 pieces + 1 pad)
+  constexpr int LDS_F = NW * STAGE_V * 4 > NW * TILE ? NW * STAGE_V * 4 : NW * TILE;
+  static_assert(TB == 1 || TB == 2, "the epilogue selects between at most two channel blocks");
+
+  __shared__ __align__(16) float red[LDS_F];
+
+  if (p.wave_prio) __builtin_amdgcn_s_setprio(3);
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int li = lane & 15, lq = lane >> 4;
+  int mt, g;  // workgroup -> (pixel tile, weight group), tiles that read the same weights on one XCD (see conv_wave_body)
+  {
+    const int x = L & 7, q = L >> 3;
+    if (p.xmode == 1) {
+      g = (q / p.MT) * 8 + x;
+      mt = q % p.MT;
+      if (g >= p.G) return;
+    } else if (p.xmode == 2) {
+      const int r = 8 / p.G;
+      g = x / r;
+      mt = q * r + (x % r);
+      if (mt >= p.MT) return;
+    } else {
+      g = L / p.MT;
+      mt = L % p.MT;
+      if (g >= p.G) return;
+    }
+  }
+  const int zi = g / p.NTn;
+  const int m0 = mt * 16, nb0 = (g - zi * p.NTn) * TB;
+  const int s_wg0 = zi * p.sz;
+  const int s_wg1 = min(s_wg0 + p.sz, p.S);
+  const int sbeg = min(s_wg0 + wave * p.sw, s_wg1);
+  const int nsteps = min(sbeg + p.sw, s_wg1) - sbeg;
+
+  // The pixel operand is fetched as whole 64-byte rows (lane = (pixel lane / 4, 16-byte piece lane % 4): four
+  // neighbouring lanes read one contiguous row, the access shape the load unit serves at full rate) and turned into MFMA
+  // order (lane = (pixel row, quarter)) through the wave's own corner of LDS, as in the staged mode of the 32-row kernel.
+  const unsigned char* xb = (const unsigned char*)p.x;
+  const int prow = lane >> 2, piece = lane & 3;
+  const int m = m0 + prow;
+  const bool a_ok = m < p.M;
+  const int oy = fast_div(m, p.mg_wo), ox = m - oy * p.Wo;
+  const int iy0 = oy * p.stride - p.pad, ix0 = ox * p.stride - p.pad;
+  const int kcur = sbeg * KS;
+  const int tap = fast_div(kcur, p.mg_cin);
+  int ci = kcur - tap * p.Cin;
+  int ky = fast_div(tap, p.mg_kw), kx = tap - ky * p.kw;
+  bool a_valid;
+  const unsigned char* ap;
+  auto enter_tap = [&]() {
+    const int iy = iy0 + ky, ix = ix0 + kx;
+    a_valid = a_ok && ky < p.kh && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
+    ap = xb + ((size_t)(a_valid ? iy * p.W + ix : 0) * p.Cin + ci) * ES + piece * 16;  // always a valid address
+  };
+  uint4* const st = reinterpret_cast<uint4*>(red) + wave * STAGE_V;
+  enter_tap();
+  const unsigned char* wptr[TB];
+#pragma unroll
+  for (int j = 0; j < TB; ++j) wptr[j] = (const unsigned char*)p.w + (((size_t)(nb0 + j) * p.S + sbeg) * 64 + lane) * 16;
+
+  uint4 ar[D], br[D][TB];
+  bool av[D];
+  auto load = [&](int d) {
+    ar[d] = *(const uint4*)ap;
+    av[d] = a_valid;
+#pragma unroll
+    for (int j = 0; j < TB; ++j) {
+      br[d][j] = *(const uint4*)wptr[j];
+      wptr[j] += 1024;
+    }
+    ci += KS;
+    if (ci >= p.Cin) {  // wave-uniform
+      ci -= p.Cin;
+      if (++kx == p.kw) { kx = 0; ++ky; }
+      enter_tap();
+    } else {
+      ap += KS * ES;
+    }
+  };
+
+  // epilogue operands fetched ahead of the K loop: this thread's quad of consecutive channels (see below)
+  constexpr int QUADS = TILE / 4;
+  const bool has_quad = tid < QUADS;
+  const int qe = 4 * tid;                                     // first tile element of the quad: (b * 4 + v) * 64 + lane
+  const int qb = qe >> 8, qv = (qe >> 6) & 3, ql = qe & 63;
+  const int qm = m0 + 4 * (ql >> 4) + qv;                      // pixel
+  const int qn = (nb0 + qb) * 16 + (ql & 15);                  // first channel
+  const bool q_ok = has_quad && qm < p.M && qn < p.Cout;
+  const bool own_epilogue = p.splitk == 1;
+  float4 bias = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (q_ok) bias = *(const float4*)(p.bias + qn);
+  using ResVec = typename std::conditional<BF16, uint2, uint4>::type;
+  ResVec res_pre = ResVec();
+  const bool use_res = own_epilogue && p.res != nullptr;
+  if (use_res && q_ok) res_pre = *(const ResVec*)((const unsigned char*)p.res + ((size_t)qm * p.Cout + qn) * ES);
+
+  f32x4 acc[TB];
+#pragma unroll
+  for (int j = 0; j < TB; ++j)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) acc[j][v] = 0.f;
+
+  auto compute = [&](int d) {
+    st[prow * 5 + piece] = keep_if(av[d], ar[d]);
+    // lanes exchange data through the wave's buffer: order the accesses of the whole wave, not only of each lane
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const uint4 a4 = st[li * 5 + lq];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    if (BF16) {
+#pragma unroll
+      for (int j = 0; j < TB; ++j)
+        acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a4), __builtin_bit_cast(bf16x8, br[d][j]), acc[j], 0, 0, 0);
+    } else {
+#pragma unroll
+      for (int j = 0; j < TB; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a4.x), __uint_as_float(br[d][j].x), acc[j], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < TB; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a4.y), __uint_as_float(br[d][j].y), acc[j], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < TB; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a4.z), __uint_as_float(br[d][j].z), acc[j], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < TB; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a4.w), __uint_as_float(br[d][j].w), acc[j], 0, 0, 0);
+    }
+  };
+
+  // the same D-deep software pipeline as the 32-row kernel: unconditional loads, conditional computes only in the tail
+#pragma unroll
+  for (int d = 0; d < D; ++d) load(d);
+  int done = 0;
+  for (; done + D <= nsteps; done += D) {
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+      compute(d);
+      load(d);
+    }
+  }
+#pragma unroll
+  for (int d = 0; d < D; ++d)
+    if (done + d < nsteps) compute(d);
+
+  // partial tiles of the NW waves summed in wave order; accumulator v of lane l is pixel 4 * (l / 16) + v, channel l % 16
+  __syncthreads();  // the partial tiles reuse the LDS of every wave's staging buffer
+#pragma unroll
+  for (int j = 0; j < TB; ++j)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) red[wave * TILE + (j * 4 + v) * 64 + lane] = acc[j][v];
+  __syncthreads();
+  if (!q_ok) return;
+  float4 sum = *(const float4*)&red[qe];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) {
+    const float4 t = *(const float4*)&red[w * TILE + qe];
+    sum.x += t.x; sum.y += t.y; sum.z += t.z; sum.w += t.w;
+  }
+  const size_t o = (size_t)qm * p.Cout + qn;
+  if (!own_epilogue) {
+    *(float4*)(p.ws + (size_t)zi * p.M * p.Cout + o) = sum;
+    return;
+  }
+  float val[4] = {sum.x + bias.x, sum.y + bias.y, sum.z + bias.z, sum.w + bias.w};
+  if (use_res) {
+    if constexpr (BF16) {
+      val[0] += __uint_as_float(res_pre.x << 16); val[1] += __uint_as_float(res_pre.x & 0xffff0000u);
+      val[2] += __uint_as_float(res_pre.y << 16); val[3] += __uint_as_float(res_pre.y & 0xffff0000u);
+    } else {
+      val[0] += __uint_as_float(res_pre.x); val[1] += __uint_as_float(res_pre.y);
+      val[2] += __uint_as_float(res_pre.z); val[3] += __uint_as_float(res_pre.w);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) val[i] = apply_act(val[i], p.act);
+  if (BF16) {
+    uint2 out;
+    out.x = f32_to_bf16_bits(val[0]) | (f32_to_bf16_bits(val[1]) << 16);
+    out.y = f32_to_bf16_bits(val[2]) | (f32_to_bf16_bits(val[3]) << 16);
+    *(uint2*)((uint16_t*)p.y + o) = out;
+  } else {
+    *(float4*)((float*)p.y + o) = make_float4(val[0], val[1], val[2], val[3]);
+  }
+}
+
+template <bool BF16, int TB, int NW>
+__global__ __launch_bounds__(NW * 64) void conv_wave16_kernel(const ConvArgs p) {
+  conv_wave16_body<BF16, TB, NW>(p, (int)blockIdx.x);
+}
+
+// Two independent convolutions on one tensor in one launch, as conv_wave_pair_kernel: workgroups [0, n0) work on p0.
+template <bool BF16, int TB, int NW>
+__global__ __launch_bounds__(NW * 64) void conv_wave16_pair_kernel(const ConvArgs p0, const ConvArgs p1, const int n0) {
+  const int L = (int)blockIdx.x;
+  if (L < n0) conv_wave16_body<BF16, TB, NW>(p0, L);
+  else conv_wave16_body<BF16, TB, NW>(p1, L - n0);
+}
+
 // ---- depthwise convolution: memory bound, one thread per (output pixel, 16-byte channel vector) -----------------------
 template <bool BF16>
 __global__ __launch_bounds__(256) void dwconv_kernel(const DwArgs a) {
@@ -681,9 +898,17 @@ __global__ __launch_bounds__(64) void cu_probe_kernel(uint32_t* out, int spin) {
   template __global__ void conv_wave_pair_kernel<B, TN_, NW_, 0>(const ConvArgs, const ConvArgs, const int); \
   template __global__ void conv_wave_pair_kernel<B, TN_, NW_, 1>(const ConvArgs, const ConvArgs, const int); \
   template __global__ void conv_wave_pair_kernel<B, TN_, NW_, 3>(const ConvArgs, const ConvArgs, const int);
+#define DARIS_INST_CONV16(B, TB_)                                                                  \
+  template __global__ void conv_wave16_kernel<B, TB_, 2>(const ConvArgs);                          \
+  template __global__ void conv_wave16_kernel<B, TB_, 4>(const ConvArgs);                          \
+  template __global__ void conv_wave16_kernel<B, TB_, 8>(const ConvArgs);                          \
+  template __global__ void conv_wave16_pair_kernel<B, TB_, 2>(const ConvArgs, const ConvArgs, const int); \
+  template __global__ void conv_wave16_pair_kernel<B, TB_, 4>(const ConvArgs, const ConvArgs, const int); \
+  template __global__ void conv_wave16_pair_kernel<B, TB_, 8>(const ConvArgs, const ConvArgs, const int);
 #define DARIS_INST_ALL(B)                                                                          \
   DARIS_INST_CONV(B, 1, 2) DARIS_INST_CONV(B, 1, 4) DARIS_INST_CONV(B, 1, 8)                        \
   DARIS_INST_CONV(B, 2, 2) DARIS_INST_CONV(B, 2, 4) DARIS_INST_CONV(B, 2, 8)                        \
+  DARIS_INST_CONV16(B, 1) DARIS_INST_CONV16(B, 2)                                                   \
   template __global__ void splitk_reduce_kernel<B>(const float*, const float*, const void*, void*, int, int, int, int); \
   template __global__ void dwconv_kernel<B>(const DwArgs);                                         \
   template __global__ void maxpool_kernel<B>(const PoolArgs);                                      \
@@ -695,5 +920,6 @@ DARIS_INST_ALL(false)
 DARIS_INST_ALL(true)
 #undef DARIS_INST_ALL
 #undef DARIS_INST_CONV
+#undef DARIS_INST_CONV16
 
 }  // namespace daris

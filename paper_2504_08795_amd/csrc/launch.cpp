@@ -14,6 +14,8 @@ static const char* const kNames[K_COUNT] = {
     "none",
     "conv_wave_f32_t1w2", "conv_wave_f32_t1w4", "conv_wave_f32_t1w8", "conv_wave_f32_t2w2", "conv_wave_f32_t2w4", "conv_wave_f32_t2w8",
     "conv_wave_bf16_t1w2", "conv_wave_bf16_t1w4", "conv_wave_bf16_t1w8", "conv_wave_bf16_t2w2", "conv_wave_bf16_t2w4", "conv_wave_bf16_t2w8",
+    "conv_wave16_f32_t1w2", "conv_wave16_f32_t1w4", "conv_wave16_f32_t1w8", "conv_wave16_f32_t2w2", "conv_wave16_f32_t2w4", "conv_wave16_f32_t2w8",
+    "conv_wave16_bf16_t1w2", "conv_wave16_bf16_t1w4", "conv_wave16_bf16_t1w8", "conv_wave16_bf16_t2w2", "conv_wave16_bf16_t2w4", "conv_wave16_bf16_t2w8",
     "splitk_reduce", "dwconv", "maxpool", "gavgpool", "fc", "ingest", "egress"};
 
 const char* kernel_name(int32_t id) { return (id >= 0 && id < K_COUNT) ? kNames[id] : "?"; }
@@ -37,7 +39,8 @@ static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16, int step_align,
   if (force_tn) tn = force_tn;
   // Fetching the pixel operand as coalesced rows through LDS pays where a launch is bound by its loads: every bf16 shape
   // (+11 % on the saturated ResNet-50 set) and 32-channel fp32 tiles.  fp32 tiles of 64 channels are bound by the matrix
-  // pipe; there the extra LDS round trip and registers cost 10-25 % (measured on VGG-16's layers), so they stay register-fed.
+  // pipe; there the extra LDS round trip and registers cost 10-25 % (measured on VGG-16's layers; still 10 % with the
+  // register count held at 128), so they stay register-fed.
   if (step_align > 1 && !bf16 && tn == 2) step_align = 1;
   const int tiles = cdiv(M, 32) * (nb / tn);
   const int nominal_cus = kNominalWaveSlots / 4;
@@ -73,6 +76,7 @@ static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16, int step_align,
   // operand in chunks of two steps; S is then even as well)
   const int sz = cdiv(cdiv(S, z), step_align) * step_align;
   z = cdiv(S, sz);
+  pl.rows = 32;
   pl.tn = tn;
   pl.nw = nw;
   pl.S = S;
@@ -101,10 +105,69 @@ static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16, int step_align,
   return pl;
 }
 
-ConvPlan plan_conv(int M, int N, int Kpad, int bf16, int step_align) { return plan_conv_wave(M, N, Kpad, bf16, step_align); }
+// 16-pixel tiles of tn 16-channel blocks, K split among the waves of a workgroup only.  Chosen for layers whose 32-row
+// plan needs a reduction launch; returns kernel == K_NONE when the shape does not fill three quarters of the nominal
+// partition either, or is too shallow to split eight (four) ways.
+static ConvPlan plan_conv_wave16(int M, int N, int Kpad, int bf16, int force_tn = 0, int force_nw = 0) {
+  ConvPlan pl = ConvPlan();
+  const int ks = bf16 ? 32 : 16;
+  if (Kpad % ks) return pl;
+  const int S = Kpad / ks;
+  const int nb = cdiv(N, 16), mt = cdiv(M, 16);
+  const int nominal_cus = kNominalWaveSlots / 4;
+  // two channel blocks per wave halve the reads of the pixel operand: taken when that still gives nearly one workgroup per CU
+  int tn = (nb % 2 == 0 && mt * (nb / 2) >= nominal_cus * 3 / 4) ? 2 : 1;
+  if (force_tn) tn = force_tn;
+  if (nb % tn) return pl;
+  const int tiles = mt * (nb / tn);
+  int nw = bf16 ? 4 : 8;
+  while (nw > 2 && S / nw < 4) nw /= 2;
+  if (force_nw) {  // second problem of a two-problem launch: the first one's kernel variant, whatever its own shape
+    nw = force_nw;
+  } else if (tiles < nominal_cus * 3 / 4 || tiles > 4 * nominal_cus || S / nw < 2) {
+    return pl;
+  }
+  pl.rows = 16;
+  pl.tn = tn;
+  pl.nw = nw;
+  pl.S = S;
+  pl.sz = S;
+  pl.sw = cdiv(S, nw);
+  pl.step_align = 1;
+  pl.splitk = 1;
+  pl.tiles = tiles;
+  pl.threads = nw * 64;
+  pl.MT = mt;
+  pl.NTn = nb / tn;
+  pl.G = pl.NTn;
+  if (pl.G % 8 == 0) {
+    pl.xmode = 1;
+    pl.grid_x = (uint32_t)(pl.G * pl.MT);
+  } else if (8 % pl.G == 0) {
+    pl.xmode = 2;
+    pl.grid_x = (uint32_t)(8 * cdiv(pl.MT, 8 / pl.G));
+  } else {
+    pl.xmode = 0;
+    pl.grid_x = (uint32_t)(pl.G * pl.MT);
+  }
+  pl.ws_bytes = 0;
+  const int wi = nw == 2 ? 0 : (nw == 4 ? 1 : 2);
+  pl.kernel = (bf16 ? K_CONV16_BF16_T1W2 : K_CONV16_F32_T1W2) + (tn - 1) * 3 + wi;
+  return pl;
+}
+
+ConvPlan plan_conv(int M, int N, int Kpad, int bf16, int step_align, int cin_stride) {
+  const ConvPlan pl = plan_conv_wave(M, N, Kpad, bf16, step_align);
+  if (pl.splitk > 1 && cin_stride > 0 && cin_stride % (bf16 ? 32 : 16) == 0) {
+    const ConvPlan p16 = plan_conv_wave16(M, N, Kpad, bf16);
+    if (p16.kernel != K_NONE) return p16;
+  }
+  return pl;
+}
 
 ConvPlan plan_conv_like(const ConvPlan& first, int M, int N, int Kpad, int bf16, int step_align) {
   ConvPlan none = ConvPlan();
+  if (first.rows == 16) return plan_conv_wave16(M, N, Kpad, bf16, first.tn, first.nw);
   if (cdiv(N, 32) % first.tn != 0) return none;
   return plan_conv_wave(M, N, Kpad, bf16, step_align, first.tn, first.nw);
 }
@@ -174,6 +237,10 @@ std::string KernelTable::resolve(const AqlRuntime& rt) {
       static const int pair_modes[3] = {0, 1, 3};
       for (int m = 0; m < 3; ++m) pair[b][v][m] = get("daris::conv_wave_pair_kernel<" + tp + std::to_string(pair_modes[m]) + ">", kPairBytes);
     }
+    for (int v = 0; v < 6; ++v) {
+      conv16[b][v] = get("daris::conv_wave16_kernel<" + B + ", " + std::to_string(tn_[v]) + ", " + std::to_string(nw_[v]) + ">", sizeof(ConvArgs));
+      pair16[b][v] = get("daris::conv_wave16_pair_kernel<" + B + ", " + std::to_string(tn_[v]) + ", " + std::to_string(nw_[v]) + ">", kPairBytes);
+    }
     reduce[b] = get("daris::splitk_reduce_kernel<" + B + ">", sizeof(ReduceArgs));
     dwconv[b] = get("daris::dwconv_kernel<" + B + ">", sizeof(DwArgs));
     maxpool[b] = get("daris::maxpool_kernel<" + B + ">", sizeof(PoolArgs));
@@ -196,6 +263,14 @@ static bool push_reduce(const KernelTable& kt, const ConvPlan& pl, const ConvArg
 }
 
 bool encode_conv(const KernelTable& kt, const ConvPlan& pl, const ConvArgs& a, int bf16, std::vector<KernelLaunch>* out) {
+  if (pl.rows == 16) {
+    const int v16 = pl.kernel - (bf16 ? K_CONV16_BF16_T1W2 : K_CONV16_F32_T1W2);
+    const int ks16 = bf16 ? 32 : 16;
+    if (v16 < 0 || v16 >= 6 || pl.threads != 64 * pl.nw || a.c_real > 0 || a.Cin % ks16 || a.Kpad % ks16 || pl.S * ks16 != a.Kpad) return false;
+    if (pl.splitk > 1 && !a.ws) return false;
+    if (!push(out, kt.conv16[bf16][v16], pl.kernel, pl.grid_x, (uint32_t)pl.threads, &a, sizeof(a))) return false;
+    return push_reduce(kt, pl, a, bf16, out);
+  }
   const int variant = pl.kernel - (bf16 ? K_CONVW_BF16_T1W2 : K_CONVW_F32_T1W2);
   if (variant < 0 || variant >= 6 || pl.threads != 64 * pl.nw) return false;
   // 0: a K step never straddles a filter tap; 1: general walk; 2: layer 0 reading the caller's fp32 [C][H][W] input;
@@ -210,9 +285,22 @@ bool encode_conv(const KernelTable& kt, const ConvPlan& pl, const ConvArgs& a, i
 
 bool encode_conv_pair(const KernelTable& kt, const ConvPlan& pl0, const ConvArgs& a0, const ConvPlan& pl1, const ConvArgs& a1, int bf16,
                       std::vector<KernelLaunch>* out) {
+  if (pl0.rows == 16) {
+    const int ks16 = bf16 ? 32 : 16;
+    const int v16 = pl0.kernel - (bf16 ? K_CONV16_BF16_T1W2 : K_CONV16_F32_T1W2);
+    if (pl1.rows != 16 || pl0.kernel != pl1.kernel || v16 < 0 || v16 >= 6 || pl0.splitk != 1 || pl1.splitk != 1 || a0.c_real > 0 || a1.c_real > 0 ||
+        a0.Cin % ks16 || a1.Cin % ks16 || pl0.S * ks16 != a0.Kpad || pl1.S * ks16 != a1.Kpad)
+      return false;
+    PairArgs pa;
+    std::memset(&pa, 0, sizeof(pa));
+    pa.p0 = a0;
+    pa.p1 = a1;
+    pa.n0 = (int)((pl0.grid_x + 7) / 8 * 8);
+    return push(out, kt.pair16[bf16][v16], pl0.kernel, (uint32_t)pa.n0 + pl1.grid_x, (uint32_t)pl0.threads, &pa, kPairBytes);
+  }
   const int ks = bf16 ? 16 : 8;
   const bool aligned = a0.Cin % ks == 0;
-  if (pl0.kernel != pl1.kernel || aligned != (a1.Cin % ks == 0) || pl1.splitk != 1 || a0.c_real > 0 || a1.c_real > 0) return false;
+  if (pl0.kernel != pl1.kernel || pl0.rows != 32 || aligned != (a1.Cin % ks == 0) || pl1.splitk != 1 || a0.c_real > 0 || a1.c_real > 0) return false;
   const bool staged = conv_rows_staged(a0.Cin, bf16) && conv_rows_staged(a1.Cin, bf16) && pl0.step_align == 2 && pl1.step_align == 2;
   if (staged && (pl0.S % 2 || pl0.sz % 2 || pl0.sw % 2 || pl1.S % 2 || pl1.sz % 2 || pl1.sw % 2)) return false;
   const int variant = pl0.kernel - (bf16 ? K_CONVW_BF16_T1W2 : K_CONVW_F32_T1W2);

@@ -17,7 +17,7 @@ uint16_t host_f32_to_bf16(float f) {
   return (uint16_t)(u >> 16);
 }
 
-std::string build_plan(const daris_dnn& dnn, bool keep_activations, bool pair_launches, bool fuse_ingest, bool staged_rows, NetPlan* out) {
+std::string build_plan(const daris_dnn& dnn, bool keep_activations, bool pair_launches, bool fuse_ingest, bool staged_rows, bool small_tiles, NetPlan* out) {
   NetPlan& net = *out;
   net = NetPlan();
   if (dnn.n_layers < 1 || !dnn.layers) return "DNN has no layers";
@@ -67,7 +67,7 @@ std::string build_plan(const daris_dnn& dnn, bool keep_activations, bool pair_la
           // the kernels divide pixel and k indices by Wo, Cin and kw with 32-bit multipliers: operands must stay small
           if ((uint64_t)(o.H * (uint64_t)o.W + 64) * (uint64_t)o.W >= (1ull << 32) || (uint64_t)(L.Kpad + 64) * (uint64_t)in.Cs >= (1ull << 32))
             return "layer " + std::to_string(l) + ": tensor too large for the kernels' index arithmetic";
-          L.cp = plan_conv(o.H * o.W, o.Cs, L.Kpad, net.bf16, staged_rows && conv_rows_staged(in.Cs, net.bf16) ? 2 : 1);
+          L.cp = plan_conv(o.H * o.W, o.Cs, L.Kpad, net.bf16, staged_rows && conv_rows_staged(in.Cs, net.bf16) ? 2 : 1, small_tiles ? in.Cs : 0);
           L.kernel_id = L.cp.kernel;
           net.ws_bytes = std::max(net.ws_bytes, L.cp.ws_bytes);
         } else {
@@ -248,6 +248,23 @@ void pack_conv(const NetPlan& net, const LayerPlan& L, const float* w, const flo
     wp->assign((size_t)kk * in.Cs * es, 0);
     for (int c = 0; c < d.c_out; ++c)
       for (int t = 0; t < kk; ++t) put<float>(wp, (size_t)t * in.Cs + c, w[(size_t)c * kk + t], bf);
+    return;
+  }
+  if (L.cp.rows == 16) {
+    // 16-row kernel: [channel block of 16][step][lane = j + 16 q][VEC], element e of lane (j, q) at step s is
+    // W[n = 16 nb + j][k = s * 4 VEC + q * VEC + e], k = tap * Cs_in + ci; blocks padded to a multiple of TN
+    const int vec = bf ? 8 : 4, ks = 4 * vec, S = L.cp.S;
+    const int nblocks = (L.out.Cs + 15) / 16;
+    const int nb_alloc = (nblocks + L.cp.tn - 1) / L.cp.tn * L.cp.tn;
+    wp->assign((size_t)nb_alloc * S * 64 * 16 + 8 * 1024, 0);  // + slack for the pipeline's refills past the last step
+    for (int o = 0; o < d.c_out; ++o)
+      for (int ci = 0; ci < d.c_in; ++ci)
+        for (int t = 0; t < kk; ++t) {
+          const int k = t * in.Cs + ci;
+          const int st = k / ks, q = (k % ks) / vec, e = k % vec;
+          const size_t lane = (size_t)(o % 16) + 16 * q;
+          put<float>(wp, (((size_t)(o / 16) * S + st) * 64 + lane) * vec + e, w[((size_t)o * d.c_in + ci) * kk + t], bf);
+        }
     return;
   }
   // [channel block of 32][step][lane = i + 32 h][VEC], element e of lane (i, h) at step s is

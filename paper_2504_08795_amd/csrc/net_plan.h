@@ -51,8 +51,9 @@ struct NetPlan {
 
 // Builds shapes, MACs, legal cuts, buffer slots and kernel plans.  pair_launches: two independent convolutions on one
 // tensor share a launch; fuse_ingest: the first convolution may read the caller's input layout itself; staged_rows:
-// convolutions whose pixels are whole 64-byte rows fetch them coalesced through LDS.  Returns "" or an error text.
-std::string build_plan(const daris_dnn& dnn, bool keep_activations, bool pair_launches, bool fuse_ingest, bool staged_rows, NetPlan* out);
+// convolutions whose pixels are whole 64-byte rows fetch them coalesced through LDS; small_tiles: deep, skinny layers
+// get 16-pixel tiles instead of a K split across workgroups.  Returns "" or an error text.
+std::string build_plan(const daris_dnn& dnn, bool keep_activations, bool pair_launches, bool fuse_ingest, bool staged_rows, bool small_tiles, NetPlan* out);
 // Chooses k - 1 cuts minimising the largest per-stage MAC count, ties to the lexicographically smallest cut
 // list.  Returns false when k exceeds the number of legal cuts + 1.
 bool split_stages(NetPlan* net, int k);

@@ -58,6 +58,8 @@ CONV_CASES = [
     (8, 1, 1, 12, 1, 1, 0, 0),        # 1x1 image, 1x1 kernel: a plain mat-vec
     (4, 9, 9, 4, 3, 3, 0, 0),         # stride equal to the kernel size: no window overlap
     (8, 6, 6, 8, 3, 1, 2, 1),         # padding larger than half the kernel: whole windows of zeros at the border
+    (256, 14, 14, 200, 3, 1, 1, 1),   # 16-pixel tiles (M = 196: ragged last tile), N = 200: 13 blocks of 16, the last one ragged
+    (512, 7, 7, 520, 3, 1, 1, 2),     # 16-pixel tiles, M = 49, 33 channel blocks, K = 4608, ReLU6
     (64, 224, 224, 64, 3, 1, 1, 1),   # the largest layer of any configuration (VGG-16 conv1_2): M = 50176
     (3, 224, 224, 64, 3, 1, 1, 1),    # VGG-16 conv1_1: K = 27, M = 50176
 ]

@@ -141,15 +141,21 @@ def _check_plan(pl, name):
     """What the kernels and their grids assume about a dense convolution's launch plan."""
     M, N, S = pl["M"], pl["N"], pl["S"]
     z = pl["splitk"]
-    assert pl["wave"] == 1 and pl["grid_y"] == 1 and pl["grid_z"] == 1 and pl["grid_x"] >= 1, name
+    rows = pl["rows"]                                                       # pixels per wave tile = width of a channel block
+    assert rows in (16, 32) and pl["grid_y"] == 1 and pl["grid_z"] == 1 and pl["grid_x"] >= 1, name
     if z > 1:
         assert pl["ws_bytes"] >= z * M * N * 4, name                       # one fp32 partial tile set per K slice
     tn, nw = pl["tn"], pl["nw"]
     assert tn in (1, 2) and nw in (2, 4, 8) and pl["threads"] == 64 * nw, name
-    assert D.daris_kernel_name(pl["kernel_id"]).endswith(f"t{tn}w{nw}"), name
-    nb = (N + 31) // 32
-    assert nb % tn == 0 and pl["NTn"] * tn == nb and pl["MT"] == (M + 31) // 32, name
-    assert S * (8 if "f32" in D.daris_kernel_name(pl["kernel_id"]) else 16) == pl["Kpad"], name
+    kname = D.daris_kernel_name(pl["kernel_id"])
+    assert kname.endswith(f"t{tn}w{nw}") and kname.startswith("conv_wave16_" if rows == 16 else "conv_wave_"), name
+    nb = (N + rows - 1) // rows
+    assert (nb + tn - 1) // tn == pl["NTn"] and pl["MT"] == (M + rows - 1) // rows, name
+    if rows == 32:
+        assert nb % tn == 0, name
+    assert S * (8 if "f32" in kname else 16) * (32 // rows) == pl["Kpad"], name
+    if rows == 16:
+        assert z == 1, name                                                  # the reason these tiles exist
     # the z slices cover all K steps and none is empty; the nw waves cover their slice
     assert z >= 1 and pl["sz"] * z >= S and pl["sz"] * (z - 1) < S, name
     assert pl["sw"] * nw >= pl["sz"] and pl["sw"] >= 1, name
@@ -399,7 +405,7 @@ def test_code_object_kernels_match_the_argument_structures():
     if not (os.path.exists(co) and os.path.exists(tool)):
         pytest.skip("code object or llvm-readelf not available")
     notes = subprocess.run([tool, "--notes", co], check=True, capture_output=True, text=True).stdout
-    want = {"conv_wave_kernel": 160, "conv_wave_pair_kernel": 324, "splitk_reduce_kernel": 48, "dwconv_kernel": 72,
+    want = {"conv_wave_kernel": 160, "conv_wave_pair_kernel": 324, "conv_wave16_kernel": 160, "conv_wave16_pair_kernel": 324, "splitk_reduce_kernel": 48, "dwconv_kernel": 72,
             "maxpool_kernel": 48, "gavgpool_kernel": 48, "fc_kernel": 56, "ingest_kernel": 28, "egress_kernel": 28,
             "cu_probe_kernel": 12}
     seen = {}
@@ -414,7 +420,7 @@ def test_code_object_kernels_match_the_argument_structures():
         assert size == want[base[0]], (name, size)
         assert scratch == 0 and lds <= 65536, (name, scratch, lds)
         seen[base[0]] = seen.get(base[0], 0) + 1
-    assert seen == {"conv_wave_kernel": 48, "conv_wave_pair_kernel": 36, "splitk_reduce_kernel": 2, "dwconv_kernel": 2,
+    assert seen == {"conv_wave_kernel": 48, "conv_wave_pair_kernel": 36, "conv_wave16_kernel": 12, "conv_wave16_pair_kernel": 12, "splitk_reduce_kernel": 2, "dwconv_kernel": 2,
                     "maxpool_kernel": 2, "gavgpool_kernel": 2, "fc_kernel": 2, "ingest_kernel": 2, "egress_kernel": 2,
                     "cu_probe_kernel": 1}
 
