@@ -405,6 +405,118 @@ def test_saturated_run_with_streams_and_ablation_flags(streams, lib_flags, des_f
         g.close()
 
 
+def _full_size_run(config, hp_jobs):
+    """A configuration at the job count it is specified with, at its nominal periods: the trace replays through the
+    oracle, no HP job misses its deadline, fewer than 2 % of the LP jobs do, none is rejected, and the logits of every
+    20th job of every task match the oracle."""
+    ts = wl.make_taskset(config)
+    ts.n_inputs = 2                                   # the oracle computes one forward pass per (task, input)
+    g = GpuTaskSet(ts)
+    try:
+        afet = g.calibrate(3)
+        res = harness.run_periodic(g, ts.n_jobs)
+        got = D.trace_read_all()
+        _replay_and_check(ts, afet, got)
+        assert res["hp"]["completed"] == hp_jobs and res["hp"]["missed"] == 0, res["hp"]
+        assert res["lp"]["miss_pct"] < 2.0 and res["lp"]["rejected_admission"] == 0 and res["lp"]["rejected_overrun"] == 0, res["lp"]
+        assert res["hp"]["completed"] + res["lp"]["completed"] == ts.n_jobs * len(ts.tasks)
+        want = g.oracle_logits()
+        outs = [l.cpu().numpy() for l in g.logits]
+        worst = 0.0
+        for task, t in enumerate(ts.tasks):
+            for job in range(0, ts.n_jobs, 20):
+                e_max, e_l2 = rel_err(outs[task][job], want[task][job % ts.n_inputs])
+                worst = max(worst, e_max)
+                assert e_max <= TOL[t.dtype] and e_l2 <= TOL[t.dtype], (task, job, e_max, e_l2)
+        print(f"config {config} full size: {res['inferences_per_s']} inf/s over {res['wall_s']} s, HP resp {res['hp']['mean_response_ms']} ms (max {res['hp']['max_response_ms']}), "
+              f"LP resp {res['lp']['mean_response_ms']} ms (max {res['lp']['max_response_ms']}), LP miss {res['lp']['miss_pct']:.2f} %, worst logits error {worst:.2e}")
+    finally:
+        g.close()
+
+
+def test_config3_full_size_periodic_run():
+    """6x ResNet-50 bf16 on 4 x 128 CUs, 1000 jobs per task at 25 / 50 ms (50 s of wall time)."""
+    _full_size_run(3, hp_jobs=2000)
+
+
+def test_config4_full_size_periodic_run():
+    """The mixed 8-task set on 96/96/128/192 CUs, 500 jobs per task at 20-80 ms periods (about 40 s of wall time)."""
+    _full_size_run(4, hp_jobs=1000)
+
+
+def _solo_job_ns(net, dtype, n_cu):
+    """Execution time of one DNN alone on a partition, for sizing periods relative to it."""
+    layers, shp = wl.build_net(net)
+    D.daris_init(0, 0, 0)
+    try:
+        p = D.daris_create_partition(n_cu)
+        dnn, keep = D.make_dnn(layers, wl.make_weights(layers, 1), shp, dtype)
+        t = D.daris_register_task(dnn, 10_000_000, 10_000_000, D.LP)
+        D.daris_calibrate_afet(t, p, 3)
+        return D.daris_get_mret(t, 0)
+    finally:
+        D.daris_shutdown()
+
+
+def test_paper_shaped_set_with_loaded_afet_replays_through_oracle():
+    """The shape of the paper's main experiment (Table II: HP : LP = 1 : 2, every task at the same rate, about 150 % of
+    what the GPU sustains, equal partitions of ceil_even(OS * 256 / N_c) CUs) with the AFET of every stage measured the
+    way Sec. IV-A1 describes it: while the other streams run other tasks.  The trace replays through the oracle from those
+    AFETs, HP jobs are never rejected or migrated, LP jobs are shed by the admission test, logits match."""
+    solo = _solo_job_ns("resnet18", "fp32", 128)
+    n_high, n_low, n_c = 6, 12, 3                                  # per task u is about 0.25: two HP tasks reserve half a context
+    jps = 1.5 * n_c * (1e9 / solo) / (n_high + n_low)            # 150 % of three partitions serving jobs back to back
+    n_cu = D.daris_cu_per_partition(3, 2, 256, n_c)
+    assert n_cu == 128
+    ts = wl.make_paper_taskset("resnet18", n_high, n_low, jps, [n_cu] * n_c, n_jobs=30, n_stages=3)
+    g = GpuTaskSet(ts)
+    try:
+        plain = g.calibrate(2)
+        loaded = g.calibrate(3, loaded=True)
+        assert all(b >= 1 for a in loaded for b in a)
+        assert sum(sum(a) for a in loaded) > 0.9 * sum(sum(a) for a in plain)      # co-runners do not make a stage faster
+        res = harness.run_periodic(g, ts.n_jobs)
+        got = D.trace_read_all()
+        _replay_and_check(ts, loaded, got)
+        assert res["hp"]["rejected_admission"] == 0 and res["hp"]["completed"] == n_high * ts.n_jobs
+        assert not any(r[2] == des.MIGRATE and ts.tasks[r[6]].priority == wl.HP for r in got)
+        assert res["lp"]["rejected_admission"] + res["lp"]["rejected_overrun"] > 0, "the set was meant to overload the GPU"
+        assert res["lp"]["completed"] > 0, "the admission test was meant to let part of the LP load through"
+        worst, n = g.check_logits(got)
+        print(f"paper-shaped set at {jps:.0f} jobs/s per task: {res['inferences_per_s']} inf/s, HP miss {res['hp']['miss_pct']:.1f} %, LP miss {res['lp']['miss_pct']:.1f} %, "
+              f"LP rejected {res['lp']['rejected_admission']}+{res['lp']['rejected_overrun']}, {n} jobs checked, worst logits error {worst:.2e}; "
+              f"AFET solo {[sum(a) for a in plain][:3]} loaded {[sum(a) for a in loaded][:3]} ns")
+    finally:
+        g.close()
+
+
+def test_hp_admission_under_hp_heavy_overload():
+    """Overload + HP admission (Sec. VI-I) on the GPU: two partitions, each home to one HP task whose utilisation is about
+    0.6 and to LP tasks of about 0.3 each.  With the admission test applied to HP jobs too, an HP release that finds its
+    context's booked LP work above what is left is rejected (never migrated, never queued); others are admitted.  The
+    recorded trace replays through the oracle with the same switch, and every completed job's logits match."""
+    solo = _solo_job_ns("resnet18", "fp32", 128)
+    specs = [(wl.HP, 0.6), (wl.HP, 0.6), (wl.LP, 0.3), (wl.LP, 0.3), (wl.LP, 0.3), (wl.LP, 0.3)]
+    tasks = [wl.TaskSpec("resnet18", "fp32", prio, int(solo / u), int(solo / u), 3, wl.tasksets.SEED + 70_000 + (i % 2)) for i, (prio, u) in enumerate(specs)]
+    ts = wl.TaskSet("hp_heavy_overload", tasks, [128, 128], 60, n_inputs=2)
+    g = GpuTaskSet(ts, flags=D.HP_ADMISSION)
+    try:
+        afet = g.calibrate(3)
+        res = harness.run_periodic(g, ts.n_jobs)
+        got = D.trace_read_all()
+        _replay_and_check(ts, afet, got, flags=des.F_HP_ADMISSION)
+        hp_rej = [r for r in got if r[2] == des.REJECT and ts.tasks[r[6]].priority == wl.HP]
+        assert hp_rej, "no HP job was rejected: the load was meant to exceed the HP tasks' contexts"
+        assert res["hp"]["completed"] > 0 and res["hp"]["completed"] + len(hp_rej) == 2 * ts.n_jobs
+        assert not any(r[2] in (des.QUEUED, des.MIGRATE) and ts.tasks[r[6]].priority == wl.HP for r in got)
+        worst, n = g.check_logits(got)
+        print(f"HP admission under overload: HP completed {res['hp']['completed']}, HP rejected {len(hp_rej)} "
+              f"({sum(1 for r in hp_rej if r[9] == des.REJECT_ADMISSION)} by the test), HP miss {res['hp']['miss_pct']:.1f} %, "
+              f"LP completed {res['lp']['completed']}, {n} jobs checked, worst logits error {worst:.2e}")
+    finally:
+        g.close()
+
+
 def test_config2_full_size_periodic_run():
     """The benchmark configuration at its full size (500 jobs per task at 20 / 40 ms periods, about 20 s of wall time):
     trace replays through the oracle, no HP miss, LP misses under 2 %, and every 20th job's logits are checked."""
