@@ -242,6 +242,64 @@ def layer_profile(net, dtype, n_cu, reps=50):
                 t_roof_us=round(sum(r["t_roof_us"] for r in rows), 2), layers=rows)
 
 
+def queue_scaling(net, dtype, n_max=8, jobs_per_task=150, n_stages=3):
+    """Separates the number of concurrently fed hardware queues from the size of their partitions: the same DNN as N
+    tasks on N partitions with one stream each, N = 1..n_max, once with equal DISJOINT masks of 256 / n_max CUs and once
+    with every partition on the full 256-CU mask; saturated closed loop.  Per row: aggregate inferences/s, and per stage
+    the GPU span (first kernel's start stamp to last kernel's end stamp) and the host's share of the wall time."""
+    import workloads as wl
+    rows = []
+    for shape in ("disjoint", "full"):
+        for n in range(1, n_max + 1):
+            n_cu = 256 // n_max if shape == "disjoint" else 256
+            period = 10_000_000
+            tasks = [wl.TaskSpec(net, dtype, wl.LP, period, period, n_stages, wl.tasksets.SEED + 90_000) for _ in range(n)]
+            ts = wl.TaskSet(f"queues_{shape}_{n}", tasks, [n_cu] * n, 8, n_inputs=1)
+            g = GpuTaskSet(ts)
+            try:
+                g.calibrate(2)
+                D.daris_commit()
+                assert sorted(D.daris_get_partition(i) for i in range(n)) == list(range(n))      # one task per partition
+                D.daris_run_closed_loop([20] * n, 0)
+                res = run_saturated(g, jobs_per_task * n, driver_profile=True)
+                pr = res["driver_profile_us_per_stage"]
+                rows.append(dict(masks=shape, queues=n, cus_per_queue=n_cu, inferences_per_s=res["inferences_per_s"],
+                                 per_queue=round(res["inferences_per_s"] / n, 1), gpu_span_us=pr["gpu"],
+                                 stage_wall_us=round(pr["wall_us"] * n / max(pr["stages"], 1), 2)))
+            finally:
+                g.close()
+    return rows
+
+
+def stress_sweep(jobs, rates=(0.5, 0.75, 1.0, 1.5, 2.0, 2.5, 3.0), oversubs=(1.0, 1.5, 2.0, 2.5), migrate_every=100):
+    """Configuration 5: 4 HP ResNet-50 (bf16) + 12 LP MobileNetV2 / ResNet-18 (fp32) tasks on four equal partitions, the
+    release rate scaled from 0.5x to 3x of the nominal 40 / 80 ms periods and the oversubscription level from 1.0 to
+    2.5 (64 / 96 / 128 / 160 CUs per partition), one forced migration per `migrate_every` completed jobs.  One row per
+    point; the sweep of a level stops after the first rate whose LP miss rate exceeds 2 %."""
+    import workloads as wl
+    rows = []
+    for osub in oversubs:
+        for rate in rates:
+            ts = wl.make_taskset(5, n_jobs=jobs, rate_scale=rate, oversub=osub)
+            ts.n_inputs = 1
+            g = GpuTaskSet(ts)
+            try:
+                g.calibrate(2)
+                D.daris_commit()
+                res = run_periodic(g, jobs, migrate_every)
+                pct = response_percentiles(D.trace_read_all(), [t.priority for t in ts.tasks])
+            finally:
+                g.close()
+            rows.append(dict(oversub=osub, cus=ts.partitions[0], rate=rate, offered=round(sum(1e9 / t.period_ns for t in ts.tasks), 1),
+                             served=res["inferences_per_s"], hp_miss=round(res["hp"]["miss_pct"], 2), lp_miss=round(res["lp"]["miss_pct"], 2),
+                             lp_rejected=res["lp"]["rejected_admission"] + res["lp"]["rejected_overrun"],
+                             hp_p99=pct["hp"]["p99_ms"] if pct["hp"] else None, lp_p99=pct["lp"]["p99_ms"] if pct["lp"] else None))
+            print(json.dumps(rows[-1]), flush=True)
+            if rows[-1]["lp_miss"] > 2.0:
+                break
+    return rows
+
+
 def main():
     import workloads as wl
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
@@ -266,7 +324,21 @@ def main():
     ap.add_argument("--dtype", default="fp32", help="--layer-profile and --paper-set: fp32 | bf16")
     ap.add_argument("--ncu", type=int, default=128, help="--layer-profile: partition size")
     ap.add_argument("--table", action="store_true", help="--layer-profile: markdown table instead of JSON")
+    ap.add_argument("--queue-scaling", default="", help="instead of a run: this DNN on 1..8 queues with disjoint 32-CU masks and with full masks (markdown table)")
+    ap.add_argument("--stress-sweep", action="store_true", help="instead of a run: configuration 5 over release rate x oversubscription (--jobs per task and point)")
     a = ap.parse_args()
+    if a.stress_sweep:
+        rows = stress_sweep(a.jobs)
+        print("\n| OS | CUs per partition | rate | offered inf/s | served inf/s | HP miss % | LP miss % | LP rejected | HP p99 ms | LP p99 ms |\n|---|---|---|---|---|---|---|---|---|---|")
+        for r in rows:
+            print(f"| {r['oversub']} | {r['cus']} | {r['rate']} | {r['offered']} | {r['served']} | {r['hp_miss']} | {r['lp_miss']} | {r['lp_rejected']} | {r['hp_p99']} | {r['lp_p99']} |")
+        return
+    if a.queue_scaling:
+        rows = queue_scaling(a.queue_scaling, a.dtype)
+        print("| masks | queues | CUs per queue | inferences/s | per queue | GPU span per stage us | wall per stage us |\n|---|---|---|---|---|---|---|")
+        for r in rows:
+            print(f"| {r['masks']} | {r['queues']} | {r['cus_per_queue']} | {r['inferences_per_s']} | {r['per_queue']} | {r['gpu_span_us']} | {r['stage_wall_us']} |")
+        return
     if a.layer_profile:
         r = layer_profile(a.layer_profile, a.dtype, a.ncu)
         if not a.table:
