@@ -34,7 +34,7 @@ WORKLOADS = {
     3: "6x ResNet-50 (2 HP + 4 LP), batch 1, bf16 storage / fp32 accumulate, 3x224x224, 4 stages/DNN, 4 partitions x 128 CUs (2x oversubscribed), closed-loop releases",
     4: "mixed 8 tasks: ResNet-18 x2 (HP), ResNet-50 x2, VGG-16 x2, MobileNetV2 x2 (LP), batch 1, fp32, 3x224x224, 3 stages/DNN, partitions 96/96/128/192 CUs (2x oversubscribed), closed-loop releases",
 }
-TRAFFIC_PROFILE = {2: "conv_kernels_resnet18_hbm_traffic.md", 3: "bench_config3_hbm_traffic.md", 4: "bench_config4_hbm_traffic.md"}
+TRAFFIC_PROFILE = {2: "bench_config2_hbm_traffic.md", 3: "bench_config3_hbm_traffic.md", 4: "bench_config4_hbm_traffic.md"}
 
 
 def read_traffic(config, kernel):
@@ -88,7 +88,7 @@ def kernel_roofline(name, launches, ms, flops):
     arithmetic type; memory-bound kernels against HBM (the caller fills in the FC kernel's rate: its bytes are the
     weights it streams, one element per MAC)."""
     t_s = max(ms, 1e-9) * 1e-3
-    if name.startswith("conv_wave_"):
+    if name.startswith("conv_wave"):
         dt = "bf16" if "_bf16_" in name else "f32"
         achieved, peak, unit, bound = flops / t_s / 1e12, PEAK_MFMA_TFLOPS[dt], "TFLOP/s", "mfma"
     else:
@@ -183,7 +183,7 @@ def measure(config, args, full):
                 if e["achieved"] is not None:
                     per_kernel[k].update(achieved=e["achieved"], unit=e["unit"], frac=e["frac"])
             roofline["all_sampled_kernels"] = per_kernel
-            conv = [(k, v) for k, v in timing.items() if k.startswith("conv_wave_")]
+            conv = [(k, v) for k, v in timing.items() if k.startswith("conv_wave")]
             if conv:
                 dt = "bf16" if "_bf16_" in conv[0][0] else "f32"
                 cf, cms = sum(v[2] for _, v in conv), sum(v[1] for _, v in conv)

@@ -326,9 +326,11 @@ def main():
     ap.add_argument("--table", action="store_true", help="--layer-profile: markdown table instead of JSON")
     ap.add_argument("--queue-scaling", default="", help="instead of a run: this DNN on 1..8 queues with disjoint 32-CU masks and with full masks (markdown table)")
     ap.add_argument("--stress-sweep", action="store_true", help="instead of a run: configuration 5 over release rate x oversubscription (--jobs per task and point)")
+    ap.add_argument("--rates", default="0.5,0.75,1,1.5,2,2.5,3", help="--stress-sweep: release-rate scales (the configuration's range is 0.5 to 3; larger values look for the knee)")
+    ap.add_argument("--oversubs", default="1,1.5,2,2.5", help="--stress-sweep: oversubscription levels")
     a = ap.parse_args()
     if a.stress_sweep:
-        rows = stress_sweep(a.jobs)
+        rows = stress_sweep(a.jobs, tuple(float(v) for v in a.rates.split(",")), tuple(float(v) for v in a.oversubs.split(",")))
         print("\n| OS | CUs per partition | rate | offered inf/s | served inf/s | HP miss % | LP miss % | LP rejected | HP p99 ms | LP p99 ms |\n|---|---|---|---|---|---|---|---|---|---|")
         for r in rows:
             print(f"| {r['oversub']} | {r['cus']} | {r['rate']} | {r['offered']} | {r['served']} | {r['hp_miss']} | {r['lp_miss']} | {r['lp_rejected']} | {r['hp_p99']} | {r['lp_p99']} |")
