@@ -65,10 +65,12 @@ enum {
                                  first convolution separately instead of in one two-problem launch (A/B and tests)  */
   DARIS_NO_FUSED_INGEST = 1024, /* ... and convert the input layout in a launch of its own instead of inside the first
                                  convolution                                                                     */
-  DARIS_NO_STAGED_ROWS = 2048 /* ... and feed every convolution's pixel operand straight from global memory to registers
+  DARIS_NO_STAGED_ROWS = 2048, /* ... and feed every convolution's pixel operand straight from global memory to registers
                                  instead of fetching whole 64-byte rows through LDS where the shape allows (A/B)   */
-  ,DARIS_NO_SMALL_TILES = 4096 /* ... and keep 32-pixel tiles with a K split across workgroups (and its reduction launch)
+  DARIS_NO_SMALL_TILES = 4096, /* ... and keep 32-pixel tiles with a K split across workgroups (and its reduction launch)
                                  for deep layers of few pixels, instead of 16-pixel tiles (A/B)                  */
+  DARIS_NO_FUSED_DW = 8192     /* ... and run a 3x3 depthwise convolution in a launch of its own instead of computing it
+                                 inside the 1x1 convolution that is its only reader (A/B and tests)              */
 };
 
 enum { DARIS_LP = 0, DARIS_HP = 1 };

@@ -13,7 +13,7 @@ LIB_PATH = os.environ.get("DARIS_LIB") or os.path.join(_HERE, "libdaris.so")   #
 
 OK, EINVAL, ENOMEM, EHIP, ESTATE, ERANGE = 0, -1, -2, -3, -4, -5
 VIRTUAL_TIME, NO_DEVICE, NO_LAST, NO_PRIOR, NO_FIXED, HP_ADMISSION, KEEP_ACTIVATIONS, WAVE_PRIORITY, SHARED_QUEUE = 1, 2, 4, 8, 16, 32, 64, 128, 256
-NO_PAIR, NO_FUSED_INGEST, NO_STAGED_ROWS, NO_SMALL_TILES = 512, 1024, 2048, 4096
+NO_PAIR, NO_FUSED_INGEST, NO_STAGED_ROWS, NO_SMALL_TILES, NO_FUSED_DW = 512, 1024, 2048, 4096, 8192
 LP, HP = 0, 1
 FP32, BF16 = 0, 1
 ACCEPTED, MIGRATED, REJECT_ADMISSION, REJECT_OVERRUN, QUEUED = 1, 2, 3, 4, 5

@@ -262,7 +262,9 @@ std::string encode_network(TaskRt& T, const std::vector<void*>& slots, float* ws
     double flops = 0;
     switch (L.d.op) {
       case DARIS_OP_CONV:
-        if (L.depthwise) {
+        if (L.depthwise && L.fused_dw) {
+          ok = true;  // computed inside the next layer's launch
+        } else if (L.depthwise) {
           DwArgs a;
           a.x = x; a.w = L.w_dev; a.bias = L.b_dev; a.y = y;
           a.H = in.H; a.W = in.W; a.C = in.Cs; a.Ho = L.out.H; a.Wo = L.out.W;
@@ -273,7 +275,16 @@ std::string encode_network(TaskRt& T, const std::vector<void*>& slots, float* ws
         } else {
           const ConvArgs a = conv_args(T, l, y, slots, ws);
           flops = 2.0 * (double)L.macs;
-          if (L.pair_with >= 0) {
+          if (L.fused_dw) {
+            LayerPlan& O = net.layers[L.pair_with];  // the depthwise layer: this launch reads ITS input
+            const TensorInfo& din = net.tensor(O.in_t);
+            ConvArgs b = a;
+            b.x = slots[din.slot];
+            DwFusedArgs d;
+            d.w = O.w_dev; d.bias = O.b_dev; d.H = din.H; d.W = din.W; d.stride = O.d.stride; d.act = O.d.act;
+            flops += 2.0 * (double)O.macs;
+            ok = encode_conv_dw(g_kt, L.cp, b, d, bf16, &ks);
+          } else if (L.pair_with >= 0) {
             LayerPlan& O = net.layers[L.pair_with];
             const ConvArgs b = conv_args(T, L.pair_with, slots[O.out.slot], slots, ws);
             flops += 2.0 * (double)O.macs;
@@ -925,7 +936,7 @@ daris_task daris_register_task(const daris_dnn* dnn, int64_t period_ns, int64_t 
   if (priority != DARIS_HP && priority != DARIS_LP) return fail(DARIS_EINVAL, "priority must be DARIS_HP or DARIS_LP");
   if (G->tasks.size() >= 65535) return fail(DARIS_ERANGE, "too many tasks");
   std::unique_ptr<TaskRt> T(new TaskRt());
-  std::string err = build_plan(*dnn, G->flags & DARIS_KEEP_ACTIVATIONS, !(G->flags & DARIS_NO_PAIR), !(G->flags & DARIS_NO_FUSED_INGEST), !(G->flags & DARIS_NO_STAGED_ROWS), !(G->flags & DARIS_NO_SMALL_TILES), &T->net);
+  std::string err = build_plan(*dnn, G->flags & DARIS_KEEP_ACTIVATIONS, !(G->flags & DARIS_NO_PAIR), !(G->flags & DARIS_NO_FUSED_INGEST), !(G->flags & DARIS_NO_STAGED_ROWS), !(G->flags & DARIS_NO_SMALL_TILES), !(G->flags & DARIS_NO_FUSED_DW), &T->net);
   if (!err.empty()) return fail(DARIS_EINVAL, "%s", err.c_str());
   if (!G->nodev) {
     NetPlan& net = T->net;

@@ -43,6 +43,16 @@ struct ConvArgs {
   int wave_prio;          // 1: the waves raise their issue priority (stages of high-priority tasks on shared CUs)
 };
 
+// The 3x3 depthwise convolution (pad 1) that conv_wave_dw_kernel computes on the fly in front of a 1x1 convolution; the
+// ConvArgs beside it describe that 1x1 convolution, except that ConvArgs::x is the DEPTHWISE layer's input tensor
+// [H][W][Cin] (ConvArgs::H, W stay the 1x1 convolution's own input size = the depthwise layer's output size).
+struct DwFusedArgs {
+  const void* w = nullptr;      // [9][C]
+  const float* bias = nullptr;  // [C]
+  int H = 0, W = 0;             // the depthwise layer's input size
+  int stride = 1, act = 0;
+};
+
 struct DwArgs {
   const void* x;      // [H][W][C]
   const void* w;      // [k*k][C]
@@ -113,6 +123,7 @@ struct KernelTable {
   const AqlKernel* pair[2][6][3] = {};  // gather modes 0, 1, 3
   const AqlKernel* conv16[2][6] = {};   // 16-row tiles: [bf16][(tn - 1) * 3 + log2(nw) - 1]
   const AqlKernel* pair16[2][6] = {};
+  const AqlKernel* convdw[2][6] = {};   // 1x1 convolution with a fused depthwise producer (fp32: tn = 1 only)
   const AqlKernel *reduce[2] = {}, *dwconv[2] = {}, *maxpool[2] = {}, *gavgpool[2] = {}, *fc[2] = {}, *ingest[2] = {}, *egress[2] = {};
   const AqlKernel* cu_probe = nullptr;
   // "" or the name of the first kernel that is missing or whose argument size is not what this header declares
@@ -124,6 +135,15 @@ bool encode_conv(const KernelTable& kt, const ConvPlan& pl, const ConvArgs& a, i
 // Two independent convolutions in one launch: pl0/a0 as planned by plan_conv, pl1/a1 by plan_conv_like(pl0, ...).
 bool encode_conv_pair(const KernelTable& kt, const ConvPlan& pl0, const ConvArgs& a0, const ConvPlan& pl1, const ConvArgs& a1, int bf16,
                       std::vector<KernelLaunch>* out);
+// A depthwise 3x3 convolution (pad 1, stride d.stride) followed by the 1x1 convolution pl/a in one launch.  a.x must be the
+// depthwise layer's input; the plan must be a staged 32-row one (conv_rows_staged shape, step_align 2).
+bool encode_conv_dw(const KernelTable& kt, const ConvPlan& pl, const ConvArgs& a, const DwFusedArgs& d, int bf16, std::vector<KernelLaunch>* out);
+// Whether a depthwise 3x3 layer in front of the 1x1 convolution planned as pl should be computed inside that convolution's
+// launch.  Measured on MobileNetV2's blocks: the producer re-reads the depthwise input up to nine times through one CU's
+// vector cache and pays a memory latency per chunk of 64 bytes of channels, so it wins only where the convolution has enough
+// workgroups to fill a partition and a single channel block (no repetition per block, few chunks per wave); elsewhere the
+// separate, fully parallel depthwise launch is faster (by 1.3 to 5 us per block).
+bool conv_dw_fusable(const ConvPlan& pl, int bf16);
 bool encode_dwconv(const KernelTable& kt, const DwArgs& a, int bf16, std::vector<KernelLaunch>* out);
 bool encode_maxpool(const KernelTable& kt, const PoolArgs& a, int bf16, std::vector<KernelLaunch>* out);
 bool encode_gavgpool(const KernelTable& kt, const PoolArgs& a, int bf16, std::vector<KernelLaunch>* out);

@@ -129,11 +129,14 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 // which splitk_reduce_kernel adds in z order (a device-wide fence per workgroup for an in-kernel reduction was
 // measured to cost several times the extra launch).
 template <bool BF16, int TN, int NW, int MODE>
-__device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L) {
+__device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L, const DwFusedArgs& dwf) {
   // MODE 0: Cin a multiple of KS; 1: any Cin; 2: the network input itself, fp32 [C][H][W]; 3: a pixel's channels are whole
-  // 64-byte rows (Cin * ES a multiple of 64): the pixel operand is fetched in coalesced rows and transposed through LDS
+  // 64-byte rows (Cin * ES a multiple of 64): the pixel operand is fetched in coalesced rows and transposed through LDS;
+  // 4: like 3 for a 1x1 convolution whose input is the output of a 3x3 depthwise convolution that is never stored: the
+  // rows are computed here from the depthwise layer's input (p.x) and weights (dwf)
   constexpr bool ALIGNED = MODE == 0;
-  constexpr bool STAGED = MODE == 3;
+  constexpr bool STAGED = MODE == 3 || MODE == 4;
+  constexpr bool DWF = MODE == 4;
   constexpr int ES = BF16 ? 2 : 4;
   constexpr int VEC = 16 / ES;
   constexpr int KS = 2 * VEC;
@@ -351,45 +354,6 @@ __device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L) {
     // of weights are in flight.  The plan makes every wave's K slice a whole number of chunks.
     uint4* const st = reinterpret_cast<uint4*>(red) + wave * STAGE_V;
     const int piece = lane & 3, prow = lane >> 2;
-    int siy0[2], six0[2];
-    bool sok[2];
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int mj = m0 + 16 * j + prow;
-      sok[j] = mj < p.M;
-      const int y = fast_div(mj, p.mg_wo), x = mj - y * p.Wo;
-      siy0[j] = y * p.stride - p.pad;
-      six0[j] = x * p.stride - p.pad;
-    }
-    const unsigned char* gp[2];
-    bool gv[2];
-    auto enter_rows = [&]() {  // (ky, kx, ci) are wave-uniform
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int iy = siy0[j] + ky, ix = six0[j] + kx;
-        gv[j] = sok[j] && ky < p.kh && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
-        gp[j] = xb + ((size_t)(gv[j] ? iy * p.W + ix : 0) * p.Cin + ci) * ES + piece * 16;  // always a valid address
-      }
-    };
-    enter_rows();
-    uint4 gr[2][2];
-    bool gok[2][2];
-    auto load_rows = [&](int slot) {  // the chunk at (tap, ci) into register slot `slot`, then on to the next chunk
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        gr[slot][j] = *(const uint4*)gp[j];
-        gok[slot][j] = gv[j];
-      }
-      ci += 2 * KS;
-      if (ci >= p.Cin) {  // wave-uniform
-        ci -= p.Cin;
-        if (++kx == p.kw) { kx = 0; ++ky; }
-        enter_rows();
-      } else {
-#pragma unroll
-        for (int j = 0; j < 2; ++j) gp[j] += 64;
-      }
-    };
     auto load_w = [&](int d) {
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
@@ -397,11 +361,8 @@ __device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L) {
         wptr[j] += 1024;
       }
     };
-    // one chunk: rows of register slot `slot` -> LDS -> MFMA order; weights of pipeline slots d0, d0 + 1
-    auto chunk = [&](int slot, int d0) {
-#pragma unroll
-      for (int j = 0; j < 2; ++j) st[(16 * j + prow) * 5 + piece] = keep_if(gok[slot][j], gr[slot][j]);
-      load_rows(slot);  // two chunks ahead (past the end of the slice: valid memory, never used)
+    // rows in the wave's buffer -> MFMA order -> two K steps against the weights of pipeline slots d0, d0 + 1
+    auto exchange_and_mma = [&](int d0) {
       // lanes exchange data through the wave's buffer: order the accesses of the whole wave, not only of each lane
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
@@ -418,17 +379,136 @@ __device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L) {
         load_w(d0 + s2);
       }
     };
-    load_rows(0);
-    load_rows(1);
-#pragma unroll
-    for (int d = 0; d < D; ++d) load_w(d);
     const int nchunks = nsteps >> 1;
-    int c = 0;
-    for (; c + 2 <= nchunks; c += 2) {
-      chunk(0, 0);
-      chunk(1, 2);
+    if constexpr (DWF) {
+      // The 1x1 convolution's input row of pixel (y, x), channels c..c+VEC-1, is the depthwise layer's output there:
+      // act(bias[c] + sum over the 3x3 taps inside the image, in (ky, kx) order, of in[y*stride-1+ky][x*stride-1+kx][c] * w[tap][c]),
+      // accumulated with fused multiply-adds in exactly the order of dwconv_kernel, then rounded to the element type as a
+      // stored tensor would be.  A lane computes the 16-byte piece it would otherwise have loaded.
+      const unsigned char* dww = (const unsigned char*)dwf.w;
+      int poff[2][9];     // element offset of each tap's input pixel (0 where the tap is outside: the value is not used)
+      unsigned vmask[2];  // bit t: tap t of this lane's pixel lies inside the image
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int mj = m0 + 16 * j + prow;
+        const bool okj = mj < p.M;
+        const int y = fast_div(mj, p.mg_wo), x = mj - y * p.Wo;
+        vmask[j] = 0u;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+          const int iy = y * dwf.stride - 1 + t / 3, ix = x * dwf.stride - 1 + t % 3;
+          const bool v = okj && (unsigned)iy < (unsigned)dwf.H && (unsigned)ix < (unsigned)dwf.W;
+          poff[j][t] = v ? (iy * dwf.W + ix) * p.Cin : 0;
+          vmask[j] |= v ? (1u << t) : 0u;
+        }
+      }
+      int cch = sbeg * KS;  // first channel of the wave's next chunk (wave-uniform)
+      uint4 xv[2][9], wv[9];
+      float4 bv[VEC / 4];
+      auto dw_issue = [&]() {  // loads of the chunk at cch; past the end of the slice the last chunk of the tensor is read again (never used)
+        const int c = min(cch, p.Cin - 2 * KS) + piece * VEC;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) wv[t] = *(const uint4*)(dww + ((size_t)t * p.Cin + c) * ES);
+#pragma unroll
+        for (int q = 0; q < VEC / 4; ++q) bv[q] = *(const float4*)(dwf.bias + c + 4 * q);
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int t = 0; t < 9; ++t) xv[j][t] = *(const uint4*)(xb + ((size_t)poff[j][t] + c) * ES);
+        cch += 2 * KS;
+      };
+      auto dw_value = [&](int j) -> uint4 {
+        float acc[VEC];
+#pragma unroll
+        for (int q = 0; q < VEC / 4; ++q) {
+          acc[4 * q] = bv[q].x; acc[4 * q + 1] = bv[q].y; acc[4 * q + 2] = bv[q].z; acc[4 * q + 3] = bv[q].w;
+        }
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+          float xf[VEC], wf[VEC];
+          unpack<BF16>(xv[j][t], xf);
+          unpack<BF16>(wv[t], wf);
+          const bool v = (vmask[j] >> t) & 1u;
+#pragma unroll
+          for (int i = 0; i < VEC; ++i) acc[i] = v ? fmaf(xf[i], wf[i], acc[i]) : acc[i];
+        }
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] = apply_act(acc[i], dwf.act);
+        return pack<BF16>(acc);
+      };
+      auto chunk_dw = [&](int d0) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) st[(16 * j + prow) * 5 + piece] = dw_value(j);
+        dw_issue();  // the next chunk's operands travel while this one goes through the matrix pipe
+        exchange_and_mma(d0);
+      };
+      dw_issue();
+#pragma unroll
+      for (int d = 0; d < D; ++d) load_w(d);
+      int c = 0;
+      for (; c + 2 <= nchunks; c += 2) {
+        chunk_dw(0);
+        chunk_dw(2);
+      }
+      if (c < nchunks) chunk_dw(0);
+    } else {
+      int siy0[2], six0[2];
+      bool sok[2];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int mj = m0 + 16 * j + prow;
+        sok[j] = mj < p.M;
+        const int y = fast_div(mj, p.mg_wo), x = mj - y * p.Wo;
+        siy0[j] = y * p.stride - p.pad;
+        six0[j] = x * p.stride - p.pad;
+      }
+      const unsigned char* gp[2];
+      bool gv[2];
+      auto enter_rows = [&]() {  // (ky, kx, ci) are wave-uniform
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int iy = siy0[j] + ky, ix = six0[j] + kx;
+          gv[j] = sok[j] && ky < p.kh && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W;
+          gp[j] = xb + ((size_t)(gv[j] ? iy * p.W + ix : 0) * p.Cin + ci) * ES + piece * 16;  // always a valid address
+        }
+      };
+      enter_rows();
+      uint4 gr[2][2];
+      bool gok[2][2];
+      auto load_rows = [&](int slot) {  // the chunk at (tap, ci) into register slot `slot`, then on to the next chunk
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          gr[slot][j] = *(const uint4*)gp[j];
+          gok[slot][j] = gv[j];
+        }
+        ci += 2 * KS;
+        if (ci >= p.Cin) {  // wave-uniform
+          ci -= p.Cin;
+          if (++kx == p.kw) { kx = 0; ++ky; }
+          enter_rows();
+        } else {
+#pragma unroll
+          for (int j = 0; j < 2; ++j) gp[j] += 64;
+        }
+      };
+      // one chunk: rows of register slot `slot` -> LDS -> MFMA order; weights of pipeline slots d0, d0 + 1
+      auto chunk = [&](int slot, int d0) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) st[(16 * j + prow) * 5 + piece] = keep_if(gok[slot][j], gr[slot][j]);
+        load_rows(slot);  // two chunks ahead (past the end of the slice: valid memory, never used)
+        exchange_and_mma(d0);
+      };
+      load_rows(0);
+      load_rows(1);
+#pragma unroll
+      for (int d = 0; d < D; ++d) load_w(d);
+      int c = 0;
+      for (; c + 2 <= nchunks; c += 2) {
+        chunk(0, 0);
+        chunk(1, 2);
+      }
+      if (c < nchunks) chunk(0, 0);
     }
-    if (c < nchunks) chunk(0, 0);
     __syncthreads();  // the partial tiles below reuse the LDS of every wave's staging buffer
   }
 
@@ -492,17 +572,23 @@ __device__ __forceinline__ void conv_wave_body(const ConvArgs& p, const int L) {
 
 template <bool BF16, int TN, int NW, int MODE>
 __global__ __launch_bounds__(NW * 64) void conv_wave_kernel(const ConvArgs p) {
-  conv_wave_body<BF16, TN, NW, MODE>(p, (int)blockIdx.x);
+  conv_wave_body<BF16, TN, NW, MODE>(p, (int)blockIdx.x, DwFusedArgs());
 }
 
+// A 1x1 convolution with the 3x3 depthwise convolution in front of it computed on the fly (gather mode 4): one launch for
+// the second and third layer of an inverted residual block, and the depthwise output never touches memory.
+template <bool BF16, int TN, int NW>
+__global__ __launch_bounds__(NW * 64) void conv_wave_dw_kernel(const ConvArgs p, const DwFusedArgs d) {
+  conv_wave_body<BF16, TN, NW, 4>(p, (int)blockIdx.x, d);
+}
 // Two independent convolutions of the same kernel variant in one launch (a residual block's first convolution and
 // the 1x1 convolution of its shortcut read the same tensor): workgroups [0, n0) work on p0, the rest on p1.  n0 is
 // a multiple of 8, so the workgroup -> XCD relation of each problem is the one its plan assumed.
 template <bool BF16, int TN, int NW, int MODE>
 __global__ __launch_bounds__(NW * 64) void conv_wave_pair_kernel(const ConvArgs p0, const ConvArgs p1, const int n0) {
   const int L = (int)blockIdx.x;
-  if (L < n0) conv_wave_body<BF16, TN, NW, MODE>(p0, L);
-  else conv_wave_body<BF16, TN, NW, MODE>(p1, L - n0);
+  if (L < n0) conv_wave_body<BF16, TN, NW, MODE>(p0, L, DwFusedArgs());
+  else conv_wave_body<BF16, TN, NW, MODE>(p1, L - n0, DwFusedArgs());
 }
 
 // ---- 16-row wave tiles for deep, skinny layers -----------------------------------------------------------------------
@@ -905,6 +991,8 @@ __global__ __launch_bounds__(64) void cu_probe_kernel(uint32_t* out, int spin) {
   template __global__ void conv_wave16_pair_kernel<B, TB_, 2>(const ConvArgs, const ConvArgs, const int); \
   template __global__ void conv_wave16_pair_kernel<B, TB_, 4>(const ConvArgs, const ConvArgs, const int); \
   template __global__ void conv_wave16_pair_kernel<B, TB_, 8>(const ConvArgs, const ConvArgs, const int);
+#define DARIS_INST_CONVDW(B, TN_, NW_)                                                             \
+  template __global__ void conv_wave_dw_kernel<B, TN_, NW_>(const ConvArgs, const DwFusedArgs);
 #define DARIS_INST_ALL(B)                                                                          \
   DARIS_INST_CONV(B, 1, 2) DARIS_INST_CONV(B, 1, 4) DARIS_INST_CONV(B, 1, 8)                        \
   DARIS_INST_CONV(B, 2, 2) DARIS_INST_CONV(B, 2, 4) DARIS_INST_CONV(B, 2, 8)                        \
@@ -918,6 +1006,11 @@ __global__ __launch_bounds__(64) void cu_probe_kernel(uint32_t* out, int spin) {
   template __global__ void egress_kernel<B>(const void*, float*, int, int, int);
 DARIS_INST_ALL(false)
 DARIS_INST_ALL(true)
+// Fused depthwise variants.  fp32 tiles of 64 channels are never staged, so they have none; bf16 plans never use 8 waves per
+// workgroup, and those variants would need scratch memory, which the dispatch path does not provide.
+DARIS_INST_CONVDW(false, 1, 2) DARIS_INST_CONVDW(false, 1, 4) DARIS_INST_CONVDW(false, 1, 8)
+DARIS_INST_CONVDW(true, 1, 2) DARIS_INST_CONVDW(true, 1, 4) DARIS_INST_CONVDW(true, 2, 2) DARIS_INST_CONVDW(true, 2, 4)
+#undef DARIS_INST_CONVDW
 #undef DARIS_INST_ALL
 #undef DARIS_INST_CONV
 #undef DARIS_INST_CONV16

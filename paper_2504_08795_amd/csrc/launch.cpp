@@ -197,7 +197,12 @@ struct PairArgs {  // conv_wave_pair_kernel(p0, p1, n0)
   ConvArgs p0, p1;
   int n0;
 };
+struct ConvDwArgs {  // conv_wave_dw_kernel(p, d)
+  ConvArgs p;
+  DwFusedArgs d;
+};
 constexpr uint32_t kIngestBytes = 28, kProbeBytes = 12, kPairBytes = 2 * sizeof(ConvArgs) + 4;
+static_assert(sizeof(DwFusedArgs) == 32 && sizeof(ConvDwArgs) == 192 && offsetof(ConvDwArgs, d) == sizeof(ConvArgs), "fused depthwise arguments");
 static_assert(sizeof(ConvArgs) == 160 && sizeof(DwArgs) == 72 && sizeof(PoolArgs) == 48 && sizeof(FcArgs) == 56 && sizeof(ReduceArgs) == 48,
               "argument structures must match what the kernels were compiled for");
 static_assert(offsetof(ConvArgs, x) == kConvInputOffset && offsetof(FcArgs, y) == kFcOutputOffset && offsetof(IngestArgs, x) == kIngestInputOffset &&
@@ -240,6 +245,8 @@ std::string KernelTable::resolve(const AqlRuntime& rt) {
     for (int v = 0; v < 6; ++v) {
       conv16[b][v] = get("daris::conv_wave16_kernel<" + B + ", " + std::to_string(tn_[v]) + ", " + std::to_string(nw_[v]) + ">", sizeof(ConvArgs));
       pair16[b][v] = get("daris::conv_wave16_pair_kernel<" + B + ", " + std::to_string(tn_[v]) + ", " + std::to_string(nw_[v]) + ">", kPairBytes);
+      if (b ? nw_[v] != 8 : tn_[v] == 1)
+        convdw[b][v] = get("daris::conv_wave_dw_kernel<" + B + ", " + std::to_string(tn_[v]) + ", " + std::to_string(nw_[v]) + ">", sizeof(ConvDwArgs));
     }
     reduce[b] = get("daris::splitk_reduce_kernel<" + B + ">", sizeof(ReduceArgs));
     dwconv[b] = get("daris::dwconv_kernel<" + B + ">", sizeof(DwArgs));
@@ -280,6 +287,31 @@ bool encode_conv(const KernelTable& kt, const ConvPlan& pl, const ConvArgs& a, i
   if (mode == 2 && (a.Cin != (bf16 ? 8 : 4) || a.c_real > 4)) return false;
   if (pl.splitk > 1 && !a.ws) return false;
   if (!push(out, kt.conv[bf16][variant][mode], pl.kernel, pl.grid_x, (uint32_t)pl.threads, &a, sizeof(a))) return false;
+  return push_reduce(kt, pl, a, bf16, out);
+}
+
+bool conv_dw_fusable(const ConvPlan& pl, int bf16) {
+  if (pl.rows != 32 || pl.step_align != 2 || (!bf16 && pl.tn != 1) || (bf16 && pl.nw == 8)) return false;  // no such kernel variant
+  return pl.MT >= 96 && pl.NTn == 1;
+}
+
+bool encode_conv_dw(const KernelTable& kt, const ConvPlan& pl, const ConvArgs& a, const DwFusedArgs& d, int bf16, std::vector<KernelLaunch>* out) {
+  const int variant = pl.kernel - (bf16 ? K_CONVW_BF16_T1W2 : K_CONVW_F32_T1W2);
+  if (pl.rows != 32 || variant < 0 || variant >= 6 || pl.threads != 64 * pl.nw || !conv_dw_fusable(pl, bf16)) return false;
+  const AqlKernel* kernel = kt.convdw[bf16][variant];
+  if (!kernel) return false;
+  // what the kernel's producer assumes: a 1x1 / stride 1 / unpadded convolution over whole 64-byte rows, K cut in chunks of two steps,
+  // a depthwise input that maps onto the convolution's pixels, and offsets that fit 32 bits
+  if (a.kh != 1 || a.kw != 1 || a.stride != 1 || a.pad != 0 || a.c_real > 0 || a.Kpad != a.Cin || a.H != a.Ho || a.W != a.Wo) return false;
+  if (!conv_rows_staged(a.Cin, bf16) || pl.step_align != 2 || pl.S % 2 || pl.sz % 2 || pl.sw % 2 || a.Cin < (bf16 ? 32 : 16)) return false;
+  if (!d.w || !d.bias || (d.stride != 1 && d.stride != 2) || (d.H + 2 - 3) / d.stride + 1 != a.H || (d.W + 2 - 3) / d.stride + 1 != a.W) return false;
+  if ((uint64_t)d.H * (uint64_t)d.W * (uint64_t)a.Cin >= (1ull << 31)) return false;
+  if (pl.splitk > 1 && !a.ws) return false;
+  ConvDwArgs args;
+  std::memset(&args, 0, sizeof(args));
+  args.p = a;
+  args.d = d;
+  if (!push(out, kernel, pl.kernel, pl.grid_x, (uint32_t)pl.threads, &args, sizeof(args))) return false;
   return push_reduce(kt, pl, a, bf16, out);
 }
 

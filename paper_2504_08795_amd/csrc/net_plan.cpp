@@ -17,7 +17,8 @@ uint16_t host_f32_to_bf16(float f) {
   return (uint16_t)(u >> 16);
 }
 
-std::string build_plan(const daris_dnn& dnn, bool keep_activations, bool pair_launches, bool fuse_ingest, bool staged_rows, bool small_tiles, NetPlan* out) {
+std::string build_plan(const daris_dnn& dnn, bool keep_activations, bool pair_launches, bool fuse_ingest, bool staged_rows, bool small_tiles, bool fuse_dw,
+                       NetPlan* out) {
   NetPlan& net = *out;
   net = NetPlan();
   if (dnn.n_layers < 1 || !dnn.layers) return "DNN has no layers";
@@ -128,6 +129,28 @@ std::string build_plan(const daris_dnn& dnn, bool keep_activations, bool pair_la
     A.pair_with = l + 1;
     B.pair_with = l;
     B.pair_lead = true;
+    ++l;
+  }
+  // depthwise 3x3 + the 1x1 convolution that alone reads it: one launch, the depthwise output is never stored
+  for (int l = 0; l + 1 < n && fuse_dw && staged_rows && !keep_activations; ++l) {
+    LayerPlan& A = net.layers[l];
+    LayerPlan& B = net.layers[l + 1];
+    if (A.d.op != DARIS_OP_CONV || !A.depthwise || A.d.k != 3 || A.d.pad != 1 || (A.d.stride != 1 && A.d.stride != 2)) continue;
+    if (B.d.op != DARIS_OP_CONV || B.depthwise || B.d.k != 1 || B.d.stride != 1 || B.d.pad != 0 || B.in_t != l + 1 || B.pair_with >= 0) continue;
+    bool only_reader = true;
+    for (int q = l + 2; q < n; ++q)
+      if (net.layers[q].in_t == l + 1 || net.layers[q].res_t == l + 1) only_reader = false;
+    if (!only_reader || !conv_rows_staged(A.out.Cs, net.bf16)) continue;
+    ConvPlan cp = B.cp;
+    if (cp.rows != 32) cp = plan_conv(B.out.H * B.out.W, B.out.Cs, B.Kpad, net.bf16, 2, 0);  // the fused producer exists for 32-pixel tiles
+    if (!conv_dw_fusable(cp, net.bf16)) continue;  // the separate launch is faster (or no such kernel variant)
+    B.cp = cp;
+    B.kernel_id = cp.kernel;
+    net.ws_bytes = std::max(net.ws_bytes, cp.ws_bytes);
+    A.pair_with = l + 1;
+    B.pair_with = l;
+    B.pair_lead = true;
+    A.fused_dw = B.fused_dw = true;
     ++l;
   }
   // Layer 0 can gather straight from the caller's input when that is its only reader and one filter tap is exactly

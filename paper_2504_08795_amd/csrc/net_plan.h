@@ -28,6 +28,10 @@ struct LayerPlan {
   // at the later layer (pair_lead), the earlier one issues nothing; the lighter of the two is planned like the heavier.
   int pair_with = -1;
   bool pair_lead = false;
+  // A 3x3 depthwise convolution whose only reader is the 1x1 convolution right after it is computed inside that
+  // convolution's launch and never stored: the two layers are linked like a launch pair (the depthwise layer issues
+  // nothing, the 1x1 convolution leads) and both carry this mark.
+  bool fused_dw = false;
   int32_t kernel_id = K_NONE;
   void* w_dev = nullptr;
   float* b_dev = nullptr;
@@ -52,8 +56,10 @@ struct NetPlan {
 // Builds shapes, MACs, legal cuts, buffer slots and kernel plans.  pair_launches: two independent convolutions on one
 // tensor share a launch; fuse_ingest: the first convolution may read the caller's input layout itself; staged_rows:
 // convolutions whose pixels are whole 64-byte rows fetch them coalesced through LDS; small_tiles: deep, skinny layers
-// get 16-pixel tiles instead of a K split across workgroups.  Returns "" or an error text.
-std::string build_plan(const daris_dnn& dnn, bool keep_activations, bool pair_launches, bool fuse_ingest, bool staged_rows, bool small_tiles, NetPlan* out);
+// get 16-pixel tiles instead of a K split across workgroups; fuse_dw: a depthwise convolution is computed inside the 1x1
+// convolution that alone reads it.  Returns "" or an error text.
+std::string build_plan(const daris_dnn& dnn, bool keep_activations, bool pair_launches, bool fuse_ingest, bool staged_rows, bool small_tiles, bool fuse_dw,
+                       NetPlan* out);
 // Chooses k - 1 cuts minimising the largest per-stage MAC count, ties to the lexicographically smallest cut
 // list.  Returns false when k exceeds the number of legal cuts + 1.
 bool split_stages(NetPlan* net, int k);

@@ -4,6 +4,7 @@ import numpy as np
 import pytest
 
 import workloads as wl
+import paper_2504_08795_amd as D
 from gpu_helpers import GpuNet, oracle_logits, rel_err
 
 pytestmark = pytest.mark.gpu
@@ -113,6 +114,54 @@ def test_conv_pair_in_bottleneck_block(cin, h, w, mid, cout, s, ds_first, dtype)
 def test_depthwise(c, h, w, s, dtype):
     layers = [N.Layer(op=N.OP_CONV, c_in=c, c_out=c, k=3, stride=s, pad=1, groups=c, act=2, in_from=-1)]
     run_case(layers, (c, h, w), dtype)
+
+
+# (block input channels, hidden channels, h, w, depthwise stride, output channels, residual)
+DW_PROJECT_CASES = [
+    (16, 32, 112, 112, 1, 16, True),    # MobileNetV2's first block: K = 32, one chunk per wave, 392 pixel tiles
+    (16, 96, 113, 111, 2, 24, False),   # stride 2 on odd sizes: 57 x 56 outputs, ragged last tile
+    (24, 144, 56, 56, 1, 24, True),     # 144 channels: whole 64-byte rows in fp32 only (bf16 keeps the separate launch)
+    (16, 64, 56, 56, 1, 64, False),     # 64 output channels: one tile of two channel blocks in bf16 (fused), two tiles in fp32 (not)
+    (32, 192, 28, 28, 2, 64, False),    # the rest: too few pixel tiles or several channel blocks, the depthwise launch stays
+    (64, 384, 14, 14, 1, 64, True),
+    (160, 960, 7, 7, 1, 320, False),
+    (40, 64, 9, 9, 1, 40, True),
+]
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("case", DW_PROJECT_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_depthwise_computed_inside_the_projection(case, dtype):
+    """An inverted residual block's depthwise 3x3 convolution computed inside the launch of the 1x1 convolution that reads it:
+    against the oracle, and against the same block with the depthwise layer in a launch of its own (bit for bit when the
+    1x1 convolution keeps its plan, since the fused producer accumulates in the same order)."""
+    cin, hid, h, w, s, cout, res = case
+    if res:
+        assert s == 1 and cin == cout
+    layers = [N.Layer(op=N.OP_CONV, c_in=3, c_out=cin, k=3, stride=1, pad=1, act=0, in_from=-1),
+              N.Layer(op=N.OP_CONV, c_in=cin, c_out=hid, k=1, stride=1, pad=0, act=2, in_from=0),
+              N.Layer(op=N.OP_CONV, c_in=hid, c_out=hid, k=3, stride=s, pad=1, groups=hid, act=2, in_from=1),
+              N.Layer(op=N.OP_CONV, c_in=hid, c_out=cout, k=1, stride=1, pad=0, act=0, in_from=2, res_from=0 if res else -1)]
+    weights = [rand_w(L) for L in layers]
+    x = RNG.normal(0, 1, (3, h, w)).astype(np.float32)
+    want = oracle_logits(layers, weights, x, dtype)
+    outs, plans = [], []
+    for flags in (0, D.NO_FUSED_DW):
+        with GpuNet(layers, weights, (3, h, w), dtype, flags=flags) as net:
+            outs.append(net.forward(x))
+            plans.append([D.daris_get_launch_plan(net.task, l) for l in range(4)])
+    # fused where the hidden tensor's pixels are whole 64-byte rows and the 1x1 convolution has at least 96 pixel tiles and one
+    # channel tile of a staged kernel variant
+    o = plans[1][3]
+    want_fused = (hid * (4 if dtype == "fp32" else 2)) % 64 == 0 and o["MT"] >= 96 and o["NTn"] == 1 and (dtype == "bf16" or o["tn"] == 1)
+    assert (plans[0][2]["pair_with"] == 3) == want_fused and plans[1][2]["pair_with"] == -1    # the case runs the path it names
+    assert want_fused == {"fp32": case in DW_PROJECT_CASES[:3], "bf16": case in DW_PROJECT_CASES[:2] + DW_PROJECT_CASES[3:4]}[dtype]
+    tol = {"fp32": 5e-5, "bf16": 1.5e-2}[dtype]
+    for got in outs:
+        e_max, e_l2 = rel_err(got, want)
+        assert e_max <= tol and e_l2 <= tol, (e_max, e_l2)
+    if all(plans[0][3][k] == plans[1][3][k] for k in ("kernel_id", "splitk", "sz", "sw", "rows")):
+        np.testing.assert_array_equal(outs[0], outs[1])
 
 
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])

@@ -43,7 +43,7 @@ def test_logits_bit_identical_across_splits_and_partitions(net, dtype):
         np.testing.assert_array_equal(o, outs[0])
 
 
-@pytest.mark.parametrize("net,dtype", [("resnet18", "fp32"), ("resnet50", "bf16")])
+@pytest.mark.parametrize("net,dtype", [("resnet18", "fp32"), ("resnet50", "bf16"), ("mobilenet_v2", "fp32"), ("mobilenet_v2", "bf16")])
 def test_plain_launch_shapes_agree_with_the_fused_ones(net, dtype):
     """The launch-count optimisations -- a residual block's shortcut and first convolution in one launch, the input layout
     conversion folded into the first convolution -- can be switched off when a task is registered: the plain launches
@@ -55,8 +55,8 @@ def test_plain_launch_shapes_agree_with_the_fused_ones(net, dtype):
     with GpuNet(layers, weights, shp, dtype, k=3) as g:
         fused = g.forward(x)
         n_pairs = sum(1 for l in range(len(layers)) if D.daris_get_launch_plan(g.task, l)["pair_lead"])
-    assert n_pairs >= 3
-    with GpuNet(layers, weights, shp, dtype, k=3, flags=D.NO_PAIR | D.NO_FUSED_INGEST) as g:
+    assert n_pairs >= (2 if net == "mobilenet_v2" else 3)      # MobileNetV2: depthwise layers computed inside the projections
+    with GpuNet(layers, weights, shp, dtype, k=3, flags=D.NO_PAIR | D.NO_FUSED_INGEST | D.NO_FUSED_DW) as g:
         plain = g.forward(x)
         assert not any(D.daris_get_launch_plan(g.task, l)["pair_lead"] for l in range(len(layers)))
     for got in (fused, plain):

@@ -179,12 +179,28 @@ def test_launch_plans_satisfy_kernel_assumptions(net, dtype):
         dnn, keep = D.make_dnn(layers, None, shp, dtype)
         t = D.daris_register_task(dnn, 10**7, 10**7, D.LP)
         plans = [D.daris_get_launch_plan(t, l) for l in range(len(layers))]
-    n_pairs = 0
+    n_pairs = n_fused = 0
+    es = 4 if dtype == "fp32" else 2
     for l, (L, pl) in enumerate(zip(layers, plans)):
         if not pl["dense_conv"]:
-            assert pl["pair_with"] == -1
+            if pl["pair_with"] >= 0:
+                # a depthwise 3x3 convolution computed inside the launch of the 1x1 convolution that follows it: what that
+                # kernel's producer assumes about the two layers and about the plan
+                o, Lo = plans[l + 1], layers[l + 1]
+                assert pl["pair_with"] == l + 1 and not pl["pair_lead"] and o["pair_with"] == l and o["pair_lead"]
+                assert L.op == wl.nets.OP_CONV and L.groups == L.c_in == L.c_out and L.k == 3 and L.pad == 1 and L.stride in (1, 2)
+                assert Lo.op == wl.nets.OP_CONV and Lo.groups == 1 and Lo.k == 1 and Lo.stride == 1 and Lo.pad == 0 and Lo.in_from == l
+                assert all(q.in_from != l and q.res_from != l for q in layers[l + 2:])      # nobody else needs the tensor
+                assert (L.c_out * es) % 64 == 0 and o["rows"] == 32 and o["Kpad"] == L.c_out
+                assert o["S"] % 2 == 0 and o["sz"] % 2 == 0 and o["sw"] % 2 == 0             # K in whole chunks of two steps
+                assert dtype == "bf16" or o["tn"] == 1
+                assert not (dtype == "bf16" and o["nw"] == 8)                                 # no such kernel variant
+                assert o["MT"] >= 96 and o["NTn"] == 1                                         # the shapes for which it is faster
+                n_fused += 1
             continue
         _check_plan(pl, f"{net} {dtype} layer {l} {L.name}")
+        if pl["pair_with"] >= 0 and not plans[pl["pair_with"]]["dense_conv"]:
+            continue                                                           # leads a fused depthwise layer (checked above)
         if pl["pair_with"] >= 0:
             o = plans[pl["pair_with"]]
             assert abs(pl["pair_with"] - l) == 1 and o["pair_with"] == l and pl["pair_lead"] != o["pair_lead"]
@@ -195,6 +211,9 @@ def test_launch_plans_satisfy_kernel_assumptions(net, dtype):
             assert light["splitk"] == 1                                        # the second problem never splits K across workgroups
             n_pairs += 1
     assert n_pairs // 2 == {"tiny": 0, "resnet18": 3, "resnet50": 4, "vgg16": 0, "mobilenet_v2": 0}[net]
+    # MobileNetV2: the blocks on the 112 x 112 and 56 x 56 maps (enough pixel tiles, one channel block); in bf16 the 144-channel
+    # hidden layer is not a whole number of 64-byte rows
+    assert n_fused == ({"fp32": 3, "bf16": 2}[dtype] if net == "mobilenet_v2" else 0)
 
 
 def test_launch_plans_of_odd_shapes():
@@ -405,7 +424,7 @@ def test_code_object_kernels_match_the_argument_structures():
     if not (os.path.exists(co) and os.path.exists(tool)):
         pytest.skip("code object or llvm-readelf not available")
     notes = subprocess.run([tool, "--notes", co], check=True, capture_output=True, text=True).stdout
-    want = {"conv_wave_kernel": 160, "conv_wave_pair_kernel": 324, "conv_wave16_kernel": 160, "conv_wave16_pair_kernel": 324, "splitk_reduce_kernel": 48, "dwconv_kernel": 72,
+    want = {"conv_wave_kernel": 160, "conv_wave_pair_kernel": 324, "conv_wave16_kernel": 160, "conv_wave16_pair_kernel": 324, "conv_wave_dw_kernel": 192, "splitk_reduce_kernel": 48, "dwconv_kernel": 72,
             "maxpool_kernel": 48, "gavgpool_kernel": 48, "fc_kernel": 56, "ingest_kernel": 28, "egress_kernel": 28,
             "cu_probe_kernel": 12}
     seen = {}
@@ -420,7 +439,7 @@ def test_code_object_kernels_match_the_argument_structures():
         assert size == want[base[0]], (name, size)
         assert scratch == 0 and lds <= 65536, (name, scratch, lds)
         seen[base[0]] = seen.get(base[0], 0) + 1
-    assert seen == {"conv_wave_kernel": 48, "conv_wave_pair_kernel": 36, "conv_wave16_kernel": 12, "conv_wave16_pair_kernel": 12, "splitk_reduce_kernel": 2, "dwconv_kernel": 2,
+    assert seen == {"conv_wave_kernel": 48, "conv_wave_pair_kernel": 36, "conv_wave16_kernel": 12, "conv_wave16_pair_kernel": 12, "conv_wave_dw_kernel": 7, "splitk_reduce_kernel": 2, "dwconv_kernel": 2,
                     "maxpool_kernel": 2, "gavgpool_kernel": 2, "fc_kernel": 2, "ingest_kernel": 2, "egress_kernel": 2,
                     "cu_probe_kernel": 1}
 
@@ -454,8 +473,13 @@ def _check_slot_lifetimes(layers, plans, name):
     slot it reads itself."""
     n = len(layers)
     issue = [max(l, plans[l]["pair_with"]) for l in range(n)]                     # when layer l's launch is issued
+    # a depthwise layer computed inside the next layer's launch: its output is neither written nor read, and its input is
+    # read by that launch
+    fused_dw = [not plans[l]["dense_conv"] and plans[l]["pair_with"] >= 0 for l in range(n)]
     readers = {}                                                                  # tensor (layer index, -1 = input) -> issue times of its readers
     for l, L in enumerate(layers):
+        if L.in_from >= 0 and fused_dw[L.in_from]:
+            continue
         readers.setdefault(L.in_from, []).append(issue[l])
         if L.res_from >= 0:
             readers.setdefault(L.res_from, []).append(issue[l])
@@ -465,10 +489,11 @@ def _check_slot_lifetimes(layers, plans, name):
     for l in range(n):
         group = [q for q in range(n) if issue[q] == issue[l]]
         s = plans[l]["out_slot"]
-        if s < 0:
+        if s < 0 or fused_dw[l]:
             continue
         for q in group:                                                           # nothing the group reads may be overwritten by it
-            assert s != plans[q]["in_slot"] and s != plans[q]["res_slot"], (name, l, q, s)
+            reads_input = not (layers[q].in_from >= 0 and fused_dw[layers[q].in_from])
+            assert (s != plans[q]["in_slot"] or not reads_input) and s != plans[q]["res_slot"], (name, l, q, s)
         if s in holds:
             old = holds[s]
             assert all(t < issue[l] for t in readers.get(old, [])), (name, "layer", l, "overwrites tensor", old, "still read at", readers.get(old))
