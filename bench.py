@@ -108,7 +108,7 @@ def measure(config, args, full):
     import workloads as wl
 
     ts = wl.make_taskset(config, n_jobs=64)
-    g = harness.GpuTaskSet(ts, flags=args.flags, seed=wl.tasksets.SEED)
+    g = harness.GpuTaskSet(ts, flags=args.flags, seed=wl.tasksets.SEED, plan_cus=args.plan_cus)
     nt = g.n_tasks
     try:
         g.calibrate(3)
@@ -137,7 +137,7 @@ def measure(config, args, full):
                              roofline_time_over_wall=sum(d * r for d, r in zip(done, roof_us)) * 1e-6 / elapsed))
         timing, pair_ms = (None, 0.0) if (not full or args.no_profile) else D.daris_kernel_timing_read()
         med = sorted(runs, key=lambda r: r["value"])[len(runs) // 2]
-        out = dict(config=config, workload=WORKLOADS[config], tasks=nt, partitions=ts.partitions, stages=[t.n_stages for t in ts.tasks],
+        out = dict(config=config, workload=WORKLOADS[config], tasks=nt, partitions=ts.partitions, plan_cus=g.plan_cus, stages=[t.n_stages for t in ts.tasks],
                    nets=[t.net for t in ts.tasks], dtype=ts.tasks[0].dtype,
                    periods_ms=[round(t.period_ns / 1e6, 3) for t in ts.tasks], value=med["value"], elapsed=med["elapsed"],
                    values=[round(r["value"], 2) for r in runs],
@@ -254,6 +254,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=4, choices=(2, 3, 4), help="configuration of the headline line (default: the mixed set)")
     ap.add_argument("--other-configs", default="2,3", help="configurations whose saturated figure is attached as other_configs ('' = none)")
+    ap.add_argument("--plan-cus", type=int, default=0, help="partition size the launch plans are balanced for (0: the partitions' size when all "
+                    "are equal, else 128)")
     ap.add_argument("--repeats", type=int, default=3, help="timed regions of --steps steps each; the median is the value")
     ap.add_argument("--periodic-jobs", type=int, default=40, help="jobs per task of the periodic (deadline) run; 0 skips it")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU-oracle baseline; 0 skips it")
@@ -289,7 +291,7 @@ def main():
         "ms_per_step": round(1e3 * main_res["elapsed"] / args.steps, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if main_res["dtype"] == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": main_res["workload"], "baseline_config": args.config, "tasks": main_res["tasks"], "nets": main_res["nets"],
-                   "partitions": main_res["partitions"], "stages": main_res["stages"], "periods_ms": main_res["periods_ms"],
+                   "partitions": main_res["partitions"], "plan_cus": main_res["plan_cus"], "stages": main_res["stages"], "periods_ms": main_res["periods_ms"],
                    "jobs_per_step": main_res["tasks"] * JOBS_PER_TASK_PER_STEP},
         "repeats": {"values": main_res["values"], "spread_pct": main_res["spread_pct"], "value_is": "median"},
         "saturated": main_res["saturated"],

@@ -160,6 +160,13 @@ const char* daris_last_error(void);
  * the read-only accessors returns DARIS_EHIP too.  daris_shutdown then lets the queues run dry for at most 5 s each before
  * it frees the buffers. */
 daris_status daris_set_timeout(int64_t ns);
+/* The partition size (CUs, 8..256; default 128, reset by daris_init) that the launch plans of tasks registered from now on
+ * are balanced for: how many workgroups a convolution is cut into, so that a launch fills the CUs in whole rounds.  A
+ * task's plan is fixed when it is registered and is the same wherever its stages run, so its results never depend on the
+ * partition (Sec. III-A: a task may be migrated to any context).  A set-up with equal partitions of another size calls
+ * this with that size (ResNet-18 on 64-CU partitions: 273 us with plans for 128 CUs, 243 us with plans for 64); with
+ * unequal partitions a plan for the smaller ones costs as much on the larger ones as it gains. */
+daris_status daris_set_plan_cus(int n_cu);
 
 /* ---- partitions (Sec. III-C) ------------------------------------------------------------------------------- */
 

@@ -53,6 +53,7 @@ _SIGS = {
     "daris_init": (C.c_int32, [C.c_int, C.c_uint64, C.c_int]),
     "daris_shutdown": (C.c_int32, []),
     "daris_set_timeout": (C.c_int32, [C.c_int64]),
+    "daris_set_plan_cus": (C.c_int32, [C.c_int32]),
     "daris_last_error": (C.c_char_p, []),
     "daris_cu_per_partition": (C.c_int32, [C.c_int32] * 4),
     "daris_create_partition": (C.c_int32, [C.c_int]),
@@ -132,6 +133,10 @@ def daris_shutdown():
 
 def daris_set_timeout(ns):
     return _chk(lib().daris_set_timeout(int(ns)))
+
+
+def daris_set_plan_cus(n_cu):
+    return _chk(lib().daris_set_plan_cus(int(n_cu)))
 
 
 def daris_cu_per_partition(os_num, os_den, n_cu_max, n_c):

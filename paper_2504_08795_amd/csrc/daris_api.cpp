@@ -155,6 +155,7 @@ struct Global {
   std::vector<PartRt> parts;
   std::vector<std::unique_ptr<TaskRt>> tasks;
   int cu_cursor = 0;
+  int plan_cus = 128;      // partition size the launch plans of tasks registered from now on are balanced for
   bool committed = false;  // Algorithm 1 has run, the online phase has begun
   bool frozen = false;     // streams exist, the partition set can no longer change
   // virtual time
@@ -856,6 +857,13 @@ daris_status daris_set_timeout(int64_t ns) {
   return DARIS_OK;
 }
 
+daris_status daris_set_plan_cus(int n_cu) {
+  if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
+  if (n_cu < 8 || n_cu > 256) return fail(DARIS_EINVAL, "the nominal partition size must be in 8..256, got %d", n_cu);
+  G->plan_cus = n_cu;
+  return DARIS_OK;
+}
+
 daris_status daris_shutdown(void) {
   if (!G || !G->inited) return fail(DARIS_ESTATE, "library not initialised");
   {
@@ -936,7 +944,7 @@ daris_task daris_register_task(const daris_dnn* dnn, int64_t period_ns, int64_t 
   if (priority != DARIS_HP && priority != DARIS_LP) return fail(DARIS_EINVAL, "priority must be DARIS_HP or DARIS_LP");
   if (G->tasks.size() >= 65535) return fail(DARIS_ERANGE, "too many tasks");
   std::unique_ptr<TaskRt> T(new TaskRt());
-  std::string err = build_plan(*dnn, G->flags & DARIS_KEEP_ACTIVATIONS, !(G->flags & DARIS_NO_PAIR), !(G->flags & DARIS_NO_FUSED_INGEST), !(G->flags & DARIS_NO_STAGED_ROWS), !(G->flags & DARIS_NO_SMALL_TILES), !(G->flags & DARIS_NO_FUSED_DW), &T->net);
+  std::string err = build_plan(*dnn, G->flags & DARIS_KEEP_ACTIVATIONS, !(G->flags & DARIS_NO_PAIR), !(G->flags & DARIS_NO_FUSED_INGEST), !(G->flags & DARIS_NO_STAGED_ROWS), !(G->flags & DARIS_NO_SMALL_TILES), !(G->flags & DARIS_NO_FUSED_DW), G->plan_cus, &T->net);
   if (!err.empty()) return fail(DARIS_EINVAL, "%s", err.c_str());
   if (!G->nodev) {
     NetPlan& net = T->net;

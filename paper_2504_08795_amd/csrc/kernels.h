@@ -90,14 +90,14 @@ struct ConvPlan {
 // True when every pixel's channel vector is a whole number of 64-byte rows, the shape for which the convolution kernel
 // fetches the pixel operand in coalesced rows through LDS (chunks of two K steps).
 inline bool conv_rows_staged(int cin_stride, int bf16) { return cin_stride > 0 && (cin_stride * (bf16 ? 2 : 4)) % 64 == 0; }
-// bf16 = 0/1.  Chooses tile shape, waves per workgroup and split-K from (M, N, Kpad) only, so results do not depend on the
-// partition a stage runs in.  step_align = 2 cuts K in whole chunks of two steps (for conv_rows_staged shapes), else 1.
+// bf16 = 0/1.  Chooses tile shape, waves per workgroup and split-K from (M, N, Kpad) and the nominal partition size
+// (nominal_cus: how many CUs the grid is balanced for) only, so results do not depend on the partition a stage runs in.  step_align = 2 cuts K in whole chunks of two steps (for conv_rows_staged shapes), else 1.
 // cin_stride = the input tensor's channel stride: when it is a whole number of the 16-row kernel's K steps and the 32-row
 // plan would split K across workgroups, a 16-row plan that does not need to is chosen instead (cin_stride 0: never).
-ConvPlan plan_conv(int M, int N, int Kpad, int bf16, int step_align, int cin_stride = 0);
+ConvPlan plan_conv(int M, int N, int Kpad, int bf16, int step_align, int cin_stride = 0, int nominal_cus = 128);
 // Plan for a second convolution that is to share a launch with `first`: the same wave-tile kernel variant, K not split
 // across workgroups.  Returns a plan with kernel == K_NONE when that is not possible.
-ConvPlan plan_conv_like(const ConvPlan& first, int M, int N, int Kpad, int bf16, int step_align);
+ConvPlan plan_conv_like(const ConvPlan& first, int M, int N, int Kpad, int bf16, int step_align, int nominal_cus = 128);
 // Multiplier for fast_div: floor(2^32 / d) + 1, or 0 for d == 1.  Exact for every n >= 0 with n * d < 2^32.
 inline uint32_t div_magic(uint32_t d) { return d <= 1 ? 0u : (uint32_t)((1ull << 32) / d) + 1u; }
 

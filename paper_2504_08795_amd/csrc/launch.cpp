@@ -22,9 +22,12 @@ const char* kernel_name(int32_t id) { return (id >= 0 && id < K_COUNT) ? kNames[
 
 static inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
-static const int kNominalWaveSlots = 512;  // 128 CUs x 4 SIMDs: the partition size the plans are tuned for
+// Launches of equal workgroups run in ceil(workgroups / CUs) rounds: how many rounds' worth of time the grid needs per
+// round's worth of work.  1 = perfectly even; 98 workgroups on 96 CUs: 1.96.
+static double round_waste(int groups, int cus) { return (double)cdiv(groups, cus) * cus / groups; }
 
-static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16, int step_align, int force_tn = 0, int force_nw = 0) {
+static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16, int step_align, int nominal_cus, int force_tn = 0, int force_nw = 0) {
+  const int kNominalWaveSlots = 4 * nominal_cus;  // SIMDs of the partition size the plan is balanced for
   // Measured on a 128-CU partition (fp32, ResNet-18 shapes): the K loop itself runs near the MFMA rate; what a
   // launch pays for is its fixed cost and idle CUs.  Best found: 8 waves per workgroup splitting K, and enough
   // grid.z slices that tiles * z is about the number of CUs, while a wave keeps at least ~6 steps.
@@ -35,7 +38,13 @@ static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16, int step_align,
   // A wave tile two channel blocks wide halves the reads of the pixel operand, but also halves the number of tiles:
   // below about 3/4 of the partition's CUs it is better to keep 32-channel tiles and split K less (or not at all,
   // which saves the reduction launch).
-  int tn = (nb % 2 == 0 && cdiv(M, 32) * (nb / 2) >= 96) ? 2 : 1;
+  int tn = (nb % 2 == 0 && cdiv(M, 32) * (nb / 2) >= nominal_cus * 3 / 4) ? 2 : 1;
+  // ... unless the 64-channel tiles are a few more than the CUs (98 on 96): the launch then takes two rounds for hardly more
+  // than one round's work, and twice as many tiles of half the work take three half rounds
+  if (tn == 2) {
+    const int t2 = cdiv(M, 32) * (nb / 2);
+    if (t2 > nominal_cus && round_waste(t2, nominal_cus) > 1.3 && round_waste(2 * t2, nominal_cus) < round_waste(t2, nominal_cus)) tn = 1;
+  }
   if (force_tn) tn = force_tn;
   // Fetching the pixel operand as coalesced rows through LDS pays where a launch is bound by its loads: every bf16 shape
   // (+11 % on the saturated ResNet-50 set) and 32-channel fp32 tiles.  fp32 tiles of 64 channels are bound by the matrix
@@ -43,7 +52,6 @@ static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16, int step_align,
   // register count held at 128), so they stay register-fed.
   if (step_align > 1 && !bf16 && tn == 2) step_align = 1;
   const int tiles = cdiv(M, 32) * (nb / tn);
-  const int nominal_cus = kNominalWaveSlots / 4;
   int nw = bf16 ? 4 : 8;  // bf16 steps are short: fewer waves to sum through LDS beat a finer K split (measured 0.4-0.8 us per layer)
   while (nw > 2 && (S / nw < 4 || tiles * nw > 8 * kNominalWaveSlots)) nw /= 2;  // >= 4 steps per wave, <= 8 waves per SIMD
   int z = nominal_cus / tiles;
@@ -108,15 +116,19 @@ static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16, int step_align,
 // 16-pixel tiles of tn 16-channel blocks, K split among the waves of a workgroup only.  Chosen for layers whose 32-row
 // plan needs a reduction launch; returns kernel == K_NONE when the shape does not fill three quarters of the nominal
 // partition either, or is too shallow to split eight (four) ways.
-static ConvPlan plan_conv_wave16(int M, int N, int Kpad, int bf16, int force_tn = 0, int force_nw = 0) {
+static ConvPlan plan_conv_wave16(int M, int N, int Kpad, int bf16, int nominal_cus, int force_tn = 0, int force_nw = 0) {
   ConvPlan pl = ConvPlan();
   const int ks = bf16 ? 32 : 16;
   if (Kpad % ks) return pl;
   const int S = Kpad / ks;
   const int nb = cdiv(N, 16), mt = cdiv(M, 16);
-  const int nominal_cus = kNominalWaveSlots / 4;
   // two channel blocks per wave halve the reads of the pixel operand: taken when that still gives nearly one workgroup per CU
+  // (and not a few more than one per CU, see plan_conv_wave)
   int tn = (nb % 2 == 0 && mt * (nb / 2) >= nominal_cus * 3 / 4) ? 2 : 1;
+  if (tn == 2) {
+    const int t2 = mt * (nb / 2);
+    if (t2 > nominal_cus && round_waste(t2, nominal_cus) > 1.3 && round_waste(2 * t2, nominal_cus) < round_waste(t2, nominal_cus)) tn = 1;
+  }
   if (force_tn) tn = force_tn;
   if (nb % tn) return pl;
   const int tiles = mt * (nb / tn);
@@ -156,20 +168,24 @@ static ConvPlan plan_conv_wave16(int M, int N, int Kpad, int bf16, int force_tn 
   return pl;
 }
 
-ConvPlan plan_conv(int M, int N, int Kpad, int bf16, int step_align, int cin_stride) {
-  const ConvPlan pl = plan_conv_wave(M, N, Kpad, bf16, step_align);
+ConvPlan plan_conv(int M, int N, int Kpad, int bf16, int step_align, int cin_stride, int nominal_cus) {
+  if (nominal_cus < 8) nominal_cus = 8;
+  if (nominal_cus > 256) nominal_cus = 256;
+  const ConvPlan pl = plan_conv_wave(M, N, Kpad, bf16, step_align, nominal_cus);
   if (pl.splitk > 1 && cin_stride > 0 && cin_stride % (bf16 ? 32 : 16) == 0) {
-    const ConvPlan p16 = plan_conv_wave16(M, N, Kpad, bf16);
+    const ConvPlan p16 = plan_conv_wave16(M, N, Kpad, bf16, nominal_cus);
     if (p16.kernel != K_NONE) return p16;
   }
   return pl;
 }
 
-ConvPlan plan_conv_like(const ConvPlan& first, int M, int N, int Kpad, int bf16, int step_align) {
+ConvPlan plan_conv_like(const ConvPlan& first, int M, int N, int Kpad, int bf16, int step_align, int nominal_cus) {
   ConvPlan none = ConvPlan();
-  if (first.rows == 16) return plan_conv_wave16(M, N, Kpad, bf16, first.tn, first.nw);
+  if (nominal_cus < 8) nominal_cus = 8;
+  if (nominal_cus > 256) nominal_cus = 256;
+  if (first.rows == 16) return plan_conv_wave16(M, N, Kpad, bf16, nominal_cus, first.tn, first.nw);
   if (cdiv(N, 32) % first.tn != 0) return none;
-  return plan_conv_wave(M, N, Kpad, bf16, step_align, first.tn, first.nw);
+  return plan_conv_wave(M, N, Kpad, bf16, step_align, nominal_cus, first.tn, first.nw);
 }
 
 

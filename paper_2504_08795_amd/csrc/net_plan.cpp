@@ -18,7 +18,7 @@ uint16_t host_f32_to_bf16(float f) {
 }
 
 std::string build_plan(const daris_dnn& dnn, bool keep_activations, bool pair_launches, bool fuse_ingest, bool staged_rows, bool small_tiles, bool fuse_dw,
-                       NetPlan* out) {
+                       int plan_cus, NetPlan* out) {
   NetPlan& net = *out;
   net = NetPlan();
   if (dnn.n_layers < 1 || !dnn.layers) return "DNN has no layers";
@@ -68,7 +68,7 @@ std::string build_plan(const daris_dnn& dnn, bool keep_activations, bool pair_la
           // the kernels divide pixel and k indices by Wo, Cin and kw with 32-bit multipliers: operands must stay small
           if ((uint64_t)(o.H * (uint64_t)o.W + 64) * (uint64_t)o.W >= (1ull << 32) || (uint64_t)(L.Kpad + 64) * (uint64_t)in.Cs >= (1ull << 32))
             return "layer " + std::to_string(l) + ": tensor too large for the kernels' index arithmetic";
-          L.cp = plan_conv(o.H * o.W, o.Cs, L.Kpad, net.bf16, staged_rows && conv_rows_staged(in.Cs, net.bf16) ? 2 : 1, small_tiles ? in.Cs : 0);
+          L.cp = plan_conv(o.H * o.W, o.Cs, L.Kpad, net.bf16, staged_rows && conv_rows_staged(in.Cs, net.bf16) ? 2 : 1, small_tiles ? in.Cs : 0, plan_cus);
           L.kernel_id = L.cp.kernel;
           net.ws_bytes = std::max(net.ws_bytes, L.cp.ws_bytes);
         } else {
@@ -122,7 +122,7 @@ std::string build_plan(const daris_dnn& dnn, bool keep_activations, bool pair_la
     LayerPlan& heavy = A.macs > B.macs ? A : B;
     LayerPlan& light = A.macs > B.macs ? B : A;
     const ConvPlan like = plan_conv_like(heavy.cp, light.out.H * light.out.W, light.out.Cs, light.Kpad, net.bf16,
-                                         staged_rows && conv_rows_staged(net.tensor(light.in_t).Cs, net.bf16) ? 2 : 1);
+                                         staged_rows && conv_rows_staged(net.tensor(light.in_t).Cs, net.bf16) ? 2 : 1, plan_cus);
     if (like.kernel == K_NONE) continue;
     light.cp = like;
     light.kernel_id = like.kernel;
@@ -142,7 +142,7 @@ std::string build_plan(const daris_dnn& dnn, bool keep_activations, bool pair_la
       if (net.layers[q].in_t == l + 1 || net.layers[q].res_t == l + 1) only_reader = false;
     if (!only_reader || !conv_rows_staged(A.out.Cs, net.bf16)) continue;
     ConvPlan cp = B.cp;
-    if (cp.rows != 32) cp = plan_conv(B.out.H * B.out.W, B.out.Cs, B.Kpad, net.bf16, 2, 0);  // the fused producer exists for 32-pixel tiles
+    if (cp.rows != 32) cp = plan_conv(B.out.H * B.out.W, B.out.Cs, B.Kpad, net.bf16, 2, 0, plan_cus);  // the fused producer exists for 32-pixel tiles
     if (!conv_dw_fusable(cp, net.bf16)) continue;  // the separate launch is faster (or no such kernel variant)
     B.cp = cp;
     B.kernel_id = cp.kernel;

@@ -58,8 +58,9 @@ struct NetPlan {
 // convolutions whose pixels are whole 64-byte rows fetch them coalesced through LDS; small_tiles: deep, skinny layers
 // get 16-pixel tiles instead of a K split across workgroups; fuse_dw: a depthwise convolution is computed inside the 1x1
 // convolution that alone reads it.  Returns "" or an error text.
+// plan_cus: the partition size the convolution grids are balanced for.
 std::string build_plan(const daris_dnn& dnn, bool keep_activations, bool pair_launches, bool fuse_ingest, bool staged_rows, bool small_tiles, bool fuse_dw,
-                       NetPlan* out);
+                       int plan_cus, NetPlan* out);
 // Chooses k - 1 cuts minimising the largest per-stage MAC count, ties to the lexicographically smallest cut
 // list.  Returns false when k exceeds the number of legal cuts + 1.
 bool split_stages(NetPlan* net, int k);

@@ -27,9 +27,11 @@ def out_elems(layers, shp):
 class GpuNet:
     """One task registered on one partition of `n_cu` CUs, for direct forward passes."""
 
-    def __init__(self, layers, weights, shp, dtype, k=1, n_cu=128, flags=0, extra_partitions=()):
+    def __init__(self, layers, weights, shp, dtype, k=1, n_cu=128, flags=0, extra_partitions=(), plan_cus=0):
         self.layers, self.shp, self.dtype = layers, shp, dtype
         D.daris_init(0, 0, flags)
+        if plan_cus:
+            D.daris_set_plan_cus(plan_cus)
         self.parts = [D.daris_create_partition(n_cu)] + [D.daris_create_partition(n) for n in extra_partitions]
         dnn, self._keep = D.make_dnn(layers, weights, shp, dtype)
         self.task = D.daris_register_task(dnn, 10_000_000, 10_000_000, D.LP)

@@ -43,6 +43,26 @@ def test_logits_bit_identical_across_splits_and_partitions(net, dtype):
         np.testing.assert_array_equal(o, outs[0])
 
 
+@pytest.mark.parametrize("net,dtype,plan_cus", [("resnet18", "fp32", 64), ("resnet18", "fp32", 96), ("resnet50", "bf16", 64), ("mobilenet_v2", "fp32", 32),
+                                                 ("vgg16", "fp32", 96)])
+def test_plans_balanced_for_another_partition_size(net, dtype, plan_cus):
+    """daris_set_plan_cus changes how the convolutions are cut into workgroups (other tiles, other K slices): the logits must
+    meet the same tolerance, and still be the same bit for bit on every partition the task runs in."""
+    layers, shp = wl.build_net(net)
+    weights = wl.make_weights(layers, 13)
+    x = wl.make_inputs(shp, 13, 1, "normal")[0]
+    want = oracle_logits(layers, weights, x, dtype)
+    with GpuNet(layers, weights, shp, dtype, k=3, n_cu=plan_cus, extra_partitions=(192,), plan_cus=plan_cus) as g:
+        a, b = g.forward(x, part=0), g.forward(x, part=1)
+        plans = [D.daris_get_launch_plan(g.task, l) for l in range(len(layers))]
+    with GpuNet(layers, weights, shp, dtype, k=3, n_cu=plan_cus) as g:
+        default_plans = [D.daris_get_launch_plan(g.task, l) for l in range(len(layers))]
+    assert any(p["grid_x"] != q["grid_x"] for p, q in zip(plans, default_plans))     # the case is what it claims to be
+    np.testing.assert_array_equal(a, b)
+    e_max, e_l2 = rel_err(a, want)
+    assert e_max <= TOL[dtype] and e_l2 <= TOL[dtype], (e_max, e_l2)
+
+
 @pytest.mark.parametrize("net,dtype", [("resnet18", "fp32"), ("resnet50", "bf16"), ("mobilenet_v2", "fp32"), ("mobilenet_v2", "bf16")])
 def test_plain_launch_shapes_agree_with_the_fused_ones(net, dtype):
     """The launch-count optimisations -- a residual block's shortcut and first convolution in one launch, the input layout

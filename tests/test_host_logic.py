@@ -216,6 +216,42 @@ def test_launch_plans_satisfy_kernel_assumptions(net, dtype):
     assert n_fused == ({"fp32": 3, "bf16": 2}[dtype] if net == "mobilenet_v2" else 0)
 
 
+@pytest.mark.parametrize("plan_cus", [32, 64, 96, 160, 256])
+def test_launch_plans_for_other_partition_sizes(plan_cus):
+    """daris_set_plan_cus: the plans still satisfy what the kernels assume, and they do change with the size."""
+    with pytest.raises(D.DarisError):
+        D.daris_set_plan_cus(96)                      # needs an initialised library
+    changed = 0
+    for net in ("resnet18", "resnet50", "vgg16", "mobilenet_v2"):
+        layers, shp = wl.build_net(net)
+        for dtype in ("fp32", "bf16"):
+            got = []
+            for cus in (plan_cus, 128):
+                with Session(HOST):
+                    for bad in (0, 7, 257):
+                        with pytest.raises(D.DarisError):
+                            D.daris_set_plan_cus(bad)
+                    D.daris_set_plan_cus(cus)
+                    D.daris_create_partition(64)
+                    dnn, keep = D.make_dnn(layers, None, shp, dtype)
+                    t = D.daris_register_task(dnn, 10**7, 10**7, D.LP)
+                    got.append([D.daris_get_launch_plan(t, l) for l in range(len(layers))])
+            for l, pl in enumerate(got[0]):
+                if pl["dense_conv"]:
+                    _check_plan(pl, f"{net} {dtype} plan_cus {plan_cus} layer {l}")
+            changed += got[0] != got[1]
+    assert changed >= 4
+    if plan_cus == 96:      # 98 tiles of 64 channels would take two rounds on 96 CUs: ResNet-18's first block uses 196 tiles of 32
+        layers, shp = wl.build_net("resnet18")
+        with Session(HOST):
+            D.daris_set_plan_cus(96)
+            D.daris_create_partition(96)
+            dnn, keep = D.make_dnn(layers, None, shp, "fp32")
+            t = D.daris_register_task(dnn, 10**7, 10**7, D.LP)
+            pl = D.daris_get_launch_plan(t, 2)
+        assert layers[2].name == "l1b0.c1" and pl["tn"] == 1 and pl["MT"] * pl["NTn"] == 196 and pl["splitk"] == 1
+
+
 def test_launch_plans_of_odd_shapes():
     rng = np.random.default_rng(5)
     N = wl.nets
