@@ -85,6 +85,37 @@ def test_plain_launch_shapes_agree_with_the_fused_ones(net, dtype):
     assert rel_err(plain, fused)[0] <= TOL[dtype]
 
 
+@pytest.mark.parametrize("net", ["mobilenet_v2", "resnet50"])
+def test_bf16_layers_on_the_oracles_own_inputs(net):
+    """The max-norm check that the chained drill-down cannot apply to bf16 intermediates (one rounding that falls the other
+    way upstream moves single elements downstream by whole bf16 steps): every layer alone, fed with the ORACLE's bf16 input
+    tensor of that layer.  With upstream decisions out of the picture, each output element must be the oracle's value or its
+    bf16 neighbour (fp32 versus double accumulation can still tip one rounding), and only a small share may differ at all."""
+    import dataclasses
+    layers, shp = wl.build_net(net)
+    weights = wl.make_weights(layers, 5)
+    x = wl.make_inputs(shp, 5, 1, "normal")[0]
+    _, acts = F.forward(layers, weights, x, "bf16", return_all=True)
+    shapes = wl.layer_shapes(layers, shp)
+    worst_share, checked = 0.0, 0
+    for l, L in enumerate(layers[:-1]):                       # the last layer's logits stay fp32: covered by the logits tests
+        if L.res_from >= 0:
+            continue                                          # needs two input tensors; its sum is covered by the chained runs
+        xin = x if L.in_from < 0 else np.asarray(acts[L.in_from], np.float32).reshape(shapes[L.in_from])
+        one = [dataclasses.replace(L, in_from=-1, res_from=-1)]
+        with GpuNet(one, [weights[l]], xin.shape, "bf16") as g:
+            got = g.forward(xin).astype(np.float64)
+        want = np.asarray(acts[l], np.float64).reshape(-1)
+        step = np.abs(want) * 2.0 ** -7 + 1e-6 * np.abs(want).max()        # one bf16 step of the element (8 significant bits)
+        assert (np.abs(got - want) <= step).all(), (l, L.name, float(np.abs(got - want).max()), float(np.abs(want).max()))
+        share = float((got != want).mean())
+        assert share <= 0.001, (l, L.name, share)
+        worst_share = max(worst_share, share)
+        checked += 1
+    assert checked >= 35
+    print(f"{net} bf16, each layer on the oracle's input: at most {100 * worst_share:.3f} % of a layer's elements differ, none by more than one step")
+
+
 @pytest.mark.parametrize("net,dtype", [("resnet18", "fp32"), ("resnet50", "bf16"), ("mobilenet_v2", "fp32")])
 def test_every_layer_output(net, dtype):
     """Drill-down with one buffer per layer: each intermediate tensor against the oracle's."""
