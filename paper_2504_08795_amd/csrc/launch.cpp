@@ -43,7 +43,8 @@ static ConvPlan plan_conv_wave(int M, int N, int Kpad, int bf16, int step_align,
   // than one round's work, and twice as many tiles of half the work take three half rounds
   if (tn == 2) {
     const int t2 = cdiv(M, 32) * (nb / 2);
-    if (t2 > nominal_cus && round_waste(t2, nominal_cus) > 1.3 && round_waste(2 * t2, nominal_cus) < round_waste(t2, nominal_cus)) tn = 1;
+    // (only for grids of one to two rounds: with more, the loss is smaller and the next round's workgroups overlap the tail -- measured: no gain)
+    if (t2 > nominal_cus && t2 <= 2 * nominal_cus && round_waste(t2, nominal_cus) > 1.3 && round_waste(2 * t2, nominal_cus) < round_waste(t2, nominal_cus)) tn = 1;
   }
   if (force_tn) tn = force_tn;
   // Fetching the pixel operand as coalesced rows through LDS pays where a launch is bound by its loads: every bf16 shape
@@ -127,7 +128,8 @@ static ConvPlan plan_conv_wave16(int M, int N, int Kpad, int bf16, int nominal_c
   int tn = (nb % 2 == 0 && mt * (nb / 2) >= nominal_cus * 3 / 4) ? 2 : 1;
   if (tn == 2) {
     const int t2 = mt * (nb / 2);
-    if (t2 > nominal_cus && round_waste(t2, nominal_cus) > 1.3 && round_waste(2 * t2, nominal_cus) < round_waste(t2, nominal_cus)) tn = 1;
+    // (only for grids of one to two rounds: with more, the loss is smaller and the next round's workgroups overlap the tail -- measured: no gain)
+    if (t2 > nominal_cus && t2 <= 2 * nominal_cus && round_waste(t2, nominal_cus) > 1.3 && round_waste(2 * t2, nominal_cus) < round_waste(t2, nominal_cus)) tn = 1;
   }
   if (force_tn) tn = force_tn;
   if (nb % tn) return pl;
