@@ -405,6 +405,31 @@ def test_saturated_run_with_streams_and_ablation_flags(streams, lib_flags, des_f
         g.close()
 
 
+@pytest.mark.parametrize("config", [4, 3])
+def test_saturated_closed_loop_in_the_benchmark_configuration(config):
+    """One step of `bench.py`'s timed region in its own launch configuration -- every task of the configuration releasing
+    back to back on its partition, 32 jobs per task released over all tasks from a common budget -- with the logits of
+    EVERY completed job checked against the oracle and the recorded trace replayed through it."""
+    per_step = 32
+    ts = wl.make_taskset(config, n_jobs=per_step * 8)          # a task may take far more than its share of the budget
+    ts.n_inputs = 2
+    nt = len(ts.tasks)
+    g = GpuTaskSet(ts)
+    try:
+        afet = g.calibrate(3)
+        D.daris_commit()
+        D.daris_run_closed_loop([per_step * nt] * nt, per_step * nt)
+        got = D.trace_read_all()
+        _replay_and_check(ts, afet, got)
+        worst, n = g.check_logits(got)
+        stats = g.stats()
+        assert n == sum(s["completed"] for s in stats) and n + sum(s["rejected_admission"] + s["rejected_overrun"] for s in stats) == per_step * nt
+        assert all(s["completed"] > 0 for s in stats)
+        print(f"config {config} saturated: {n} jobs, per task {[s['completed'] for s in stats]}, worst logits error {worst:.3e}")
+    finally:
+        g.close()
+
+
 def _full_size_run(config, hp_jobs):
     """A configuration at the job count it is specified with, at its nominal periods: the trace replays through the
     oracle, no HP job misses its deadline, fewer than 2 % of the LP jobs do, none is rejected, and the logits of every
