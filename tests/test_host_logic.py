@@ -573,3 +573,31 @@ def test_timeout_setter_validates():
         D.daris_set_timeout(0)
     assert e.value.code == D.EINVAL
     D.daris_set_timeout(20_000_000_000)
+
+
+def test_bench_roofline_helpers():
+    """`bench.py`'s pure helpers: every convolution kernel family is priced against the MFMA peak of its arithmetic type, the
+    memory-bound kernels against HBM, and the committed traffic summaries carry a figure for every dominant-kernel candidate."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    for i in range(1, 64):
+        name = D.daris_kernel_name(i)
+        if name == "?":
+            break
+        r = bench.kernel_roofline(name, 10, 0.1, 2.0e9)               # 10 launches, 0.1 ms, 2 GFLOP
+        if name.startswith("conv_wave"):
+            peak = 2500.0 if "_bf16_" in name else 157.3
+            assert r["bound"] == "mfma" and r["peak"] == peak and r["unit"] == "TFLOP/s", name
+            assert r["achieved"] == 20.0 and r["frac"] == round(20.0 / peak, 5) and r["avg_launch_us"] == 10.0, (name, r)
+        else:
+            assert r["bound"] == "hbm" and r["peak"] == 8000.0 and r["achieved"] is None, name
+    assert i > 30
+    for config, kernels in ((4, ("conv_wave_f32_t2w8", "conv_wave_f32_t1w8", "fc")), (3, ("conv_wave_bf16_t2w4", "conv_wave16_bf16_t2w4")),
+                            (2, ("conv_wave16_f32_t1w8", "conv_wave_f32_t2w8"))):
+        for k in kernels:
+            t = bench.read_traffic(config, k)
+            assert isinstance(t, int) and t > 10_000, (config, k, t)
+    assert bench.read_traffic(4, "no_such_kernel") is None
+    assert set(bench.WORKLOADS) == {2, 3, 4} and bench.JOBS_PER_TASK_PER_STEP == 32
