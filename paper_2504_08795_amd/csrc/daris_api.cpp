@@ -1010,6 +1010,27 @@ daris_status daris_split_stages(daris_task t, int k) {
   if (k < 1) return fail(DARIS_EINVAL, "k must be >= 1");
   if (k > 255) return fail(DARIS_ERANGE, "k must be <= 255");
   if (!split_stages(&net, k)) return fail(DARIS_ERANGE, "k = %d exceeds the %zu legal cut points + 1", k, net.legal_cuts.size());
+  // A depthwise layer is computed inside the next layer's launch only while both lie in one stage: a cut between them makes
+  // the depthwise layer's output the tensor that crosses the boundary (and a stage of that layer alone would have no launch).
+  bool refused = false;
+  for (size_t l = 0; l + 1 < net.layers.size(); ++l) {
+    LayerPlan& A = net.layers[l];
+    LayerPlan& B = net.layers[l + 1];
+    if (!A.fusable_dw || !A.depthwise) continue;
+    const bool cut = std::find(net.stage_first.begin(), net.stage_first.end(), (int)l + 1) != net.stage_first.end();
+    if (A.fused_dw == !cut) continue;
+    A.fused_dw = B.fused_dw = !cut;
+    A.pair_with = cut ? -1 : (int)l + 1;
+    B.pair_with = cut ? -1 : (int)l;
+    B.pair_lead = !cut;
+    refused = true;
+  }
+  if (refused && !G->nodev) {
+    TaskRt& T = *G->tasks[t];
+    T.static_launches.clear();
+    const std::string err = build_launches(T);
+    if (!err.empty()) return fail(DARIS_EHIP, "%s", err.c_str());
+  }
   G->core.set_stage_count(t, k);
   G->tasks[t]->vt.clear();
   return DARIS_OK;

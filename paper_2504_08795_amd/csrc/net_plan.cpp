@@ -151,6 +151,7 @@ std::string build_plan(const daris_dnn& dnn, bool keep_activations, bool pair_la
     B.pair_with = l;
     B.pair_lead = true;
     A.fused_dw = B.fused_dw = true;
+    A.fusable_dw = B.fusable_dw = true;
     ++l;
   }
   // Layer 0 can gather straight from the caller's input when that is its only reader and one filter tap is exactly

@@ -32,6 +32,7 @@ struct LayerPlan {
   // convolution's launch and never stored: the two layers are linked like a launch pair (the depthwise layer issues
   // nothing, the 1x1 convolution leads) and both carry this mark.
   bool fused_dw = false;
+  bool fusable_dw = false;  // the plan allows it; fused_dw is switched off while a stage cut separates the two layers
   int32_t kernel_id = K_NONE;
   void* w_dev = nullptr;
   float* b_dev = nullptr;

@@ -63,6 +63,28 @@ def test_plans_balanced_for_another_partition_size(net, dtype, plan_cus):
     assert e_max <= TOL[dtype] and e_l2 <= TOL[dtype], (e_max, e_l2)
 
 
+def test_every_legal_cut_in_use():
+    """MobileNetV2 with as many stages as the cut rule allows: stages of a single layer, among them depthwise layers that are
+    otherwise computed inside the following convolution's launch.  Same logits, bit for bit, as with one stage."""
+    from oracle import staging
+    layers, shp = wl.build_net("mobilenet_v2")
+    weights = wl.make_weights(layers, 17)
+    x = wl.make_inputs(shp, 17, 1, "normal")[0]
+    k = len(staging.legal_cuts(layers)) + 1
+    with GpuNet(layers, weights, shp, "fp32", k=1) as g:
+        one = g.forward(x)
+    with GpuNet(layers, weights, shp, "fp32", k=k) as g:
+        many = g.forward(x)
+        assert len(D.daris_get_stage_cuts(g.task)) == k
+        D.daris_calibrate_afet(g.task, g.parts[0], 1)            # runs stage by stage: every stage must have something to launch
+        D.daris_split_stages(g.task, 2)
+        two = g.forward(x)
+    np.testing.assert_array_equal(one, many)
+    np.testing.assert_array_equal(one, two)
+    e_max, e_l2 = rel_err(one, oracle_logits(layers, weights, x, "fp32"))
+    assert e_max <= TOL["fp32"] and e_l2 <= TOL["fp32"]
+
+
 @pytest.mark.parametrize("net,dtype", [("resnet18", "fp32"), ("resnet50", "bf16"), ("mobilenet_v2", "fp32"), ("mobilenet_v2", "bf16")])
 def test_plain_launch_shapes_agree_with_the_fused_ones(net, dtype):
     """The launch-count optimisations -- a residual block's shortcut and first convolution in one launch, the input layout

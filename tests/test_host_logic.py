@@ -252,6 +252,31 @@ def test_launch_plans_for_other_partition_sizes(plan_cus):
         assert layers[2].name == "l1b0.c1" and pl["tn"] == 1 and pl["MT"] * pl["NTn"] == 196 and pl["splitk"] == 1
 
 
+def test_fused_depthwise_follows_the_stage_split():
+    """A depthwise layer computed inside the next layer's launch is taken out of it while a stage cut separates the two (else
+    a stage could consist of that layer alone and launch nothing), and put back when the cut goes away."""
+    layers, shp = wl.build_net("mobilenet_v2")
+    legal = staging.legal_cuts(layers)
+    with Session(HOST):
+        D.daris_create_partition(128)
+        dnn, keep = D.make_dnn(layers, None, shp, "fp32")
+        t = D.daris_register_task(dnn, 10**7, 10**7, D.LP)
+        fused = lambda: [l for l in range(len(layers)) if D.daris_get_launch_plan(t, l)["pair_with"] == l + 1]      # noqa: E731
+        at_first = fused()
+        assert len(at_first) == 3 and all(layers[l].groups > 1 for l in at_first)
+        cuttable = [l for l in at_first if l in legal]                # (inside a block with a shortcut no cut is legal)
+        assert len(cuttable) == 2
+        D.daris_split_stages(t, len(legal) + 1)                        # with every legal cut in use, only the uncuttable one stays fused
+        assert D.daris_get_stage_cuts(t) == [0] + [c + 1 for c in legal]
+        assert fused() == [l for l in at_first if l not in legal]
+        for l in cuttable:
+            assert D.daris_get_launch_plan(t, l + 1)["pair_with"] == -1
+        D.daris_split_stages(t, 3)
+        assert fused() == at_first
+        D.daris_split_stages(t, 1)
+        assert fused() == at_first
+
+
 def test_launch_plans_of_odd_shapes():
     rng = np.random.default_rng(5)
     N = wl.nets
